@@ -1,0 +1,140 @@
+/*
+ * bitlinear.h - C-ABI of the BitLinear W1.58A8 hot path for AMD MI355X (gfx950).
+ *
+ * The operation is the BitLinear layer of BitNet b1.58 (technical report,
+ * Section 2 "Architecture": absmean ternary weights, per-token absmax int8
+ * activations; Section 5.1 "GPU Inference": four ternary values stored per
+ * 8-bit integer, unpacked just before the integer matrix product).
+ *
+ * The report gives these steps in words only.  The arithmetic below is the
+ * reading this library fixes; every fp32 step is ONE IEEE-754 binary32
+ * round-to-nearest-even operation, in the order written, with no fused
+ * multiply-add contraction.
+ *
+ *   weight scale   beta = fp32( (sum_{n,k} |W[n][k]|) / (N*K) )      (sum and
+ *                  division carried in fp64, one final rounding to fp32)
+ *   ternarize      d = beta + 1e-5f ; t = rint(W[n][k] / d) (ties to even);
+ *                  Wt[n][k] = clamp(t, -1, +1)  in {-1, 0, +1}
+ *   code           c = Wt + 1  in {0, 1, 2}        (3 is never produced)
+ *   activation     x~ = fp32(bf16 X[m][k]) ; gamma = max_k |x~| ;
+ *   quantizer      g = max(gamma, 1e-5f) ; inv = 127.0f / g ;
+ *                  q[m][k] = clamp(rint(x~ * inv), -127, 127)  (ties to even);
+ *                  scale[m] = g / 127.0f ; rowsum[m] = sum_k q[m][k]  (int32)
+ *   contraction    acc[m][n] = sum_k q[m][k] * Wt[n][k]      (exact, int32)
+ *   rescale        y[m][n] = (float)acc[m][n] * (beta * scale[m])
+ *
+ * PACKED LAYOUTS.  A packed matrix is N*K/4 bytes, 2 bits per weight.
+ *   BL_LAYOUT_ROWMAJOR (0): byte index b = n*(K/4) + k/4 ; weight k occupies
+ *     bits [2*(k%4), 2*(k%4)+1] of byte b (lowest bits = lowest k).
+ *   BL_LAYOUT_TILE16 (1): a pure permutation of the row-major bytes in units
+ *     of 16 bytes (64 consecutive k of one row).  Rows are grouped in bands of
+ *     16, k in slices of 64:  the 16-byte unit of row n, slice s=k/64 sits at
+ *     unit index  (n/16)*(16*K/64) + s*16 + (n%16) ; inside the unit the bytes
+ *     keep their row-major order and bit order.  Requires N % 16 == 0.
+ *
+ * CONVENTIONS.  Every pointer is a DEVICE pointer owned by the caller unless a
+ * comment says "host".  The library allocates and frees nothing; all work is
+ * enqueued on the caller's stream `s` (a hipStream_t passed as void*; NULL is
+ * the null stream) and no call synchronises.  Argument errors are found on the
+ * host before any HIP call and reported as a status code (no exceptions, no
+ * global error state).  Preconditions on every matrix: N >= 4, N % 4 == 0,
+ * K >= 64, K % 64 == 0; `packed` and `q` 16-byte aligned; otherwise
+ * BL_ERR_SHAPE / BL_ERR_ALIGN.  Non-finite activations or weights: undefined.
+ * There is no bias argument (the report removes all biases, Section 2).
+ */
+#ifndef BITLINEAR_H
+#define BITLINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BL_OK            = 0,
+    BL_ERR_NULL      = 1,  /* a required pointer is NULL                        */
+    BL_ERR_SHAPE     = 2,  /* M/N/K out of range or not a permitted multiple    */
+    BL_ERR_LAYOUT    = 3,  /* unknown layout id / layout not valid for shape    */
+    BL_ERR_ALIGN     = 4,  /* pointer not aligned as required                   */
+    BL_ERR_VALUE     = 5,  /* unknown in_kind / op id                           */
+    BL_ERR_HIP       = 6,  /* a HIP runtime call or kernel launch failed        */
+    BL_ERR_WORKSPACE = 7   /* workspace required but NULL                       */
+} bl_status;
+
+typedef void* bl_stream;   /* hipStream_t */
+
+enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_TILE16 = 1 };
+enum { BL_IN_FP32_LATENT = 0, BL_IN_INT8_TERNARY = 1 };
+enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3,
+       BL_OP_FUSED_DECODE = 4, BL_OP_FFN_GLUE = 5 };
+
+/* Library version (major*10000 + minor*100 + patch) and a static string
+ * naming a status code.  Host-only, no GPU needed. */
+int         bl_version(void);
+const char* bl_status_str(int status);
+
+/* Bytes of a packed N x K matrix (N*K/4 for every layout); 0 if the shape or
+ * layout is not permitted.  Host-only.  (Section 5.1: 4 values per byte.) */
+size_t bl_packed_bytes(int64_t N, int64_t K, int layout);
+
+/* Bytes of device scratch the given op needs for the given shape (may be 0).
+ * The workspace is caller-allocated, 256-byte aligned, and may be reused by
+ * later calls on the same stream.  Host-only. */
+size_t bl_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
+
+/* Weight quantisation and packing (Section 2, "Weight Quantization": absmean
+ * to ternary; Section 5.1: packing).  Offline step, not on the timed path.
+ *   W        device, in_kind 0: fp32 [N][K] row-major latent weights (beta is
+ *            computed and written); in_kind 1: int8 [N][K] values in {-1,0,1}
+ *            (beta is read, not written).
+ *   packed   device out, bl_packed_bytes(N,K,layout) bytes.
+ *   beta     device, 1 float.
+ *   workspace device, bl_workspace_bytes(BL_OP_PACK, 0, N, K) bytes.
+ * Enqueues three kernels (partial |W| sums in fp64, fixed-order final sum,
+ * ternarize+pack).  The fp64 sum order is fixed, so beta is reproducible. */
+bl_status bl_pack_ternary(const void* W, int in_kind, int64_t N, int64_t K, int layout,
+                          uint8_t* packed, float* beta, void* workspace, bl_stream s);
+
+/* Inverse of the packing, for round-trip tests: writes Wt int8 [N][K] row-major
+ * in {-1,0,1} and sets *bad (device int32, zeroed by this call) to the number
+ * of 2-bit fields holding the invalid code 3 (those decode to +2). */
+bl_status bl_unpack_ternary(const uint8_t* packed, int64_t N, int64_t K, int layout,
+                            int8_t* Wt, int32_t* bad, bl_stream s);
+
+/* Per-token absmax int8 activation quantisation (Section 2, "Activation
+ * Quantization").
+ *   X      device bf16 [M][K] row-major (raw 16-bit patterns).
+ *   q      device out int8 [M][K];  scale device out fp32 [M] (= max(gamma,1e-5)/127);
+ *   rowsum device out int32 [M], may be NULL.          M >= 1. */
+bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K,
+                            int8_t* q, float* scale, int32_t* rowsum, bl_stream s);
+
+/* W1.58A8 product for decode batches, 1 <= M <= 64 (Section 5.1).  Streams the
+ * packed weights once per call.
+ *   packed/beta/layout  as written by bl_pack_ternary.
+ *   q      device int8 [M][K];  scale device fp32 [M] (needed only if y != NULL).
+ *   rowsum device int32 [M] or NULL (this call derives what it needs from q).
+ *   acc    device out int32 [M][N] or NULL;  y device out fp32 [M][N] or NULL;
+ *          at least one of the two must be non-NULL.
+ *   workspace unused by the current kernels (may be NULL). */
+bl_status bl_gemv_w158a8(const uint8_t* packed, const float* beta, int layout,
+                         const int8_t* q, const float* scale, const int32_t* rowsum,
+                         int64_t M, int64_t N, int64_t K,
+                         int32_t* acc, float* y, void* workspace, bl_stream s);
+
+/* W1.58A8 product for prefill, any M >= 1 (Section 5.1): packed tiles are
+ * unpacked to int8 on chip and contracted on the int8 matrix cores.  Same
+ * arguments as bl_gemv_w158a8.  If rowsum is NULL the call computes the row
+ * sums itself into `workspace` (bl_workspace_bytes(BL_OP_GEMM, M, N, K) bytes,
+ * then required). */
+bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout,
+                         const int8_t* q, const float* scale, const int32_t* rowsum,
+                         int64_t M, int64_t N, int64_t K,
+                         int32_t* acc, float* y, void* workspace, bl_stream s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITLINEAR_H */

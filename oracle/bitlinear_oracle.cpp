@@ -1,0 +1,263 @@
+/*
+ * CPU ORACLE for the BitLinear W1.58A8 layer.  TEST INFRASTRUCTURE ONLY: a
+ * plain, slow, obviously-correct statement of what the layer computes, used by
+ * tests/, by the smoke check and by the benchmark's cpu_baseline leg.  It shares
+ * no code with the GPU library and the GPU library never calls it.
+ *
+ * Source: BitNet b1.58 2B4T technical report.  Section 2 ("Architecture") states
+ * the two quantisers in words only: weights -> {-1,0,+1} by an absolute-mean
+ * scheme, activations -> 8-bit integers by per-token absolute-maximum.  Section
+ * 5.1 ("GPU Inference") states the storage format (four ternary values in one
+ * 8-bit integer) and that the product is taken between the unpacked ternary
+ * weights and the 8-bit activations.  The report prints no formula; the
+ * formulas below are the benchmark definition this repository is bound to
+ * (beta = mean|W|, Wt = clip(round(W/(beta+1e-5)),-1,1), Q = 127, int32
+ * accumulate, y = acc * beta * absmax / 127) with round = ties-to-even.
+ *
+ * Every fp32 step is a single IEEE binary32 operation in the order written
+ * (compile with -ffp-contract=off, no fast-math).  Loops are the definitions
+ * written out: no blocking, no packing tricks, no offset codes.  OpenMP, where
+ * present, splits independent output rows only and cannot change a result.
+ *
+ * Pins (tests/test_oracle_*.py): exhaustive 81-tuple pack table, hand-made tie
+ * cases, closed-form Gaussian statistics, exact int64 library matmul, fp64
+ * brute force of the dequantised product, one-hot / all-ones special cases.
+ * Unpinned: the synthetic 30-layer chain glue (orc_chain_* below) is a
+ * construction of this repository, not of the report: "parity unpinned"
+ * against anything external; it is pinned only through its parts.
+ */
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+extern "C" {
+
+/* ---- Section 2, weight quantisation: the absmean scale -------------------
+ * beta = mean |W| over the whole matrix.  The sum is carried in fp64 with
+ * Neumaier compensation in plain row-major order, divided in fp64, and rounded
+ * once to fp32.  *mean64 receives the fp64 mean so a test can assert that it is
+ * not within a hair of an fp32 rounding midpoint. */
+float orc_absmean_beta(const float* W, int64_t N, int64_t K, double* mean64) {
+    double sum = 0.0, comp = 0.0;
+    const int64_t n = N * K;
+    for (int64_t i = 0; i < n; ++i) {
+        const double a = std::fabs((double)W[i]);
+        const double t = sum + a;
+        if (std::fabs(sum) >= a) comp += (sum - t) + a;
+        else                     comp += (a - t) + sum;
+        sum = t;
+    }
+    const double mean = (sum + comp) / (double)n;
+    if (mean64) *mean64 = mean;
+    return (float)mean;
+}
+
+/* ---- Section 2, weight quantisation: ternarisation ------------------------
+ * Wt = clip(round(W / (beta + 1e-5)), -1, +1), round = nearest, ties to even
+ * (nearbyintf under the default rounding mode). */
+void orc_ternarize(const float* W, int64_t N, int64_t K, float beta, int8_t* Wt) {
+    const float d = beta + 1e-5f;
+    for (int64_t i = 0; i < N * K; ++i) {
+        const float r = W[i] / d;
+        float t = std::nearbyintf(r);
+        if (t > 1.0f) t = 1.0f;
+        if (t < -1.0f) t = -1.0f;
+        Wt[i] = (int8_t)t;
+    }
+}
+
+/* Position of weight (n,k) in a packed buffer: byte index and bit shift.
+ * Layout 0 (row-major): byte n*(K/4)+k/4, bits 2*(k%4).
+ * Layout 1 (16-row bands of 16-byte units): the 16-byte unit holding k-slice
+ * s = k/64 of row n is unit number (n/16)*(16*(K/64)) + s*16 + n%16.
+ * Returns 0 on an unknown layout. */
+static int packed_position(int layout, int64_t N, int64_t K, int64_t n, int64_t k,
+                           int64_t* byte, int* shift) {
+    (void)N;
+    *shift = 2 * (int)(k % 4);
+    if (layout == 0) {
+        *byte = n * (K / 4) + k / 4;
+        return 1;
+    }
+    if (layout == 1) {
+        const int64_t slices = K / 64;
+        const int64_t unit = (n / 16) * (16 * slices) + (k / 64) * 16 + (n % 16);
+        *byte = unit * 16 + (k % 64) / 4;
+        return 1;
+    }
+    return 0;
+}
+
+/* ---- Section 5.1, storage: four ternary values per byte -------------------
+ * code = Wt + 1 in {0,1,2}; two bits per weight.  Returns 0 on success,
+ * 1 if some Wt is outside {-1,0,1}, 2 on an unknown layout. */
+int orc_pack(const int8_t* Wt, int64_t N, int64_t K, int layout, uint8_t* packed) {
+    std::memset(packed, 0, (size_t)(N * K / 4));
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const int v = Wt[n * K + k];
+            if (v < -1 || v > 1) return 1;
+            int64_t b; int sh;
+            if (!packed_position(layout, N, K, n, k, &b, &sh)) return 2;
+            packed[b] = (uint8_t)(packed[b] | ((v + 1) << sh));
+        }
+    return 0;
+}
+
+/* Inverse of orc_pack.  Returns the number of fields holding the invalid code
+ * 3 (those are written as +2), or -1 on an unknown layout. */
+int64_t orc_unpack(const uint8_t* packed, int64_t N, int64_t K, int layout, int8_t* Wt) {
+    int64_t bad = 0;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t b; int sh;
+            if (!packed_position(layout, N, K, n, k, &b, &sh)) return -1;
+            const int c = (packed[b] >> sh) & 3;
+            if (c == 3) ++bad;
+            Wt[n * K + k] = (int8_t)(c - 1);
+        }
+    return bad;
+}
+
+static inline float bf16_bits_to_f32(uint16_t h) {
+    const uint32_t u = (uint32_t)h << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+/* fp32 -> bf16 bits, round to nearest, ties to even (finite inputs). */
+static inline uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    const uint32_t lower = u & 0xFFFFu;
+    uint32_t upper = u >> 16;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) upper += 1;
+    return (uint16_t)upper;
+}
+
+/* ---- Section 2, activation quantisation: per-token absmax to int8 ---------
+ * For each token row: gamma = max|x|, g = max(gamma, 1e-5), inv = 127/g,
+ * q = clip(round(x*inv), -127, 127), scale = g/127, rowsum = sum q. */
+void orc_quant_act(const uint16_t* X, int64_t M, int64_t K, int8_t* q, float* scale,
+                   int32_t* rowsum) {
+    for (int64_t m = 0; m < M; ++m) {
+        float gamma = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            const float a = std::fabs(bf16_bits_to_f32(X[m * K + k]));
+            if (a > gamma) gamma = a;
+        }
+        const float g = gamma > 1e-5f ? gamma : 1e-5f;
+        const float inv = 127.0f / g;
+        int32_t sum = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            const float p = bf16_bits_to_f32(X[m * K + k]) * inv;
+            float r = std::nearbyintf(p);
+            if (r > 127.0f) r = 127.0f;
+            if (r < -127.0f) r = -127.0f;
+            q[m * K + k] = (int8_t)r;
+            sum += (int32_t)r;
+        }
+        scale[m] = g / 127.0f;
+        if (rowsum) rowsum[m] = sum;
+    }
+}
+
+/* ---- Section 5.1, the W1.58A8 product --------------------------------------
+ * acc[m][n] = sum_k q[m][k] * Wt[n][k], int32, on the UNPACKED ternary matrix. */
+void orc_matmul_i32(const int8_t* q, const int8_t* Wt, int64_t M, int64_t N, int64_t K,
+                    int32_t* acc) {
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            int32_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += (int32_t)q[m * K + k] * (int32_t)Wt[n * K + k];
+            acc[m * N + n] = s;
+        }
+}
+
+/* Single output elements of the same product, for sampled checks at sizes where
+ * the full product is too slow: out[i] = acc[ms[i]][ns[i]]. */
+void orc_matmul_i32_sampled(const int8_t* q, const int8_t* Wt, int64_t N, int64_t K,
+                            const int64_t* ms, const int64_t* ns, int64_t count, int32_t* out) {
+    (void)N;
+    for (int64_t i = 0; i < count; ++i) {
+        int32_t s = 0;
+        for (int64_t k = 0; k < K; ++k)
+            s += (int32_t)q[ms[i] * K + k] * (int32_t)Wt[ns[i] * K + k];
+        out[i] = s;
+    }
+}
+
+/* ---- rescale: y = acc * beta * absmax / 127 ---------------------------------
+ * c = beta * scale[m] (one fp32 multiply), y = (float)acc * c (one multiply). */
+void orc_rescale(const int32_t* acc, float beta, const float* scale, int64_t M, int64_t N,
+                 float* y) {
+    for (int64_t m = 0; m < M; ++m) {
+        const float c = beta * scale[m];
+        for (int64_t n = 0; n < N; ++n)
+            y[m * N + n] = (float)acc[m * N + n] * c;
+    }
+}
+
+/* ---- synthetic chain glue (a construction of this repository; unpinned) -----
+ * One token-independent "layer" around the four BitLinear products, made only
+ * of order-free, elementwise-exact steps so that integer parity survives a
+ * 30-layer chain.  The report's real glue (sub-layer norm, rotary embedding,
+ * attention; Section 2) needs trained gains and float reductions and is
+ * outside this path.  ReLU^2 in the FFN is the report's (Section 2).
+ * Each BitLinear input is narrowed to bf16 and quantised by orc_quant_act; the
+ * caller passes scale = 1/127 to orc_rescale (norm stand-in: the layer acts on
+ * x / absmax).  The residual stream stays fp32.
+ */
+
+/* fp32 tensor -> bf16 bit patterns (round to nearest even). */
+void orc_f32_to_bf16(const float* x, int64_t n, uint16_t* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16_bits(x[i]);
+}
+
+/* Context-length-1 attention: the attention output of head h is the value
+ * vector of its key/value group.  qkv row = [Q: n_q*hd | K: n_kv*hd | V: n_kv*hd].
+ * a[m][h*hd+d] = bf16(qkv[m][(n_q+n_kv)*hd + (h/(n_q/n_kv))*hd + d]). */
+void orc_chain_attn_stub(const float* qkv, int64_t M, int n_q, int n_kv, int hd, uint16_t* a) {
+    const int64_t row = (int64_t)(n_q + 2 * n_kv) * hd;
+    const int group = n_q / n_kv;
+    for (int64_t m = 0; m < M; ++m)
+        for (int h = 0; h < n_q; ++h)
+            for (int d = 0; d < hd; ++d) {
+                const float v = qkv[m * row + (int64_t)(n_q + n_kv) * hd + (int64_t)(h / group) * hd + d];
+                a[m * (int64_t)n_q * hd + (int64_t)h * hd + d] = f32_to_bf16_bits(v);
+            }
+}
+
+/* h = x + y, one fp32 add per element. */
+void orc_chain_residual(const float* x, const float* y, int64_t n, float* h) {
+    for (int64_t i = 0; i < n; ++i) h[i] = x[i] + y[i];
+}
+
+/* f = bf16( (relu(g)*relu(g)) * u ), gu row = [g: F | u: F]  (ReLU^2 gated FFN). */
+void orc_chain_relu2_gate(const float* gu, int64_t M, int64_t F, uint16_t* f) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < F; ++j) {
+            const float g = gu[m * 2 * F + j];
+            const float u = gu[m * 2 * F + F + j];
+            const float r = g > 0.0f ? g : 0.0f;
+            const float r2 = r * r;
+            const float p = r2 * u;
+            f[m * F + j] = f32_to_bf16_bits(p);
+        }
+}
+
+int orc_omp_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+}  /* extern "C" */
