@@ -26,11 +26,12 @@
  * PACKED LAYOUTS.  A packed matrix is N*K/4 bytes, 2 bits per weight.
  *   BL_LAYOUT_ROWMAJOR (0): byte index b = n*(K/4) + k/4 ; weight k occupies
  *     bits [2*(k%4), 2*(k%4)+1] of byte b (lowest bits = lowest k).
- *   BL_LAYOUT_TILE16 (1): a pure permutation of the row-major bytes in units
- *     of 16 bytes (64 consecutive k of one row).  Rows are grouped in bands of
- *     16, k in slices of 64:  the 16-byte unit of row n, slice s=k/64 sits at
- *     unit index  (n/16)*(16*K/64) + s*16 + (n%16) ; inside the unit the bytes
- *     keep their row-major order and bit order.  Requires N % 16 == 0.
+ *   BL_LAYOUT_K16 (1): same byte count and the same 4-byte word per group of
+ *     16 consecutive k of a row, but inside the word the two index digits are
+ *     swapped: with i = k % 16, weight k occupies bits [2*(i/4), 2*(i/4)+1] of
+ *     byte n*(K/4) + (k/16)*4 + i%4.  (So `(word >> 2s) & 0x03030303` yields the
+ *     codes of k = 4s..4s+3 as four bytes in natural order: the kernels' native
+ *     form.  Layout 0 is supported by permuting the activation bytes instead.)
  *
  * CONVENTIONS.  Every pointer is a DEVICE pointer owned by the caller unless a
  * comment says "host".  The library allocates and frees nothing; all work is
@@ -65,7 +66,7 @@ typedef enum {
 
 typedef void* bl_stream;   /* hipStream_t */
 
-enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_TILE16 = 1 };
+enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_K16 = 1 };
 enum { BL_IN_FP32_LATENT = 0, BL_IN_INT8_TERNARY = 1 };
 enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3,
        BL_OP_FUSED_DECODE = 4, BL_OP_FFN_GLUE = 5 };

@@ -71,21 +71,21 @@ void orc_ternarize(const float* W, int64_t N, int64_t K, float beta, int8_t* Wt)
 
 /* Position of weight (n,k) in a packed buffer: byte index and bit shift.
  * Layout 0 (row-major): byte n*(K/4)+k/4, bits 2*(k%4).
- * Layout 1 (16-row bands of 16-byte units): the 16-byte unit holding k-slice
- * s = k/64 of row n is unit number (n/16)*(16*(K/64)) + s*16 + n%16.
+ * Layout 1 (digits swapped inside each group of 16 k): with i = k%16, byte
+ * n*(K/4) + (k/16)*4 + i%4, bits 2*(i/4).
  * Returns 0 on an unknown layout. */
 static int packed_position(int layout, int64_t N, int64_t K, int64_t n, int64_t k,
                            int64_t* byte, int* shift) {
     (void)N;
-    *shift = 2 * (int)(k % 4);
     if (layout == 0) {
         *byte = n * (K / 4) + k / 4;
+        *shift = 2 * (int)(k % 4);
         return 1;
     }
     if (layout == 1) {
-        const int64_t slices = K / 64;
-        const int64_t unit = (n / 16) * (16 * slices) + (k / 64) * 16 + (n % 16);
-        *byte = unit * 16 + (k % 64) / 4;
+        const int64_t i = k % 16;
+        *byte = n * (K / 4) + (k / 16) * 4 + i % 4;
+        *shift = 2 * (int)(i / 4);
         return 1;
     }
     return 0;

@@ -1,0 +1,167 @@
+"""ctypes binding of the BitLinear C-ABI (include/bitlinear.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libbitlinear_hip.so.  PyTorch supplies device memory and the current stream.
+There is no CPU fallback: if the library is missing, load() raises.
+"""
+import ctypes
+import os
+
+from . import build as _build
+
+BL_OK = 0
+BL_LAYOUT_ROWMAJOR, BL_LAYOUT_K16 = 0, 1
+BL_IN_FP32_LATENT, BL_IN_INT8_TERNARY = 0, 1
+BL_OP_PACK, BL_OP_QUANT, BL_OP_GEMV, BL_OP_GEMM = 0, 1, 2, 3
+
+_i64, _vp, _ci, _sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+
+# name -> (restype, argtypes); mirrors include/bitlinear.h one to one
+SIGNATURES = {
+    "bl_version": (_ci, []),
+    "bl_status_str": (ctypes.c_char_p, [_ci]),
+    "bl_packed_bytes": (_sz, [_i64, _i64, _ci]),
+    "bl_workspace_bytes": (_sz, [_ci, _i64, _i64, _i64]),
+    "bl_pack_ternary": (_ci, [_vp, _ci, _i64, _i64, _ci, _vp, _vp, _vp, _vp]),
+    "bl_unpack_ternary": (_ci, [_vp, _i64, _i64, _ci, _vp, _vp, _vp]),
+    "bl_quant_act_int8": (_ci, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "bl_gemv_w158a8": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "bl_gemm_w158a8": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
+}
+
+
+class BitLinearError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s failed: %s" % (where, status_str(status)))
+
+
+_lib = None
+
+
+def load():
+    """Load the built library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB_PATH):
+            raise RuntimeError("libbitlinear_hip.so is not built (run __graft_entry__.build()); "
+                               "this package has no fallback path")
+        lib = ctypes.CDLL(_build.LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def status_str(status):
+    return load().bl_status_str(int(status)).decode()
+
+
+def _check(status, where):
+    if status != BL_OK:
+        raise BitLinearError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def bl_version():
+    return load().bl_version()
+
+
+def bl_packed_bytes(N, K, layout=BL_LAYOUT_K16):
+    return load().bl_packed_bytes(N, K, layout)
+
+
+def bl_workspace_bytes(op, M, N, K):
+    return load().bl_workspace_bytes(op, M, N, K)
+
+
+def _workspace(nbytes, device):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def bl_pack_ternary(W, layout=BL_LAYOUT_K16, beta=None):
+    """W: cuda fp32 [N][K] latent weights, or cuda int8 ternary with `beta` given.
+    Returns (packed uint8 [N*K/4], beta fp32 [1])."""
+    import torch
+    N, K = W.shape
+    assert W.is_cuda and W.is_contiguous()
+    nbytes = bl_packed_bytes(N, K, layout)
+    if nbytes == 0:
+        raise BitLinearError(2 if layout in (0, 1) else 3, "bl_packed_bytes")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    if W.dtype == torch.float32:
+        kind = BL_IN_FP32_LATENT
+        beta_t = torch.empty(1, dtype=torch.float32, device=W.device)
+    elif W.dtype == torch.int8:
+        kind = BL_IN_INT8_TERNARY
+        beta_t = torch.as_tensor([float(beta)], dtype=torch.float32, device=W.device) \
+            if not isinstance(beta, torch.Tensor) else beta
+    else:
+        raise TypeError("W must be float32 or int8")
+    ws = _workspace(bl_workspace_bytes(BL_OP_PACK, 0, N, K), W.device)
+    _check(load().bl_pack_ternary(_ptr(W), kind, N, K, layout, _ptr(packed), _ptr(beta_t), _ptr(ws), _stream()),
+           "bl_pack_ternary")
+    return packed, beta_t
+
+
+def bl_unpack_ternary(packed, N, K, layout=BL_LAYOUT_K16):
+    """Returns (Wt int8 [N][K], bad int32 [1])."""
+    import torch
+    Wt = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    bad = torch.empty(1, dtype=torch.int32, device=packed.device)
+    _check(load().bl_unpack_ternary(_ptr(packed), N, K, layout, _ptr(Wt), _ptr(bad), _stream()),
+           "bl_unpack_ternary")
+    return Wt, bad
+
+
+def bl_quant_act_int8(X, want_rowsum=True):
+    """X: cuda bfloat16 [M][K].  Returns (q int8 [M][K], scale fp32 [M], rowsum int32 [M] or None)."""
+    import torch
+    assert X.is_cuda and X.is_contiguous() and X.dtype == torch.bfloat16
+    M, K = X.shape
+    q = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    scale = torch.empty(M, dtype=torch.float32, device=X.device)
+    rowsum = torch.empty(M, dtype=torch.int32, device=X.device) if want_rowsum else None
+    _check(load().bl_quant_act_int8(_ptr(X), M, K, _ptr(q), _ptr(scale), _ptr(rowsum), _stream()),
+           "bl_quant_act_int8")
+    return q, scale, rowsum
+
+
+def _matmul(fn_name, op, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y, acc, y, workspace):
+    import torch
+    M, K = q.shape
+    assert q.is_cuda and q.is_contiguous() and q.dtype == torch.int8
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=q.device)
+    if want_y and y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=q.device)
+    if workspace is None and rowsum is None:
+        workspace = _workspace(bl_workspace_bytes(op, M, N, K), q.device)
+    fn = getattr(load(), fn_name)
+    _check(fn(_ptr(packed), _ptr(beta), layout, _ptr(q), _ptr(scale), _ptr(rowsum), M, N, K,
+              _ptr(acc), _ptr(y), _ptr(workspace), _stream()), fn_name)
+    return acc, y
+
+
+def bl_gemv_w158a8(packed, beta, layout, q, scale, rowsum, N, want_acc=True, want_y=True,
+                   acc=None, y=None, workspace=None):
+    """Decode product, 1 <= M <= 64.  Returns (acc int32 [M][N] or None, y fp32 [M][N] or None)."""
+    return _matmul("bl_gemv_w158a8", BL_OP_GEMV, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y,
+                   acc, y, workspace)
+
+
+def bl_gemm_w158a8(packed, beta, layout, q, scale, rowsum, N, want_acc=True, want_y=True,
+                   acc=None, y=None, workspace=None):
+    """Prefill product, any M.  Returns (acc, y) like bl_gemv_w158a8."""
+    return _matmul("bl_gemm_w158a8", BL_OP_GEMM, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y,
+                   acc, y, workspace)

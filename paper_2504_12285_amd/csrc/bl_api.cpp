@@ -1,0 +1,35 @@
+/* Host-only entry points of the BitLinear library: sizes, names, version. */
+#include "bl_host.h"
+
+extern "C" int bl_version(void) { return 100; }
+
+extern "C" const char* bl_status_str(int status) {
+    switch (status) {
+        case BL_OK: return "BL_OK";
+        case BL_ERR_NULL: return "BL_ERR_NULL: a required pointer is NULL";
+        case BL_ERR_SHAPE: return "BL_ERR_SHAPE: M/N/K out of range or not a permitted multiple";
+        case BL_ERR_LAYOUT: return "BL_ERR_LAYOUT: unknown packed layout";
+        case BL_ERR_ALIGN: return "BL_ERR_ALIGN: pointer not aligned as required";
+        case BL_ERR_VALUE: return "BL_ERR_VALUE: unknown in_kind or op id";
+        case BL_ERR_HIP: return "BL_ERR_HIP: a HIP call or kernel launch failed";
+        case BL_ERR_WORKSPACE: return "BL_ERR_WORKSPACE: workspace required but NULL";
+        default: return "unknown bl_status";
+    }
+}
+
+extern "C" size_t bl_packed_bytes(int64_t N, int64_t K, int layout) {
+    if (!bl_shape_ok(N, K)) return 0;
+    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return 0;
+    return (size_t)(N * K / 4);
+}
+
+extern "C" size_t bl_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
+    (void)N;
+    (void)K;
+    switch (op) {
+        case BL_OP_PACK: return BL_PACK_PARTIALS * sizeof(double);
+        case BL_OP_GEMV:
+        case BL_OP_GEMM: return M > 0 ? (size_t)((M * 4 + 255) / 256 * 256) : 0;
+        default: return 0;
+    }
+}

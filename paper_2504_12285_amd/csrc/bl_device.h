@@ -1,0 +1,75 @@
+/* Internal device helpers shared by the HIP kernels of the BitLinear library
+ * (not part of the public boundary).  gfx950 only: 64-lane wavefronts. */
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bitlinear.h"
+
+typedef int bl_v4i __attribute__((ext_vector_type(4)));
+typedef int bl_v16i __attribute__((ext_vector_type(16)));
+
+#define BL_WAVE 64
+
+/* bf16 bit pattern -> fp32 (exact). */
+__device__ __forceinline__ float bl_bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+/* fp32 -> bf16 bit pattern, round to nearest even (finite inputs). */
+__device__ __forceinline__ uint32_t bl_f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+/* Correctly rounded fp32 quotient: the fp64 quotient of two fp32 values,
+ * rounded to fp32, equals the directly rounded fp32 quotient (53 >= 2*24+2). */
+__device__ __forceinline__ float bl_div_rn(float a, float b) { return (float)((double)a / (double)b); }
+
+/* DPP cross-lane moves inside a row of 16 lanes (old value = 0 for disabled lanes). */
+template <int CTRL>
+__device__ __forceinline__ int bl_dpp(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+#define BL_DPP_QUAD_XOR1 0xB1   /* quad_perm [1,0,3,2] */
+#define BL_DPP_QUAD_XOR2 0x4E   /* quad_perm [2,3,0,1] */
+#define BL_DPP_ROW_HALF_MIRROR 0x141
+#define BL_DPP_ROW_MIRROR 0x140
+
+/* Sum over aligned groups of G lanes (G = 4, 8 or 16), result in every lane of
+ * the group.  DPP only: quad butterflies, then half-row / row mirrors (after a
+ * quad sum all four lanes of a quad agree, so a mirror pairs distinct quads). */
+template <int G>
+__device__ __forceinline__ int bl_group_sum(int v) {
+    static_assert(G == 1 || G == 2 || G == 4 || G == 8 || G == 16, "group size");
+    if (G >= 2) v += bl_dpp<BL_DPP_QUAD_XOR1>(v);
+    if (G >= 4) v += bl_dpp<BL_DPP_QUAD_XOR2>(v);
+    if (G >= 8) v += bl_dpp<BL_DPP_ROW_HALF_MIRROR>(v);
+    if (G >= 16) v += bl_dpp<BL_DPP_ROW_MIRROR>(v);
+    return v;
+}
+
+/* Full-wave integer sum / float max via butterflies (ds_bpermute for the
+ * cross-row steps). */
+__device__ __forceinline__ int bl_wave_sum(int v) {
+    v = bl_group_sum<16>(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+__device__ __forceinline__ float bl_wave_max(float v) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+/* 4x4 byte transpose of four dwords: out[s].byte[b] = in[b].byte[s]. */
+__device__ __forceinline__ void bl_transpose4x4(uint32_t& a0, uint32_t& a1, uint32_t& a2, uint32_t& a3) {
+    const uint32_t t0 = __builtin_amdgcn_perm(a1, a0, 0x05010400u);
+    const uint32_t t1 = __builtin_amdgcn_perm(a1, a0, 0x07030602u);
+    const uint32_t t2 = __builtin_amdgcn_perm(a3, a2, 0x05010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
+    a0 = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    a1 = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    a2 = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+    a3 = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+}

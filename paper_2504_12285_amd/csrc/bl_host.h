@@ -1,0 +1,13 @@
+/* Internal host-side helpers: argument checks shared by the entry points. */
+#pragma once
+#include <stdint.h>
+
+#include "bitlinear.h"
+
+#define BL_PACK_PARTIALS 1024          /* fp64 partial sums used by bl_pack_ternary */
+#define BL_MAX_DIM ((int64_t)1 << 24)  /* upper bound on M, N and K                 */
+
+static inline bool bl_shape_ok(int64_t N, int64_t K) {
+    return N >= 4 && N % 4 == 0 && K >= 64 && K % 64 == 0 && N <= BL_MAX_DIM && K <= BL_MAX_DIM;
+}
+static inline bool bl_aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }

@@ -1,0 +1,172 @@
+/* Weight quantisation (absmean -> ternary, Section 2 of the BitNet b1.58 2B4T
+ * report) and 2-bit packing (Section 5.1), plus the inverse for round trips.
+ * Offline step: bandwidth-trivial, but every bit must match the definition in
+ * bitlinear.h. */
+#include "bl_device.h"
+#include "bl_host.h"
+
+#define PACK_THREADS 256
+
+/* Partial sums of |W| in fp64: block b sums a contiguous span of float4s in a
+ * fixed order (thread-strided, then a fixed LDS tree). */
+__global__ __launch_bounds__(PACK_THREADS) void bl_abs_sum_partial(const float4* __restrict__ W,
+                                                                    int64_t n4, double* __restrict__ partial) {
+    __shared__ double red[PACK_THREADS];
+    const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x;
+    const int64_t hi = lo + per < n4 ? lo + per : n4;
+    double s = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += PACK_THREADS) {
+        const float4 v = W[i];
+        s += (double)fabsf(v.x);
+        s += (double)fabsf(v.y);
+        s += (double)fabsf(v.z);
+        s += (double)fabsf(v.w);
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = PACK_THREADS / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+/* Fixed-order sum of the partials, mean in fp64, one rounding to fp32. */
+__global__ __launch_bounds__(PACK_THREADS) void bl_abs_sum_final(const double* __restrict__ partial, int np,
+                                                                  double count, float* __restrict__ beta) {
+    __shared__ double red[PACK_THREADS];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < np; i += PACK_THREADS) s += partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = PACK_THREADS / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *beta = (float)(red[0] / count);
+}
+
+/* Bit position of weight i (0..15) inside its 32-bit word. */
+template <int LAYOUT>
+__device__ __forceinline__ int bl_bitpos(int i) {
+    return LAYOUT == 0 ? 2 * i : 8 * (i & 3) + 2 * (i >> 2);
+}
+
+template <int LAYOUT>
+__device__ __forceinline__ uint32_t bl_code_word(const int* c) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w |= (uint32_t)c[i] << bl_bitpos<LAYOUT>(i);
+    return w;
+}
+
+/* One thread = 16 consecutive k of one row = one packed word. */
+template <int LAYOUT>
+__global__ __launch_bounds__(PACK_THREADS) void bl_ternarize_pack(const float4* __restrict__ W,
+                                                                   const float* __restrict__ beta, int64_t words,
+                                                                   uint32_t* __restrict__ packed) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const float d = *beta + 1e-5f;
+    int c[16];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float4 v = W[g * 4 + j];
+        const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float t = rintf(bl_div_rn(f[e], d));
+            t = fminf(fmaxf(t, -1.0f), 1.0f);
+            c[4 * j + e] = (int)t + 1;
+        }
+    }
+    packed[g] = bl_code_word<LAYOUT>(c);
+}
+
+/* Same packing for weights that are already ternary int8. */
+template <int LAYOUT>
+__global__ __launch_bounds__(PACK_THREADS) void bl_pack_int8(const bl_v4i* __restrict__ Wt, int64_t words,
+                                                              uint32_t* __restrict__ packed) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const bl_v4i v = Wt[g];
+    int c[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int b = (int)(int8_t)((uint32_t)v[i >> 2] >> (8 * (i & 3)));
+        c[i] = (b < -1 ? -1 : (b > 1 ? 1 : b)) + 1;
+    }
+    packed[g] = bl_code_word<LAYOUT>(c);
+}
+
+template <int LAYOUT>
+__global__ __launch_bounds__(PACK_THREADS) void bl_unpack_kernel(const uint32_t* __restrict__ packed, int64_t words,
+                                                                  bl_v4i* __restrict__ Wt, int32_t* __restrict__ bad) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const uint32_t w = packed[g];
+    bl_v4i out = {0, 0, 0, 0};
+    int nbad = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = (int)((w >> bl_bitpos<LAYOUT>(i)) & 3u);
+        nbad += (c == 3);
+        out[i >> 2] |= (int)(((uint32_t)(c - 1) & 0xFFu) << (8 * (i & 3)));
+    }
+    Wt[g] = out;
+    if (nbad) atomicAdd(bad, nbad);
+}
+
+__global__ void bl_zero_i32(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+extern "C" bl_status bl_pack_ternary(const void* W, int in_kind, int64_t N, int64_t K, int layout,
+                                     uint8_t* packed, float* beta, void* workspace, bl_stream s) {
+    if (!W || !packed || !beta) return BL_ERR_NULL;
+    if (!bl_shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (in_kind != BL_IN_FP32_LATENT && in_kind != BL_IN_INT8_TERNARY) return BL_ERR_VALUE;
+    if (!bl_aligned(W, 16) || !bl_aligned(packed, 16) || !bl_aligned(beta, 4)) return BL_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)s;
+    const int64_t words = N * K / 16;
+    const unsigned grid = (unsigned)((words + PACK_THREADS - 1) / PACK_THREADS);
+    if (in_kind == BL_IN_FP32_LATENT) {
+        if (!workspace) return BL_ERR_WORKSPACE;
+        if (!bl_aligned(workspace, 8)) return BL_ERR_ALIGN;
+        double* partial = (double*)workspace;
+        const int64_t n4 = N * K / 4;
+        const int np = (int)(n4 < BL_PACK_PARTIALS ? n4 : BL_PACK_PARTIALS);
+        bl_abs_sum_partial<<<np, PACK_THREADS, 0, st>>>((const float4*)W, n4, partial);
+        bl_abs_sum_final<<<1, PACK_THREADS, 0, st>>>(partial, np, (double)(N * K), beta);
+        if (layout == 0)
+            bl_ternarize_pack<0><<<grid, PACK_THREADS, 0, st>>>((const float4*)W, beta, words, (uint32_t*)packed);
+        else
+            bl_ternarize_pack<1><<<grid, PACK_THREADS, 0, st>>>((const float4*)W, beta, words, (uint32_t*)packed);
+    } else {
+        if (layout == 0)
+            bl_pack_int8<0><<<grid, PACK_THREADS, 0, st>>>((const bl_v4i*)W, words, (uint32_t*)packed);
+        else
+            bl_pack_int8<1><<<grid, PACK_THREADS, 0, st>>>((const bl_v4i*)W, words, (uint32_t*)packed);
+    }
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+extern "C" bl_status bl_unpack_ternary(const uint8_t* packed, int64_t N, int64_t K, int layout,
+                                       int8_t* Wt, int32_t* bad, bl_stream s) {
+    if (!packed || !Wt || !bad) return BL_ERR_NULL;
+    if (!bl_shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (!bl_aligned(packed, 16) || !bl_aligned(Wt, 16) || !bl_aligned(bad, 4)) return BL_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)s;
+    const int64_t words = N * K / 16;
+    const unsigned grid = (unsigned)((words + PACK_THREADS - 1) / PACK_THREADS);
+    bl_zero_i32<<<1, 64, 0, st>>>(bad, 1);
+    if (layout == 0)
+        bl_unpack_kernel<0><<<grid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, words, (bl_v4i*)Wt, bad);
+    else
+        bl_unpack_kernel<1><<<grid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, words, (bl_v4i*)Wt, bad);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}

@@ -1,0 +1,90 @@
+/* Per-token absmax int8 activation quantisation (Section 2, "Activation
+ * Quantization", of the BitNet b1.58 2B4T report).  One workgroup per token
+ * row; the row is read twice (absmax, then quantise), the second pass hitting
+ * cache.  HBM-bound at prefill sizes, latency-bound at decode sizes. */
+#include "bl_device.h"
+#include "bl_host.h"
+
+#define QUANT_THREADS 256
+
+/* Quantise 8 bf16 values held in a uint4 to 8 int8 in a uint2; returns their sum. */
+__device__ __forceinline__ int bl_quant8(const uint4 v, float inv, uint2* out) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[2] = {0u, 0u};
+    int sum = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t h = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
+        float r = rintf(bl_bf16_to_f32(h) * inv);
+        r = fminf(fmaxf(r, -127.0f), 127.0f);
+        const int qi = (int)r;
+        sum += qi;
+        o[j >> 2] |= ((uint32_t)qi & 0xFFu) << (8 * (j & 3));
+    }
+    out->x = o[0];
+    out->y = o[1];
+    return sum;
+}
+
+__device__ __forceinline__ float bl_absmax8(const uint4 v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float m = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        m = fmaxf(m, fabsf(bl_bf16_to_f32(w[j] & 0xFFFFu)));
+        m = fmaxf(m, fabsf(bl_bf16_to_f32(w[j] >> 16)));
+    }
+    return m;
+}
+
+__global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows(const uint4* __restrict__ X, int K8,
+                                                                uint2* __restrict__ q, float* __restrict__ scale,
+                                                                int32_t* __restrict__ rowsum) {
+    __shared__ float smax[QUANT_THREADS / BL_WAVE];
+    __shared__ int ssum[QUANT_THREADS / BL_WAVE];
+    const int64_t m = blockIdx.x;
+    const uint4* x = X + m * K8;
+    uint2* qo = q + m * K8;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+
+    float mx = 0.0f;
+    for (int i = threadIdx.x; i < K8; i += QUANT_THREADS) mx = fmaxf(mx, bl_absmax8(x[i]));
+    mx = bl_wave_max(mx);
+    if (lane == 0) smax[w] = mx;
+    __syncthreads();
+    float gamma = smax[0];
+#pragma unroll
+    for (int i = 1; i < QUANT_THREADS / BL_WAVE; ++i) gamma = fmaxf(gamma, smax[i]);
+
+    const float g = fmaxf(gamma, 1e-5f);
+    const float inv = bl_div_rn(127.0f, g);
+    int sum = 0;
+    for (int i = threadIdx.x; i < K8; i += QUANT_THREADS) {
+        uint2 o;
+        sum += bl_quant8(x[i], inv, &o);
+        qo[i] = o;
+    }
+    sum = bl_wave_sum(sum);
+    if (lane == 0) ssum[w] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        scale[m] = bl_div_rn(g, 127.0f);
+        if (rowsum) {
+            int t = 0;
+#pragma unroll
+            for (int i = 0; i < QUANT_THREADS / BL_WAVE; ++i) t += ssum[i];
+            rowsum[m] = t;
+        }
+    }
+}
+
+extern "C" bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K, int8_t* q, float* scale,
+                                       int32_t* rowsum, bl_stream s) {
+    if (!X || !q || !scale) return BL_ERR_NULL;
+    if (M < 1 || M > BL_MAX_DIM || K < 64 || K % 64 != 0 || K > BL_MAX_DIM) return BL_ERR_SHAPE;
+    if (!bl_aligned(X, 16) || !bl_aligned(q, 16) || !bl_aligned(scale, 4) || !bl_aligned(rowsum, 4))
+        return BL_ERR_ALIGN;
+    bl_quant_rows<<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>((const uint4*)X, (int)(K / 8), (uint2*)q,
+                                                                    scale, rowsum);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}

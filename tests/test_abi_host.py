@@ -1,0 +1,82 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, sizes are right and argument errors are
+reported as status codes before any GPU work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2504_12285_amd import binding as bl
+from paper_2504_12285_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hip_build.LIB_PATH):
+        hip_build.build()
+    return bl.load()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bitlinear.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bl_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    names = _declared_symbols()
+    assert {"bl_pack_ternary", "bl_quant_act_int8", "bl_gemv_w158a8", "bl_gemm_w158a8"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+        assert n in bl.SIGNATURES, "binding lacks " + n
+    assert sorted(bl.SIGNATURES) == names
+
+
+def test_sizes(lib):
+    assert lib.bl_version() >= 100
+    for layout in (0, 1):
+        assert lib.bl_packed_bytes(2560, 2560, layout) == 2560 * 2560 // 4
+        assert lib.bl_packed_bytes(13824, 2560, layout) == 8847360
+        assert lib.bl_packed_bytes(2560, 6912, layout) == 4423680
+    assert lib.bl_packed_bytes(2560, 2560, 7) == 0
+    assert lib.bl_packed_bytes(2560, 100, 0) == 0   # K % 64
+    assert lib.bl_packed_bytes(6, 128, 0) == 0      # N % 4
+    assert lib.bl_workspace_bytes(bl.BL_OP_PACK, 0, 2560, 2560) >= 8192
+    assert lib.bl_workspace_bytes(bl.BL_OP_GEMM, 2048, 2560, 2560) >= 2048 * 4
+    assert b"BL_ERR_SHAPE" in lib.bl_status_str(2)
+
+
+def test_argument_errors_need_no_gpu(lib):
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) & ~255  # an aligned host address: never dereferenced on error paths
+    NULL = None
+    # NULL pointers
+    assert lib.bl_pack_ternary(NULL, 0, 64, 64, 0, p, p, p, NULL) == 1
+    assert lib.bl_quant_act_int8(p, 1, 64, NULL, p, NULL, NULL) == 1
+    assert lib.bl_gemv_w158a8(p, p, 0, p, p, NULL, 1, 64, 64, NULL, NULL, NULL, NULL) == 1  # no output
+    assert lib.bl_gemv_w158a8(p, p, 0, p, NULL, NULL, 1, 64, 64, NULL, p, NULL, NULL) == 1  # y without scale
+    # shapes
+    assert lib.bl_pack_ternary(p, 0, 64, 100, 0, p, p, p, NULL) == 2
+    assert lib.bl_pack_ternary(p, 0, 6, 64, 0, p, p, p, NULL) == 2
+    assert lib.bl_quant_act_int8(p, 0, 64, p, p, NULL, NULL) == 2
+    assert lib.bl_gemv_w158a8(p, p, 0, p, p, NULL, 65, 64, 64, p, NULL, NULL, NULL) == 2   # M > 64
+    assert lib.bl_gemv_w158a8(p, p, 0, p, p, NULL, 0, 64, 64, p, NULL, NULL, NULL) == 2
+    assert lib.bl_gemm_w158a8(p, p, 0, p, p, NULL, 8, 64, 96, p, NULL, NULL, NULL) == 2
+    # layout / kind
+    assert lib.bl_pack_ternary(p, 0, 64, 64, 5, p, p, p, NULL) == 3
+    assert lib.bl_gemv_w158a8(p, p, 9, p, p, NULL, 1, 64, 64, p, NULL, NULL, NULL) == 3
+    assert lib.bl_pack_ternary(p, 3, 64, 64, 0, p, p, p, NULL) == 5
+    # alignment
+    assert lib.bl_gemv_w158a8(p + 4, p, 0, p, p, NULL, 1, 64, 64, p, NULL, NULL, NULL) == 4
+    assert lib.bl_gemm_w158a8(p, p, 0, p + 1, p, NULL, 1, 64, 64, p, NULL, NULL, NULL) == 4
+    # workspace
+    assert lib.bl_pack_ternary(p, 0, 64, 64, 0, p, p, NULL, NULL) == 7
+
+
+def test_binding_raises_with_status():
+    with pytest.raises(bl.BitLinearError) as e:
+        bl._check(2, "bl_gemv_w158a8")
+    assert e.value.status == 2 and "BL_ERR_SHAPE" in str(e.value)

@@ -1,0 +1,233 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded
+inputs.  Integers, bytes and bit patterns must match exactly; rescaled fp32
+outputs to 1e-6 relative (the stated bar; both sides use the same two fp32
+multiplies so they are normally bit-identical)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from helpers import Case, assert_y_close, to_dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def bl():
+    from paper_2504_12285_amd import binding
+    binding.load()
+    return binding
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------- packing
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("shape", [(4, 64), (48, 320), (2560, 2560), (2560, 6912)])
+def test_pack_bytes_and_beta_bit_exact(bl, layout, shape):
+    N, K = shape
+    c = Case(10 + N % 7, 1, N, K, full=False)
+    packed, beta = bl.bl_pack_ternary(to_dev(c.W), layout)
+    _sync()
+    assert beta.item() == float(c.beta)
+    assert np.array_equal(packed.cpu().numpy(), c.packed(layout))
+    Wt, bad = bl.bl_unpack_ternary(packed, N, K, layout)
+    _sync()
+    assert bad.item() == 0 and np.array_equal(Wt.cpu().numpy(), c.Wt)
+    # already-ternary input gives the same bytes
+    p2, _ = bl.bl_pack_ternary(to_dev(c.Wt), layout, beta=float(c.beta))
+    _sync()
+    assert np.array_equal(p2.cpu().numpy(), c.packed(layout))
+
+
+def test_pack_ties_and_zero_matrix(bl):
+    # exact ties of W/(beta+1e-5): beta chosen so the divisor is 2^-6
+    eps = np.float32(1e-5)
+    W = np.zeros((4, 64), dtype=np.float32)
+    r = np.array([0.5, -0.5, 1.5, -1.5, 2.5, 0.51, -0.51, 0.49, 100, -100], dtype=np.float32)
+    W[0, : r.size] = r * np.float32(2.0 ** -6)
+    beta_o = oracle.absmean_beta(W)
+    Wt_o = oracle.ternarize(W, beta_o)
+    packed, beta = bl.bl_pack_ternary(to_dev(W), 0)
+    _sync()
+    assert beta.item() == float(beta_o)
+    assert np.array_equal(packed.cpu().numpy(), oracle.pack(Wt_o, 0))
+    Z = np.zeros((8, 128), dtype=np.float32)
+    packed, beta = bl.bl_pack_ternary(to_dev(Z), 1)
+    _sync()
+    assert beta.item() == 0.0 and np.all(packed.cpu().numpy() == 0x55)
+
+
+def test_unpack_counts_invalid_codes(bl):
+    p = np.arange(256, dtype=np.uint8).repeat(4)  # N*K/4 = 1024 bytes -> N=16, K=256
+    Wt_o, bad_o = oracle.unpack(p, 16, 256, 0)
+    Wt, bad = bl.bl_unpack_ternary(to_dev(p), 16, 256, 0)
+    _sync()
+    assert bad.item() == bad_o and np.array_equal(Wt.cpu().numpy(), Wt_o)
+
+
+# --------------------------------------------------------------- quantiser
+@pytest.mark.parametrize("M,K,relu2", [(1, 64, False), (4, 2560, False), (33, 6912, True), (3, 320, False),
+                                       (64, 2560, False)])
+def test_quant_bit_exact(bl, M, K, relu2):
+    X = synth.activations_bf16(21, M, K, matrix=3 if relu2 else 0, relu2=relu2)
+    q_o, s_o, r_o = oracle.quant_act(X)
+    q, s, r = bl.bl_quant_act_int8(to_dev(X))
+    _sync()
+    assert np.array_equal(q.cpu().numpy(), q_o)
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
+    assert np.array_equal(r.cpu().numpy(), r_o)
+
+
+def test_quant_edge_rows(bl):
+    K = 128
+    rows = np.zeros((5, K), dtype=np.float32)
+    rows[0, :8] = [127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 63]       # ties at inv = 1
+    rows[1, :7] = [2, 1, 0.5, -1, -2, 0, 0.25]                      # ties at inv = 63.5
+    rows[3, :7] = [254, 1, 3, 5, -7, 0, -254]
+    rows[4, :] = 3.0e-6                                             # below the 1e-5 clamp
+    X = oracle.f32_to_bf16(rows)
+    q_o, s_o, r_o = oracle.quant_act(X)
+    q, s, r = bl.bl_quant_act_int8(to_dev(X))
+    _sync()
+    assert np.array_equal(q.cpu().numpy(), q_o)
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
+    assert np.array_equal(r.cpu().numpy(), r_o)
+    q2, s2, r2 = bl.bl_quant_act_int8(to_dev(X), want_rowsum=False)
+    _sync()
+    assert r2 is None and np.array_equal(q2.cpu().numpy(), q_o)
+
+
+# ------------------------------------------------------------------ products
+def _run_product(bl, fn, c, layout, use_rowsum=True):
+    packed = to_dev(c.packed(layout))
+    beta = to_dev(np.array([c.beta], dtype=np.float32))
+    q, scale = to_dev(c.q), to_dev(c.scale)
+    rowsum = to_dev(c.rowsum) if use_rowsum else None
+    acc, y = fn(packed, beta, layout, q, scale, rowsum, c.N)
+    _sync()
+    return acc.cpu().numpy(), y.cpu().numpy()
+
+
+GEMV_SHAPES = [(4, 64), (20, 64), (52, 320), (2560, 2560), (2564, 1024)]
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("shape", GEMV_SHAPES)
+def test_gemv_small_m(bl, layout, M, shape):
+    N, K = shape
+    c = Case(31, M, N, K)
+    acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=False)
+    assert np.array_equal(acc, c.acc)
+    assert_y_close(y, c.y)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("M", [5, 8, 17, 32, 64])
+def test_gemv_batched(bl, layout, M):
+    c = Case(32, M, 2560, 2560)
+    acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(M % 2 == 0))
+    assert np.array_equal(acc, c.acc)
+    assert_y_close(y, c.y)
+
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+@pytest.mark.parametrize("M", [1, 4])
+def test_gemv_layer_shapes(bl, name, M):
+    N, K = synth.LAYER_SHAPES[name]
+    c = Case(0, M, N, K, layer=0, matrix=name, relu2=(name == "down"))
+    for layout in (0, 1):
+        acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout)
+        assert np.array_equal(acc, c.acc)
+        assert_y_close(y, c.y)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("M,N,K", [(1, 4, 64), (7, 20, 64), (100, 132, 320), (128, 128, 128), (300, 2560, 2560),
+                                   (129, 260, 6912)])
+def test_gemm_ragged(bl, layout, M, N, K):
+    c = Case(33, M, N, K)
+    acc, y = _run_product(bl, bl.bl_gemm_w158a8, c, layout, use_rowsum=(M % 2 == 1))
+    assert np.array_equal(acc, c.acc)
+    assert_y_close(y, c.y)
+
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+def test_gemm_prefill_2048_full(bl, name):
+    N, K = synth.LAYER_SHAPES[name]
+    c = Case(0, 2048, N, K, layer=0, matrix=name, relu2=(name == "down"))
+    acc, y = _run_product(bl, bl.bl_gemm_w158a8, c, 1)
+    assert np.array_equal(acc, c.acc)
+    assert_y_close(y, c.y)
+
+
+def test_weights_read_back_through_the_product(bl):
+    """x = 127 * e_k gives acc[m][n] = 127 * Wt[n][k]: one token per k reads the
+    whole matrix back through pack + product (catches any layout/index slip)."""
+    N, K = 64, 256
+    Wt = synth.uniform_i8(40, (N, K), -1, 1)
+    q = np.zeros((K, K), dtype=np.int8)
+    q[np.arange(K), np.arange(K)] = 127
+    scale = np.ones(K, dtype=np.float32)
+    beta = to_dev(np.array([1.0], dtype=np.float32))
+    for layout in (0, 1):
+        packed = to_dev(oracle.pack(Wt, layout))
+        acc, _ = bl.bl_gemm_w158a8(packed, beta, layout, to_dev(q), to_dev(scale), None, N)
+        _sync()
+        assert np.array_equal(acc.cpu().numpy(), 127 * Wt.T.astype(np.int32))
+        for k0 in (0, 64, 192):
+            acc, _ = bl.bl_gemv_w158a8(packed, beta, layout, to_dev(q[k0:k0 + 4]), to_dev(scale[:4]), None, N)
+            _sync()
+            assert np.array_equal(acc.cpu().numpy(), 127 * Wt.T[k0:k0 + 4].astype(np.int32))
+
+
+def test_extreme_values_and_zero_input(bl):
+    N, K = 128, 6912
+    ones = np.ones((N, K), dtype=np.int8)
+    q = np.full((2, K), 127, dtype=np.int8)
+    q[1] = -127
+    beta = to_dev(np.array([1.0], dtype=np.float32))
+    scale = to_dev(np.ones(2, dtype=np.float32))
+    packed = to_dev(oracle.pack(ones, 1))
+    for fn in (bl.bl_gemv_w158a8, bl.bl_gemm_w158a8):
+        acc, y = fn(packed, beta, 1, to_dev(q), scale, None, N)
+        _sync()
+        a = acc.cpu().numpy()
+        assert np.all(a[0] == 127 * K) and np.all(a[1] == -127 * K)   # |acc| bound 877,824 reached
+        acc, y = fn(packed, beta, 1, to_dev(np.zeros((2, K), np.int8)), scale, None, N)
+        _sync()
+        assert not acc.cpu().numpy().any()
+        yz = y.cpu().numpy()
+        assert np.all(yz == 0) and not np.signbit(yz).any()
+
+
+def test_repeatable_and_token_independent(bl):
+    c = Case(34, 4, 2560, 2560)
+    first = _run_product(bl, bl.bl_gemv_w158a8, c, 1)[0]
+    for _ in range(3):
+        assert np.array_equal(_run_product(bl, bl.bl_gemv_w158a8, c, 1)[0], first)
+    packed = to_dev(c.packed(1))
+    beta = to_dev(np.array([c.beta], dtype=np.float32))
+    for m in range(4):
+        acc, _ = bl.bl_gemv_w158a8(packed, beta, 1, to_dev(c.q[m:m + 1]), to_dev(c.scale[m:m + 1]), None, c.N)
+        _sync()
+        assert np.array_equal(acc.cpu().numpy()[0], first[m])
+
+
+def test_whole_layer_through_the_abi(bl):
+    """Config-0 style end to end: latent weights and bf16 activations in, every
+    intermediate compared (packed, beta, q, scale, acc, y)."""
+    c = Case(0, 4, 2560, 2560)
+    packed, beta = bl.bl_pack_ternary(to_dev(c.W), 1)
+    q, scale, rowsum = bl.bl_quant_act_int8(to_dev(c.X))
+    acc, y = bl.bl_gemv_w158a8(packed, beta, 1, q, scale, rowsum, c.N)
+    _sync()
+    assert np.array_equal(packed.cpu().numpy(), c.packed(1)) and beta.item() == float(c.beta)
+    assert np.array_equal(q.cpu().numpy(), c.q) and np.array_equal(scale.cpu().numpy(), c.scale)
+    assert np.array_equal(acc.cpu().numpy(), c.acc)
+    assert_y_close(y.cpu().numpy(), c.y)

@@ -72,11 +72,13 @@ def test_pack_one_hot_positions(layout):
         assert diff.size == 1
         if layout == 0:
             byte = n * (K // 4) + k // 4
+            shift = 2 * (k % 4)
         else:
-            unit = (n // 16) * (16 * (K // 64)) + (k // 64) * 16 + (n % 16)
-            byte = unit * 16 + (k % 64) // 4
+            i = k % 16
+            byte = n * (K // 4) + (k // 16) * 4 + i % 4
+            shift = 2 * (i // 4)
         assert diff[0] == byte
-        assert p[byte] == (0x55 + (1 << (2 * (k % 4))))
+        assert p[byte] == (0x55 + (1 << shift))
 
 
 @pytest.mark.parametrize("layout", [0, 1])
@@ -90,14 +92,21 @@ def test_pack_roundtrip_random(layout, shape):
     assert bad == 0 and np.array_equal(back, Wt)
 
 
-def test_layout1_is_permutation_of_layout0_units():
-    N, K = 64, 512
+def test_layout1_word_digit_swap():
+    """Layout 1 keeps each 16-weight word in place and swaps (byte, bit-pair)
+    digits inside it: word1.byte[b].pair[s] == word0.byte[s].pair[b]."""
+    N, K = 8, 128
     Wt = synth.uniform_i8(5, (N, K), -1, 1)
-    p0 = oracle.pack(Wt, 0).reshape(N, K // 64, 16)
-    p1 = oracle.pack(Wt, 1).reshape(N // 16, K // 64, 16, 16)
-    for n in (0, 5, 17, 63):
-        for s in (0, 3, 7):
-            assert np.array_equal(p1[n // 16, s, n % 16], p0[n, s])
+    p0 = oracle.pack(Wt, 0).reshape(-1, 4)
+    p1 = oracle.pack(Wt, 1).reshape(-1, 4)
+    f0 = np.stack([(p0 >> (2 * s)) & 3 for s in range(4)], axis=2)  # [word][byte][pair]
+    f1 = np.stack([(p1 >> (2 * s)) & 3 for s in range(4)], axis=2)
+    assert np.array_equal(f1, f0.transpose(0, 2, 1))
+    # natural order: pair s of byte b of layout 1 is weight 4s+b of the word
+    w = (Wt.reshape(-1, 16) + 1).astype(np.uint8)
+    for s_ in range(4):
+        for b in range(4):
+            assert np.array_equal(f1[:, b, s_], w[:, 4 * s_ + b])
 
 
 def test_pack_rejects_non_ternary():
