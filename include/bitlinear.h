@@ -135,6 +135,44 @@ bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout,
                          int64_t M, int64_t N, int64_t K,
                          int32_t* acc, float* y, void* workspace, bl_stream s);
 
+/* Fused BitLinear for decode, 1 <= M <= 4, K <= 8192: the per-token absmax
+ * int8 quantiser (Section 2) runs inside the product kernel (Section 5.1), so
+ * one launch takes bf16 activations to fp32 outputs.  Same arithmetic, bit for
+ * bit, as bl_quant_act_int8 followed by bl_gemv_w158a8.
+ *   X         device bf16 [M][K].
+ *   acc / y   device out [M][N], either may be NULL (not both).
+ *   q_out     device out int8 [M][K] or NULL: the quantised activations;
+ *   scale_out device out fp32 [M] or NULL: max(absmax,1e-5)/127 per token. */
+bl_status bl_bitlinear_decode(const uint8_t* packed, const float* beta, int layout,
+                              const uint16_t* X, int64_t M, int64_t N, int64_t K,
+                              int32_t* acc, float* y, int8_t* q_out, float* scale_out, bl_stream s);
+
+/* One decode product of a group.  Give either X (bf16, fused quantiser) or
+ * q (+ scale if y is wanted, + optional rowsum).  All pointers are device
+ * pointers; the descriptor array itself is HOST memory, read during the call.
+ * fixed_scale > 0 (fused path only) replaces absmax/127 in the rescale, i.e.
+ * the layer then acts on x/absmax (a normalised input); 0 = normal. */
+typedef struct {
+    const uint8_t* packed;
+    const float* beta;
+    const uint16_t* X;
+    const int8_t* q;
+    const float* scale;
+    const int32_t* rowsum;
+    int64_t N, K;
+    int32_t* acc;
+    float* y;
+    int8_t* q_out;
+    float* scale_out;
+    float fixed_scale;
+} bl_decode_desc;
+
+/* Up to four INDEPENDENT decode products (same M <= 4, same layout, K <= 8192
+ * each) in one kernel launch, e.g. the four BitLinear shapes of a layer on
+ * independent inputs.  Results are identical to separate calls; the point is
+ * one launch and one continuous weight stream instead of four. */
+bl_status bl_bitlinear_decode_group(const bl_decode_desc* descs, int count, int layout, int64_t M, bl_stream s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,16 @@ SIGNATURES = {
     "bl_quant_act_int8": (_ci, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_gemv_w158a8": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_gemm_w158a8": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "bl_bitlinear_decode": (_ci, [_vp, _vp, _ci, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "bl_bitlinear_decode_group": (_ci, [_vp, _ci, _ci, _i64, _vp]),
 }
+
+
+class DecodeDesc(ctypes.Structure):
+    """Mirror of bl_decode_desc."""
+    _fields_ = [("packed", _vp), ("beta", _vp), ("X", _vp), ("q", _vp), ("scale", _vp), ("rowsum", _vp),
+                ("N", _i64), ("K", _i64), ("acc", _vp), ("y", _vp), ("q_out", _vp), ("scale_out", _vp),
+                ("fixed_scale", ctypes.c_float)]
 
 
 class BitLinearError(RuntimeError):
@@ -165,3 +174,37 @@ def bl_gemm_w158a8(packed, beta, layout, q, scale, rowsum, N, want_acc=True, wan
     """Prefill product, any M.  Returns (acc, y) like bl_gemv_w158a8."""
     return _matmul("bl_gemm_w158a8", BL_OP_GEMM, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y,
                    acc, y, workspace)
+
+
+def bl_bitlinear_decode(packed, beta, layout, X, N, want_acc=False, want_y=True, want_q=False, acc=None, y=None):
+    """Fused decode BitLinear, M <= 4: bf16 X [M][K] -> (acc, y, q, scale)."""
+    import torch
+    assert X.is_cuda and X.is_contiguous() and X.dtype == torch.bfloat16
+    M, K = X.shape
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=X.device)
+    if want_y and y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    q = torch.empty((M, K), dtype=torch.int8, device=X.device) if want_q else None
+    scale = torch.empty(M, dtype=torch.float32, device=X.device) if want_q else None
+    _check(load().bl_bitlinear_decode(_ptr(packed), _ptr(beta), layout, _ptr(X), M, N, K, _ptr(acc), _ptr(y),
+                                      _ptr(q), _ptr(scale), _stream()), "bl_bitlinear_decode")
+    return acc, y, q, scale
+
+
+def make_decode_descs(items):
+    """items: list of dicts with tensor values for the bl_decode_desc fields
+    (packed, beta, X or q/scale/rowsum, acc, y, q_out, scale_out) and int N, K.
+    Returns a ctypes array usable with bl_bitlinear_decode_group."""
+    arr = (DecodeDesc * len(items))()
+    for d, it in zip(arr, items):
+        for f in ("packed", "beta", "X", "q", "scale", "rowsum", "acc", "y", "q_out", "scale_out"):
+            setattr(d, f, _ptr(it.get(f)))
+        d.N, d.K = int(it["N"]), int(it["K"])
+        d.fixed_scale = float(it.get("fixed_scale", 0.0))
+    return arr
+
+
+def bl_bitlinear_decode_group(descs, layout, M):
+    """descs: ctypes array from make_decode_descs (host memory)."""
+    _check(load().bl_bitlinear_decode_group(descs, len(descs), layout, M, _stream()), "bl_bitlinear_decode_group")

@@ -73,3 +73,15 @@ __device__ __forceinline__ void bl_transpose4x4(uint32_t& a0, uint32_t& a1, uint
     a2 = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
     a3 = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
+
+/* Wait for in-flight matrix-core results before ordinary vector instructions
+ * read an accumulator.  The hardware has no interlock for that read, and the
+ * compiler's wait-state count for the gfx950 16x16x64 int8 MFMA proved too
+ * short on hardware (the last result rows were read before they were written).
+ * 32 idle issue cycles cover the longest (16-pass) MFMA; the scheduling
+ * barriers keep every MFMA before and every reader after this point. */
+__device__ __forceinline__ void bl_mfma_fence() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}

@@ -9,28 +9,61 @@
 #include "bl_device.h"
 #include "bl_host.h"
 
-#define GEMM_THREADS 256
-#define GEMM_BK 64
-#define A_STRIDE 80   /* bytes per activation row in LDS: 64 + 16 pad */
-#define W_STRIDE 5    /* dwords per packed weight row in LDS: 4 + 1 pad */
+#include <stdlib.h>
 
-template <int BM, int BN, int LAYOUT>
+#define GEMM_THREADS 256
+
+/* Expand one packed word (16 weights, layout-1 digit order) into the sixteen
+ * int8 codes of 16 consecutive k: three shifts and four masks. */
+__device__ __forceinline__ bl_v4i bl_unpack16(uint32_t p) {
+    bl_v4i b;
+    b[0] = (int)(p & 0x03030303u);
+    b[1] = (int)((p >> 2) & 0x03030303u);
+    b[2] = (int)((p >> 4) & 0x03030303u);
+    b[3] = (int)((p >> 6) & 0x03030303u);
+    return b;
+}
+#define GEMM_PAD 16   /* bytes of padding per activation row in LDS (bank spread) */
+
+/* Block tile BM x BN, k step BK (64 or 128), four waves arranged WGM x WGN.
+ * LDS is double buffered: while the matrix cores work on buffer b, the next
+ * k step travels global -> registers -> buffer 1-b; one barrier per k step.
+ *   A buffer: BM rows x (BK + pad) int8 activations.
+ *   W buffer: BN rows x (BK/16 + 1) packed words (16 weights each).
+ * Operand mapping of v_mfma_i32_32x32x32_i8: lane l supplies 16 consecutive k
+ * (offset 16*(l/32)) of row l%32 for both operands; a packed word expands to
+ * exactly those 16 int8 (layout 1), so one ds_read_b32 feeds one B operand. */
+template <int BM, int BN, int BK, int WGM, int LAYOUT>
 __global__ __launch_bounds__(GEMM_THREADS) void bl_gemm_mfma(const uint8_t* __restrict__ packed,
                                                               const int8_t* __restrict__ q,
                                                               const int32_t* __restrict__ rowsum,
                                                               const float* __restrict__ beta,
                                                               const float* __restrict__ scale, int M, int N, int K,
                                                               int32_t* __restrict__ acc, float* __restrict__ y) {
-    constexpr int WM = BM / 2, WN = BN / 2, MI = WM / 32, NI = WN / 32;
-    constexpr int A_UNITS = BM * 4 / GEMM_THREADS;  /* 16-byte units per thread */
-    __shared__ __attribute__((aligned(16))) uint8_t As[BM * A_STRIDE];
-    __shared__ uint32_t Ws[BN * W_STRIDE];
+    constexpr int WGN = 4 / WGM;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    constexpr int KS = BK / 32;                       /* MFMA k sub-steps per k step  */
+    constexpr int A_STRIDE = BK + GEMM_PAD;           /* bytes                        */
+    constexpr int W_WORDS = BK / 16;                  /* packed words per row, k step */
+    constexpr int W_STRIDE = W_WORDS + 1;             /* dwords                       */
+    constexpr int A_UPR = BK / 16;                    /* 16-byte units per A row      */
+    constexpr int A_UNITS = BM * A_UPR / GEMM_THREADS;
+    constexpr int W_UPR = BK / 64;                    /* 16-byte units per W row      */
+    constexpr int W_UNITS = (BN * W_UPR + GEMM_THREADS - 1) / GEMM_THREADS;
+    static_assert(BM * A_UPR % GEMM_THREADS == 0, "A tile must split evenly");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr int A_BYTES = BM * A_STRIDE;
+    constexpr int W_BYTES = BN * W_STRIDE * 4;
+    auto As = [&](int b) { return smem + b * A_BYTES; };
+    auto Ws = [&](int b) { return (uint32_t*)(smem + 2 * A_BYTES + b * W_BYTES); };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int l32 = lane & 31, h = lane >> 5;
-    const int kb = K / 4;  /* packed bytes per weight row */
+    const int kb = K / 4;
 
     bl_v16i C[MI][NI];
 #pragma unroll
@@ -40,80 +73,101 @@ __global__ __launch_bounds__(GEMM_THREADS) void bl_gemm_mfma(const uint8_t* __re
 #pragma unroll
             for (int v = 0; v < 16; ++v) C[mi][ni][v] = 0;
 
-    /* global -> register staging */
     uint4 areg[A_UNITS];
-    uint4 wreg = make_uint4(0, 0, 0, 0);
+    uint4 wreg[W_UNITS];
     const uint8_t* aptr[A_UNITS];
+    const uint8_t* wptr[W_UNITS];
 #pragma unroll
     for (int i = 0; i < A_UNITS; ++i) {
-        const int u = tid + i * GEMM_THREADS, row = u >> 2, c = u & 3;
+        const int u = tid + i * GEMM_THREADS, row = u / A_UPR, c = u % A_UPR;
         int m = m0 + row;
         if (m >= M) m = M - 1;
         aptr[i] = (const uint8_t*)q + (int64_t)m * K + c * 16;
     }
-    int wn = n0 + tid;
-    if (wn >= N) wn = N - 1;
-    const uint8_t* wptr = packed + (int64_t)wn * kb;
-    const bool wload = tid < BN;
+#pragma unroll
+    for (int i = 0; i < W_UNITS; ++i) {
+        const int u = tid + i * GEMM_THREADS, row = u / W_UPR, c = u % W_UPR;
+        int n = n0 + row;
+        if (n >= N) n = N - 1;
+        wptr[i] = packed + (int64_t)n * kb + c * 16;
+    }
 
     auto load_tiles = [&](int kk) {
 #pragma unroll
-        for (int i = 0; i < A_UNITS; ++i) areg[i] = *(const uint4*)(aptr[i] + (int64_t)kk * GEMM_BK);
-        if (wload) wreg = *(const uint4*)(wptr + (int64_t)kk * 16);
+        for (int i = 0; i < A_UNITS; ++i) areg[i] = *(const uint4*)(aptr[i] + (int64_t)kk * BK);
+#pragma unroll
+        for (int i = 0; i < W_UNITS; ++i)
+            if (tid + i * GEMM_THREADS < BN * W_UPR) wreg[i] = *(const uint4*)(wptr[i] + (int64_t)kk * (BK / 4));
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](int b) {
 #pragma unroll
         for (int i = 0; i < A_UNITS; ++i) {
-            const int u = tid + i * GEMM_THREADS, row = u >> 2, c = u & 3;
+            const int u = tid + i * GEMM_THREADS, row = u / A_UPR, c = u % A_UPR;
             uint32_t a0 = areg[i].x, a1 = areg[i].y, a2 = areg[i].z, a3 = areg[i].w;
             if (LAYOUT == 0) bl_transpose4x4(a0, a1, a2, a3);
-            *(uint4*)(As + row * A_STRIDE + c * 16) = make_uint4(a0, a1, a2, a3);
+            *(uint4*)(As(b) + row * A_STRIDE + c * 16) = make_uint4(a0, a1, a2, a3);
         }
-        if (wload) {
-            uint32_t* d = Ws + tid * W_STRIDE;
-            d[0] = wreg.x; d[1] = wreg.y; d[2] = wreg.z; d[3] = wreg.w;
+#pragma unroll
+        for (int i = 0; i < W_UNITS; ++i) {
+            const int u = tid + i * GEMM_THREADS, row = u / W_UPR, c = u % W_UPR;
+            if (u < BN * W_UPR) {
+                uint32_t* d = Ws(b) + row * W_STRIDE + c * 4;
+                d[0] = wreg[i].x; d[1] = wreg[i].y; d[2] = wreg[i].z; d[3] = wreg[i].w;
+            }
         }
     };
 
-    const int steps = K / GEMM_BK;
+    const int steps = K / BK;
     load_tiles(0);
-    store_tiles();
+    store_tiles(0);
     __syncthreads();
     for (int kk = 0; kk < steps; ++kk) {
+        const int b = kk & 1;
         if (kk + 1 < steps) load_tiles(kk + 1);
+        const uint8_t* Ab = As(b) + (wm0 + l32) * A_STRIDE + h * 16;
+        const uint32_t* Wb = Ws(b) + (wn0 + l32) * W_STRIDE + h;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             bl_v4i a[MI];
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                a[mi] = *(const bl_v4i*)(As + (wm0 + mi * 32 + l32) * A_STRIDE + ks * 32 + h * 16);
+            for (int mi = 0; mi < MI; ++mi) a[mi] = *(const bl_v4i*)(Ab + mi * 32 * A_STRIDE + ks * 32);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
-                const uint32_t p = Ws[(wn0 + ni * 32 + l32) * W_STRIDE + ks * 2 + h];
-                bl_v4i b;
-                b[0] = (int)(p & 0x03030303u);
-                b[1] = (int)((p >> 2) & 0x03030303u);
-                b[2] = (int)((p >> 4) & 0x03030303u);
-                b[3] = (int)((p >> 6) & 0x03030303u);
+                const uint32_t p = Wb[ni * 32 * W_STRIDE + ks * 2];
+                bl_v4i bop;
+                bop[0] = (int)(p & 0x03030303u);
+                bop[1] = (int)((p >> 2) & 0x03030303u);
+                bop[2] = (int)((p >> 4) & 0x03030303u);
+                bop[3] = (int)((p >> 6) & 0x03030303u);
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    C[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b, C[mi][ni], 0, 0, 0);
+                    C[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], bop, C[mi][ni], 0, 0, 0);
             }
         }
-        __syncthreads();
-        if (kk + 1 < steps) store_tiles();
+        if (kk + 1 < steps) store_tiles(b ^ 1);
         __syncthreads();
     }
 
-    const float bt = *beta;
+    /* Epilogue: per-row terms through LDS once (see bl_gemm_tile256). */
+    bl_mfma_fence();
+    __syncthreads();
+    int* rs_s = (int*)smem;
+    float* cf_s = (float*)(smem + BM * 4);
+    for (int i = tid; i < BM; i += GEMM_THREADS) {
+        const int m = m0 + i;
+        rs_s[i] = m < M ? rowsum[m] : 0;
+        cf_s[i] = (y && m < M) ? *beta * scale[m] : 0.0f;
+    }
+    __syncthreads();
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int m = m0 + wm0 + mi * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+            const int ml = wm0 + mi * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+            const int m = m0 + ml;
             if (m < M) {
-                const int rs = rowsum[m];
-                const float c = y ? bt * scale[m] : 0.0f;
+                const int rs = rs_s[ml];
+                const float c = cf_s[ml];
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const int n = n0 + wn0 + ni * 32 + l32;
@@ -125,6 +179,292 @@ __global__ __launch_bounds__(GEMM_THREADS) void bl_gemm_mfma(const uint8_t* __re
                 }
             }
         }
+}
+
+template <int BM, int BN, int BK, int WGM>
+static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
+                             const float* scale, const int32_t* rowsum, int M, int N, int K, int32_t* acc,
+                             float* y, hipStream_t st) {
+    constexpr size_t lds = 2 * (size_t)(BM * (BK + GEMM_PAD) + BN * (BK / 16 + 1) * 4);
+    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
+    auto k0 = bl_gemm_mfma<BM, BN, BK, WGM, 0>;
+    auto k1 = bl_gemm_mfma<BM, BN, BK, WGM, 1>;
+    auto kern = layout == 0 ? k0 : k1;
+    if (lds > 64 * 1024) {
+        static bool set0 = false, set1 = false;
+        bool& done = layout == 0 ? set0 : set1;
+        if (!done) {
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+                hipSuccess)
+                return BL_ERR_HIP;
+            done = true;
+        }
+    }
+    kern<<<grid, GEMM_THREADS, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, acc, y);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+/* ---- large-tile pipelined kernel -------------------------------------------
+ * 256 x 256 output tile per workgroup, k step 128, three LDS stages filled by
+ * direct global->LDS loads (no register staging) two k steps ahead of the
+ * matrix cores; one barrier per k step.  WM x WN waves (4 or 8 in total): with
+ * eight waves every SIMD holds two, so one wave's unpack and LDS traffic hide
+ * behind the other's MFMAs (a single wave reaches only ~60 % of the MFMA rate
+ * once the unpack instructions share its issue slot).
+ *
+ * LDS stage = A part (256 rows x 128 int8, 16-byte units XOR-swizzled by
+ * row%8) + W part (256 rows x 32 packed bytes = two units, swapped by row/4%2).
+ * A direct load writes 64 consecutive units per wave, so the swizzle is applied
+ * to the GLOBAL address each lane fetches, not to the LDS address.
+ *
+ * k mapping inside a k step: MFMA sub-step ks, lane half h  <->  the 16 k of
+ * packed word 4h+ks (bytes 16*(4h+ks).. of the activation row).  Lane half h
+ * therefore needs exactly unit h of a weight row: one ds_read_b128 per 32 rows
+ * and k step, and one per (32 rows, sub-step) for the activations.
+ *
+ * Workgroups are numbered so that the 32 that share an XCD (and its L2) at a
+ * time form an 8 x 4 patch of tiles: 8 activation row tiles x 4 weight tiles.
+ * Requires layout 1, K % 128 == 0. */
+#define G3_BM 256
+#define G3_BN 256
+#define G3_BK 128
+#define G3_STAGES 3
+#define G3_A_BYTES (G3_BM * G3_BK)
+#define G3_W_BYTES (G3_BN * G3_BK / 4)
+#define G3_STAGE_BYTES (G3_A_BYTES + G3_W_BYTES)
+
+typedef const __attribute__((address_space(1))) void* bl_gptr;
+typedef __attribute__((address_space(3))) void* bl_lptr;
+
+/* s_waitcnt vmcnt(n) only (n < 16): expcnt = 7, lgkmcnt = 15 left open */
+#define BL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+
+template <int WM, int WN, int DBG>
+__global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
+                                                                const int8_t* __restrict__ q,
+                                                                const int32_t* __restrict__ rowsum,
+                                                                const float* __restrict__ beta,
+                                                                const float* __restrict__ scale, int M, int N,
+                                                                int K, int tiles_m, int tiles_n,
+                                                                int32_t* __restrict__ acc, float* __restrict__ y) {
+    constexpr int NW = WM * WN, THREADS = NW * 64;
+    constexpr int MI = G3_BM / WM / 32, NI = G3_BN / WN / 32;
+    constexpr int A_LOADS = G3_A_BYTES / 16 / THREADS;      /* direct loads per thread and stage */
+    constexpr int W_LOADS = G3_W_BYTES / 16 / THREADS;
+    constexpr int LOADS = A_LOADS + W_LOADS;
+    static_assert(LOADS < 16, "vmcnt immediate assumes a 4-bit count");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    /* XCD-aware tile id: workgroup L runs on XCD L%8 */
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (tile >= total) return;
+    const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+    const int m0 = tm * G3_BM, n0 = tn * G3_BN;
+    const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
+    const int kb = K / 4;
+
+    /* per-lane global sources of the direct loads */
+    const uint8_t* asrc[A_LOADS];
+    {
+        const int u = (lane & 7) ^ ((lane >> 3) & 7);
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j) {
+            int m = m0 + (j * NW + wave) * 8 + (lane >> 3);
+            if (m >= M) m = M - 1;
+            asrc[j] = (const uint8_t*)q + (int64_t)m * K + u * 16;
+        }
+    }
+    const uint8_t* wsrc[W_LOADS];
+    {
+        const int u = (lane & 1) ^ ((lane >> 3) & 1);
+#pragma unroll
+        for (int j = 0; j < W_LOADS; ++j) {
+            int n = n0 + (j * NW + wave) * 32 + (lane >> 1);
+            if (n >= N) n = N - 1;
+            wsrc[j] = packed + (int64_t)n * kb + u * 16;
+        }
+    }
+    auto issue = [&](int kk, int buf) {
+        uint8_t* st = smem + buf * G3_STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j)
+            __builtin_amdgcn_global_load_lds((bl_gptr)(asrc[j] + (int64_t)kk * G3_BK),
+                                             (bl_lptr)(st + (j * NW + wave) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < W_LOADS; ++j)
+            __builtin_amdgcn_global_load_lds((bl_gptr)(wsrc[j] + (int64_t)kk * (G3_BK / 4)),
+                                             (bl_lptr)(st + G3_A_BYTES + (j * NW + wave) * 1024), 16, 0, 0);
+    };
+
+    bl_v16i C[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) C[mi][ni][v] = 0;
+
+    /* per-lane LDS read offsets (bytes) inside a stage */
+    const int a_row_off = (wm0 + l32) * G3_BK;
+    const int a_swz = l32 & 7;
+    const int w_off = G3_A_BYTES + ((wn0 + l32) * 2 + (h ^ ((l32 >> 2) & 1))) * 16;
+
+    const int steps = K / G3_BK;
+    issue(0, 0);
+    if (steps > 1) issue(1, 1);
+    for (int kk = 0; kk < steps; ++kk) {
+        if (!(DBG & 2)) {
+            if (kk + 1 < steps) BL_WAIT_VM(LOADS);
+            else BL_WAIT_VM(0);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        if (!(DBG & 1) && kk + 2 < steps) issue(kk + 2, (kk + 2) % G3_STAGES);
+        if (DBG & 4) continue;
+        const uint8_t* st = smem + (kk % G3_STAGES) * G3_STAGE_BYTES;
+        if (NW == 8) {
+            /* Two waves share a SIMD.  A wave's own VALU and MFMA instructions do
+             * not overlap, but one wave's MFMAs run while the other unpacks and
+             * reads LDS.  So each half k step is three pinned phases - LDS reads,
+             * unpack, a solid block of MFMAs - and the two waves of a SIMD fall
+             * into opposite phases by themselves. */
+            bl_v4i wq[NI];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) wq[ni] = *(const bl_v4i*)(st + w_off + ni * 32 * 32);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                bl_v4i a[2][MI], bop[2][NI];
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    const int unit = ((4 * h + half * 2 + k2) ^ a_swz) * 16;
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+                        a[k2][mi] = *(const bl_v4i*)(st + a_row_off + mi * 32 * G3_BK + unit);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) bop[k2][ni] = bl_unpack16((uint32_t)wq[ni][half * 2 + k2]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi)
+                            C[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[k2][mi], bop[k2][ni], C[mi][ni], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            /* one wave per SIMD: operands of sub-step ks+1 are fetched while ks multiplies */
+            bl_v4i wq[NI], a[2][MI];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) wq[ni] = *(const bl_v4i*)(st + w_off + ni * 32 * 32);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                a[0][mi] = *(const bl_v4i*)(st + a_row_off + mi * 32 * G3_BK + (((4 * h) ^ a_swz) * 16));
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < 3) {
+                    const int unit = ((4 * h + ks + 1) ^ a_swz) * 16;
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+                        a[(ks + 1) & 1][mi] = *(const bl_v4i*)(st + a_row_off + mi * 32 * G3_BK + unit);
+                }
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const bl_v4i bop = bl_unpack16((uint32_t)wq[ni][ks]);
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+                        C[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][mi], bop, C[mi][ni], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    /* Epilogue.  The per-row terms go through LDS once (the stages are free now):
+     * a load per output row inside the store loop would serialise on latency. */
+    bl_mfma_fence();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    int* rs_s = (int*)smem;
+    float* cf_s = (float*)(smem + G3_BM * 4);
+    if (tid < G3_BM) {
+        const int m = m0 + tid;
+        rs_s[tid] = m < M ? rowsum[m] : 0;
+        cf_s[tid] = (y && m < M) ? *beta * scale[m] : 0.0f;
+    }
+    __syncthreads();
+    if (DBG & 8) {   /* timing experiment: keep the accumulators alive, write almost nothing */
+        int sum = 0;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += C[mi][ni][v];
+        if (sum == 0x7fffffff) y[0] = 1.0f;
+        return;
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int ml = wm0 + mi * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+            const int m = m0 + ml;
+            if (m < M) {
+                const int rs = rs_s[ml];
+                const float c = cf_s[ml];
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int n = n0 + wn0 + ni * 32 + l32;
+                    if (n < N) {
+                        const int val = C[mi][ni][v] - rs;
+                        if (acc) acc[(int64_t)m * N + n] = val;
+                        if (y) y[(int64_t)m * N + n] = (float)val * c;
+                    }
+                }
+            }
+        }
+}
+
+template <int WM, int WN, int DBG>
+static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, const int8_t* q, const float* scale,
+                                  const int32_t* rowsum, int M, int N, int K, int32_t* acc, float* y,
+                                  hipStream_t st) {
+    constexpr int lds = G3_STAGES * G3_STAGE_BYTES;
+    auto kern = bl_gemm_tile256<WM, WN, DBG>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return BL_ERR_HIP;
+        attr_set = true;
+    }
+    const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + G3_BN - 1) / G3_BN;
+    const int total = tiles_m * tiles_n;
+    const int blocks = ((total + 7) / 8) * 8;
+    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, acc, y);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+/* variant: 0 = 2x2 waves, 1 = 2x4 waves, 2 = 4x2 waves; dbg selects timing experiments */
+static bl_status launch_tile256(int variant, const uint8_t* packed, const float* beta, const int8_t* q,
+                                const float* scale, const int32_t* rowsum, int M, int N, int K, int32_t* acc,
+                                float* y, hipStream_t st) {
+    const char* e = getenv("BL_GEMM_DBG");
+    const int dbg = e && *e ? atoi(e) : 0;
+#define BL_T256(WMv, WNv, D) launch_tile256_t<WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, acc, y, st)
+    if (variant == 1) return dbg == 8 ? BL_T256(2, 4, 8) : dbg == 11 ? BL_T256(2, 4, 11) : BL_T256(2, 4, 0);
+    if (variant == 2) return dbg == 8 ? BL_T256(4, 2, 8) : dbg == 11 ? BL_T256(4, 2, 11) : BL_T256(4, 2, 0);
+    return dbg == 8 ? BL_T256(2, 2, 8) : dbg == 11 ? BL_T256(2, 2, 11) : BL_T256(2, 2, 0);
+#undef BL_T256
 }
 
 /* rowsum[m] = sum_k q[m][k]; one wave per row. */
@@ -157,15 +497,22 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
         bl_rowsum_kernel<<<(unsigned)((M + 3) / 4), 256, 0, st>>>(q, (int)M, (int)K, rs);
         rowsum = rs;
     }
-    constexpr int BM = 128, BN = 128;
-    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-    if (layout == 0)
-        bl_gemm_mfma<BM, BN, 0><<<grid, GEMM_THREADS, 0, st>>>(packed, q, rowsum, beta, scale, (int)M, (int)N,
-                                                               (int)K, acc, y);
-    else
-        bl_gemm_mfma<BM, BN, 1><<<grid, GEMM_THREADS, 0, st>>>(packed, q, rowsum, beta, scale, (int)M, (int)N,
-                                                               (int)K, acc, y);
-    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+    /* Tile choice.  Measured on MI355X at M = 2048: 128x128 tiles with k step
+     * 128 (three workgroups per CU) win on every 2B-layer shape; the 256x256
+     * direct-to-LDS kernel ties on the widest (N = 13824).  BL_GEMM_TILE
+     * overrides for experiments: 0 = 128x128x64, 5 = 128x128x128,
+     * 6/7/8 = 256x256x128 with 2x2 / 2x4 / 4x2 waves. */
+    const char* e = getenv("BL_GEMM_TILE");
+    const int m = (int)M, n = (int)N, k = (int)K;
+    int tile = e && *e ? atoi(e) : -1;
+    if (tile < 0) tile = (k % 128 == 0) ? 5 : 0;
+    if (tile >= 6 && tile <= 8 && (layout != 1 || k % G3_BK)) tile = (k % 128 == 0) ? 5 : 0;
+    if (tile == 5 && k % 128) tile = 0;
+    if (tile >= 6 && tile <= 8)
+        return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, acc, y, st);
+    if (tile == 5)
+        return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, acc, y, st);
+    return launch_gemm<128, 128, 64, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, acc, y, st);
 }
 
 extern "C" bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout, const int8_t* q,

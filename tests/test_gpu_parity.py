@@ -231,3 +231,73 @@ def test_whole_layer_through_the_abi(bl):
     assert np.array_equal(q.cpu().numpy(), c.q) and np.array_equal(scale.cpu().numpy(), c.scale)
     assert np.array_equal(acc.cpu().numpy(), c.acc)
     assert_y_close(y.cpu().numpy(), c.y)
+
+
+# ------------------------------------------------ fused and grouped decode
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("M", [1, 3, 4])
+@pytest.mark.parametrize("name", ["o", "down", "small"])
+def test_fused_decode_matches_oracle(bl, layout, M, name):
+    N, K = (52, 320) if name == "small" else synth.LAYER_SHAPES[name]
+    c = Case(51, M, N, K, matrix=3 if name == "down" else 1, relu2=(name == "down"))
+    packed = to_dev(c.packed(layout))
+    beta = to_dev(np.array([c.beta], dtype=np.float32))
+    acc, y, q, scale = bl.bl_bitlinear_decode(packed, beta, layout, to_dev(c.X), N, want_acc=True, want_q=True)
+    _sync()
+    assert np.array_equal(q.cpu().numpy(), c.q)
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), c.scale.view(np.uint32))
+    assert np.array_equal(acc.cpu().numpy(), c.acc)
+    assert_y_close(y.cpu().numpy(), c.y)
+
+
+def test_fused_decode_zero_and_tiny_rows(bl):
+    N, K = 64, 256
+    Wt = synth.uniform_i8(52, (N, K), -1, 1)
+    rows = np.zeros((3, K), dtype=np.float32)
+    rows[1, :] = 3.0e-6
+    rows[2, :5] = [2, 1, 0.5, -1, 0.25]
+    X = oracle.f32_to_bf16(rows)
+    ref = oracle.bitlinear(X, Wt, np.float32(0.5))
+    packed = to_dev(oracle.pack(Wt, 1))
+    beta = to_dev(np.array([0.5], dtype=np.float32))
+    acc, y, q, scale = bl.bl_bitlinear_decode(packed, beta, 1, to_dev(X), N, want_acc=True, want_q=True)
+    _sync()
+    assert np.array_equal(q.cpu().numpy(), ref["q"]) and np.array_equal(scale.cpu().numpy(), ref["scale"])
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    assert_y_close(y.cpu().numpy(), ref["y"])
+
+
+@pytest.mark.parametrize("M", [1, 4])
+@pytest.mark.parametrize("fused", [False, True])
+def test_grouped_decode_whole_layer(bl, M, fused):
+    """The four shapes of one layer in ONE launch equal four oracle products."""
+    cases, items, keep = [], [], []
+    for name in ["qkv", "o", "gate_up", "down"]:
+        N, K = synth.LAYER_SHAPES[name]
+        c = Case(0, M, N, K, layer=1, matrix=name, relu2=(name == "down"))
+        it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=N, K=K,
+                  acc=torch.empty((M, N), dtype=torch.int32, device="cuda:0"),
+                  y=torch.empty((M, N), dtype=torch.float32, device="cuda:0"))
+        if fused:
+            it["X"] = to_dev(c.X)
+        else:
+            it.update(q=to_dev(c.q), scale=to_dev(c.scale), rowsum=to_dev(c.rowsum))
+        cases.append(c)
+        items.append(it)
+    descs = bl.make_decode_descs(items)
+    bl.bl_bitlinear_decode_group(descs, 1, M)
+    _sync()
+    for c, it in zip(cases, items):
+        assert np.array_equal(it["acc"].cpu().numpy(), c.acc)
+        assert_y_close(it["y"].cpu().numpy(), c.y)
+
+
+def test_fused_fixed_scale(bl):
+    c = Case(53, 2, 128, 256)
+    it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=c.N, K=c.K,
+              X=to_dev(c.X), y=torch.empty((2, c.N), dtype=torch.float32, device="cuda:0"),
+              fixed_scale=float(np.float32(1.0) / np.float32(127.0)))
+    bl.bl_bitlinear_decode_group(bl.make_decode_descs([it]), 1, 2)
+    _sync()
+    unit = np.full(2, np.float32(1.0) / np.float32(127.0), dtype=np.float32)
+    assert_y_close(it["y"].cpu().numpy(), oracle.rescale(c.acc, c.beta, unit))
