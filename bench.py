@@ -144,6 +144,8 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--prefill-m", type=int, default=2048)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -252,6 +254,14 @@ def main():
                      "avg_launch_us": round(gemv_avg_s * 1e6, 3)},
         "decode_alternatives": alt,
     }
+
+    if args.calibrate_copy:
+        ca = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        cb = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        for _ in range(5):
+            cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
 
     # ------------------------------------------------------- prefill, M=2048
     if not args.no_prefill:

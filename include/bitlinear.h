@@ -135,7 +135,7 @@ bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout,
                          int64_t M, int64_t N, int64_t K,
                          int32_t* acc, float* y, void* workspace, bl_stream s);
 
-/* Fused BitLinear for decode, 1 <= M <= 4, K <= 8192: the per-token absmax
+/* Fused BitLinear for decode, 1 <= M <= 16, K <= 8192, M*(K+16) <= 96 KiB: the per-token absmax
  * int8 quantiser (Section 2) runs inside the product kernel (Section 5.1), so
  * one launch takes bf16 activations to fp32 outputs.  Same arithmetic, bit for
  * bit, as bl_quant_act_int8 followed by bl_gemv_w158a8.
@@ -147,11 +147,36 @@ bl_status bl_bitlinear_decode(const uint8_t* packed, const float* beta, int layo
                               const uint16_t* X, int64_t M, int64_t N, int64_t K,
                               int32_t* acc, float* y, int8_t* q_out, float* scale_out, bl_stream s);
 
-/* One decode product of a group.  Give either X (bf16, fused quantiser) or
- * q (+ scale if y is wanted, + optional rowsum).  All pointers are device
- * pointers; the descriptor array itself is HOST memory, read during the call.
- * fixed_scale > 0 (fused path only) replaces absmax/127 in the rescale, i.e.
- * the layer then acts on x/absmax (a normalised input); 0 = normal. */
+/* Fused producer: the elementwise step that yields the bf16 input X[m][k] of a
+ * BitLinear, evaluated inside the kernel that quantises it (no bf16 tensor in
+ * HBM).  Each kind is exact elementwise fp32 work, then round-to-nearest-even
+ * narrowing to bf16; the quantiser then runs on those bf16 values as usual.
+ *   BL_PROD_BF16       X = in0 (bf16 [M][K]).
+ *   BL_PROD_F32        X = bf16(in0)                      in0 fp32 [M][K].
+ *   BL_PROD_ATTN_V     context-length-1 attention over a fused QKV row
+ *                      in0 fp32 [M][(n_q+2*n_kv)*head_dim] = [Q | K | V]:
+ *                      X[m][h*head_dim+d] = bf16(V[m][h/(n_q/n_kv)][d]); K = n_q*head_dim.
+ *   BL_PROD_RESIDUAL   t = in0 + in1 (fp32 [M][K] each), X = bf16(t); if aux_out
+ *                      is given, t is also stored there (fp32 [M][K]).
+ *   BL_PROD_RELU2_GATE in0 fp32 [M][2K] = [g | u]: X = bf16((max(g,0)*max(g,0))*u)
+ *                      (the squared-ReLU gated FFN activation, Section 2).
+ * All pointers are device pointers, 16-byte aligned. */
+enum { BL_PROD_BF16 = 0, BL_PROD_F32 = 1, BL_PROD_ATTN_V = 2, BL_PROD_RESIDUAL = 3, BL_PROD_RELU2_GATE = 4 };
+typedef struct {
+    int kind;
+    const void* in0;
+    const float* in1;
+    float* aux_out;
+    int n_q, n_kv, head_dim;
+} bl_producer;
+
+/* One decode product of a group.  Give either X (bf16, fused quantiser), a
+ * producer (prod.in0 != NULL, fused producer + quantiser), or q (+ scale if y is
+ * wanted, + optional rowsum).  All pointers are device pointers; the descriptor
+ * array itself is HOST memory, read during the call.
+ * fixed_scale > 0 (fused paths only) replaces absmax/127 in the rescale, i.e.
+ * the layer then acts on x/absmax (a normalised input); 0 = normal.
+ * residual (fp32 [M][N] or NULL): y = residual + acc*(beta*scale), one fp32 add. */
 typedef struct {
     const uint8_t* packed;
     const float* beta;
@@ -165,6 +190,8 @@ typedef struct {
     int8_t* q_out;
     float* scale_out;
     float fixed_scale;
+    bl_producer prod;
+    const float* residual;
 } bl_decode_desc;
 
 /* Up to four INDEPENDENT decode products (same M <= 4, same layout, K <= 8192
@@ -172,6 +199,19 @@ typedef struct {
  * independent inputs.  Results are identical to separate calls; the point is
  * one launch and one continuous weight stream instead of four. */
 bl_status bl_bitlinear_decode_group(const bl_decode_desc* descs, int count, int layout, int64_t M, bl_stream s);
+
+/* Producer + per-token absmax int8 quantiser for prefill (Section 2): like
+ * bl_quant_act_int8, but the bf16 activations come from `prod` (HOST pointer to
+ * the descriptor; its tensors are device memory).  One workgroup per token. */
+bl_status bl_quant_act_ex(const bl_producer* prod, int64_t M, int64_t K,
+                          int8_t* q, float* scale, int32_t* rowsum, bl_stream s);
+
+/* bl_gemm_w158a8 with an optional residual (fp32 [M][N] or NULL) added in the
+ * epilogue: y = residual + acc*(beta*scale[m]), one fp32 add per element. */
+bl_status bl_gemm_w158a8_res(const uint8_t* packed, const float* beta, int layout,
+                             const int8_t* q, const float* scale, const int32_t* rowsum,
+                             int64_t M, int64_t N, int64_t K, const float* residual,
+                             int32_t* acc, float* y, void* workspace, bl_stream s);
 
 #ifdef __cplusplus
 }

@@ -60,6 +60,7 @@ float orc_absmean_beta(const float* W, int64_t N, int64_t K, double* mean64) {
  * (nearbyintf under the default rounding mode). */
 void orc_ternarize(const float* W, int64_t N, int64_t K, float beta, int8_t* Wt) {
     const float d = beta + 1e-5f;
+#pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < N * K; ++i) {
         const float r = W[i] / d;
         float t = std::nearbyintf(r);

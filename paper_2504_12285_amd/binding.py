@@ -29,14 +29,31 @@ SIGNATURES = {
     "bl_gemm_w158a8": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_bitlinear_decode": (_ci, [_vp, _vp, _ci, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "bl_bitlinear_decode_group": (_ci, [_vp, _ci, _ci, _i64, _vp]),
+    "bl_quant_act_ex": (_ci, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "bl_gemm_w158a8_res": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
 }
+
+BL_PROD_BF16, BL_PROD_F32, BL_PROD_ATTN_V, BL_PROD_RESIDUAL, BL_PROD_RELU2_GATE = 0, 1, 2, 3, 4
+
+
+class Producer(ctypes.Structure):
+    """Mirror of bl_producer."""
+    _fields_ = [("kind", _ci), ("in0", _vp), ("in1", _vp), ("aux_out", _vp),
+                ("n_q", _ci), ("n_kv", _ci), ("head_dim", _ci)]
+
+
+def make_producer(kind, in0, in1=None, aux_out=None, n_q=0, n_kv=0, head_dim=0):
+    p = Producer()
+    p.kind, p.in0, p.in1, p.aux_out = int(kind), _ptr(in0), _ptr(in1), _ptr(aux_out)
+    p.n_q, p.n_kv, p.head_dim = int(n_q), int(n_kv), int(head_dim)
+    return p
 
 
 class DecodeDesc(ctypes.Structure):
     """Mirror of bl_decode_desc."""
     _fields_ = [("packed", _vp), ("beta", _vp), ("X", _vp), ("q", _vp), ("scale", _vp), ("rowsum", _vp),
                 ("N", _i64), ("K", _i64), ("acc", _vp), ("y", _vp), ("q_out", _vp), ("scale_out", _vp),
-                ("fixed_scale", ctypes.c_float)]
+                ("fixed_scale", ctypes.c_float), ("prod", Producer), ("residual", _vp)]
 
 
 class BitLinearError(RuntimeError):
@@ -198,13 +215,47 @@ def make_decode_descs(items):
     Returns a ctypes array usable with bl_bitlinear_decode_group."""
     arr = (DecodeDesc * len(items))()
     for d, it in zip(arr, items):
-        for f in ("packed", "beta", "X", "q", "scale", "rowsum", "acc", "y", "q_out", "scale_out"):
+        for f in ("packed", "beta", "X", "q", "scale", "rowsum", "acc", "y", "q_out", "scale_out", "residual"):
             setattr(d, f, _ptr(it.get(f)))
         d.N, d.K = int(it["N"]), int(it["K"])
         d.fixed_scale = float(it.get("fixed_scale", 0.0))
+        if it.get("prod") is not None:
+            d.prod = it["prod"]
     return arr
 
 
 def bl_bitlinear_decode_group(descs, layout, M):
     """descs: ctypes array from make_decode_descs (host memory)."""
     _check(load().bl_bitlinear_decode_group(descs, len(descs), layout, M, _stream()), "bl_bitlinear_decode_group")
+
+
+def bl_quant_act_ex(prod, M, K, device, want_rowsum=True, q=None, scale=None, rowsum=None):
+    """Producer + quantiser (prefill side).  prod: Producer from make_producer.
+    Returns (q int8 [M][K], scale fp32 [M], rowsum int32 [M] or None)."""
+    import torch
+    if q is None:
+        q = torch.empty((M, K), dtype=torch.int8, device=device)
+    if scale is None:
+        scale = torch.empty(M, dtype=torch.float32, device=device)
+    if rowsum is None and want_rowsum:
+        rowsum = torch.empty(M, dtype=torch.int32, device=device)
+    _check(load().bl_quant_act_ex(ctypes.byref(prod), M, K, _ptr(q), _ptr(scale), _ptr(rowsum), _stream()),
+           "bl_quant_act_ex")
+    return q, scale, rowsum
+
+
+def bl_gemm_w158a8_res(packed, beta, layout, q, scale, rowsum, N, residual, want_acc=False, want_y=True,
+                       acc=None, y=None, workspace=None):
+    """Prefill product with a residual added in the epilogue.  Returns (acc, y)."""
+    import torch
+    M, K = q.shape
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=q.device)
+    if want_y and y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=q.device)
+    if workspace is None and rowsum is None:
+        workspace = _workspace(bl_workspace_bytes(BL_OP_GEMM, M, N, K), q.device)
+    _check(load().bl_gemm_w158a8_res(_ptr(packed), _ptr(beta), layout, _ptr(q), _ptr(scale), _ptr(rowsum), M, N, K,
+                                     _ptr(residual), _ptr(acc), _ptr(y), _ptr(workspace), _stream()),
+           "bl_gemm_w158a8_res")
+    return acc, y

@@ -39,6 +39,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void bl_gemm_mfma(const uint8_t* __re
                                                               const int32_t* __restrict__ rowsum,
                                                               const float* __restrict__ beta,
                                                               const float* __restrict__ scale, int M, int N, int K,
+                                                              const float* __restrict__ residual,
                                                               int32_t* __restrict__ acc, float* __restrict__ y) {
     constexpr int WGN = 4 / WGM;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
@@ -174,7 +175,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void bl_gemm_mfma(const uint8_t* __re
                     if (n < N) {
                         const int val = C[mi][ni][v] - rs;
                         if (acc) acc[(int64_t)m * N + n] = val;
-                        if (y) y[(int64_t)m * N + n] = (float)val * c;
+                        if (y) {
+                            const float t = (float)val * c;
+                            y[(int64_t)m * N + n] = residual ? residual[(int64_t)m * N + n] + t : t;
+                        }
                     }
                 }
             }
@@ -183,8 +187,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void bl_gemm_mfma(const uint8_t* __re
 
 template <int BM, int BN, int BK, int WGM>
 static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
-                             const float* scale, const int32_t* rowsum, int M, int N, int K, int32_t* acc,
-                             float* y, hipStream_t st) {
+                             const float* scale, const int32_t* rowsum, int M, int N, int K,
+                             const float* residual, int32_t* acc, float* y, hipStream_t st) {
     constexpr size_t lds = 2 * (size_t)(BM * (BK + GEMM_PAD) + BN * (BK / 16 + 1) * 4);
     dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     auto k0 = bl_gemm_mfma<BM, BN, BK, WGM, 0>;
@@ -200,7 +204,7 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
             done = true;
         }
     }
-    kern<<<grid, GEMM_THREADS, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, acc, y);
+    kern<<<grid, GEMM_THREADS, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, residual, acc, y);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
@@ -246,6 +250,7 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                                                                 const float* __restrict__ beta,
                                                                 const float* __restrict__ scale, int M, int N,
                                                                 int K, int tiles_m, int tiles_n,
+                                                                const float* __restrict__ residual,
                                                                 int32_t* __restrict__ acc, float* __restrict__ y) {
     constexpr int NW = WM * WN, THREADS = NW * 64;
     constexpr int MI = G3_BM / WM / 32, NI = G3_BN / WN / 32;
@@ -428,7 +433,10 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                     if (n < N) {
                         const int val = C[mi][ni][v] - rs;
                         if (acc) acc[(int64_t)m * N + n] = val;
-                        if (y) y[(int64_t)m * N + n] = (float)val * c;
+                        if (y) {
+                            const float t = (float)val * c;
+                            y[(int64_t)m * N + n] = residual ? residual[(int64_t)m * N + n] + t : t;
+                        }
                     }
                 }
             }
@@ -437,8 +445,8 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
 
 template <int WM, int WN, int DBG>
 static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, const int8_t* q, const float* scale,
-                                  const int32_t* rowsum, int M, int N, int K, int32_t* acc, float* y,
-                                  hipStream_t st) {
+                                  const int32_t* rowsum, int M, int N, int K, const float* residual,
+                                  int32_t* acc, float* y, hipStream_t st) {
     constexpr int lds = G3_STAGES * G3_STAGE_BYTES;
     auto kern = bl_gemm_tile256<WM, WN, DBG>;
     static bool attr_set = false;
@@ -450,17 +458,18 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + G3_BN - 1) / G3_BN;
     const int total = tiles_m * tiles_n;
     const int blocks = ((total + 7) / 8) * 8;
-    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, acc, y);
+    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, residual,
+                                            acc, y);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
 /* variant: 0 = 2x2 waves, 1 = 2x4 waves, 2 = 4x2 waves; dbg selects timing experiments */
 static bl_status launch_tile256(int variant, const uint8_t* packed, const float* beta, const int8_t* q,
-                                const float* scale, const int32_t* rowsum, int M, int N, int K, int32_t* acc,
-                                float* y, hipStream_t st) {
+                                const float* scale, const int32_t* rowsum, int M, int N, int K,
+                                const float* residual, int32_t* acc, float* y, hipStream_t st) {
     const char* e = getenv("BL_GEMM_DBG");
     const int dbg = e && *e ? atoi(e) : 0;
-#define BL_T256(WMv, WNv, D) launch_tile256_t<WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, acc, y, st)
+#define BL_T256(WMv, WNv, D) launch_tile256_t<WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
     if (variant == 1) return dbg == 8 ? BL_T256(2, 4, 8) : dbg == 11 ? BL_T256(2, 4, 11) : BL_T256(2, 4, 0);
     if (variant == 2) return dbg == 8 ? BL_T256(4, 2, 8) : dbg == 11 ? BL_T256(4, 2, 11) : BL_T256(4, 2, 0);
     return dbg == 8 ? BL_T256(2, 2, 8) : dbg == 11 ? BL_T256(2, 2, 11) : BL_T256(2, 2, 0);
@@ -489,7 +498,7 @@ __global__ __launch_bounds__(256) void bl_rowsum_kernel(const int8_t* __restrict
 /* Arguments already validated by the public entry points. */
 bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
                            const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
-                           int32_t* acc, float* y, void* workspace, hipStream_t st) {
+                           const float* residual, int32_t* acc, float* y, void* workspace, hipStream_t st) {
     if (!rowsum) {
         if (!workspace) return BL_ERR_WORKSPACE;
         if (!bl_aligned(workspace, 4)) return BL_ERR_ALIGN;
@@ -509,22 +518,30 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
     if (tile >= 6 && tile <= 8 && (layout != 1 || k % G3_BK)) tile = (k % 128 == 0) ? 5 : 0;
     if (tile == 5 && k % 128) tile = 0;
     if (tile >= 6 && tile <= 8)
-        return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, acc, y, st);
+        return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
     if (tile == 5)
-        return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, acc, y, st);
-    return launch_gemm<128, 128, 64, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, acc, y, st);
+        return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
+    return launch_gemm<128, 128, 64, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
 }
 
-extern "C" bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
-                                    const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
-                                    int32_t* acc, float* y, void* workspace, bl_stream s) {
+extern "C" bl_status bl_gemm_w158a8_res(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
+                                        const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
+                                        const float* residual, int32_t* acc, float* y, void* workspace,
+                                        bl_stream s) {
     if (!packed || !beta || !q) return BL_ERR_NULL;
     if (!acc && !y) return BL_ERR_NULL;
     if (y && !scale) return BL_ERR_NULL;
     if (M < 1 || M > BL_MAX_DIM || !bl_shape_ok(N, K)) return BL_ERR_SHAPE;
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(packed, 16) || !bl_aligned(q, 16) || !bl_aligned(acc, 4) || !bl_aligned(y, 4) ||
-        !bl_aligned(scale, 4) || !bl_aligned(beta, 4) || !bl_aligned(rowsum, 4))
+        !bl_aligned(scale, 4) || !bl_aligned(beta, 4) || !bl_aligned(rowsum, 4) || !bl_aligned(residual, 4))
         return BL_ERR_ALIGN;
-    return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, acc, y, workspace, (hipStream_t)s);
+    return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, residual, acc, y, workspace,
+                            (hipStream_t)s);
+}
+
+extern "C" bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
+                                    const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
+                                    int32_t* acc, float* y, void* workspace, bl_stream s) {
+    return bl_gemm_w158a8_res(packed, beta, layout, q, scale, rowsum, M, N, K, nullptr, acc, y, workspace, s);
 }

@@ -15,12 +15,15 @@
 
 #include "bl_device.h"
 #include "bl_host.h"
+#include "bl_producer.h"
 
 /* One decode product: everything a workgroup needs to know about it. */
 struct bl_gemv_prob {
     const bl_v4i* packed;     /* N x K/64 units of 16 bytes                          */
     const int8_t* q;          /* [M][K] int8, or NULL when x is given               */
-    const uint16_t* x;        /* [M][K] bf16: quantise on the fly (fused producer)  */
+    bl_prod_dev prod;         /* fused paths: where the bf16 activations come from  */
+    int fused;                /* 1: quantise prod's output on the fly; 0: use q     */
+    const float* residual;    /* [M][N] or NULL: added to y in the epilogue         */
     const float* beta;
     const float* scale;       /* [M] input scale (q path; may be NULL if y == NULL) */
     const int32_t* rowsum;    /* [M] or NULL                                        */
@@ -54,38 +57,8 @@ __device__ __forceinline__ void bl_put16(int* __restrict__ Qm, int c16, int layo
     dst[12] = (int)a3;
 }
 
-__device__ __forceinline__ int bl_sum16(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3) {
-    int part = __builtin_amdgcn_sdot4((int)a0, 0x01010101, 0, false);
-    part = __builtin_amdgcn_sdot4((int)a1, 0x01010101, part, false);
-    part = __builtin_amdgcn_sdot4((int)a2, 0x01010101, part, false);
-    return __builtin_amdgcn_sdot4((int)a3, 0x01010101, part, false);
-}
 
-/* Quantise 8 bf16 (one uint4) to two dwords of int8. */
-__device__ __forceinline__ void bl_quant8_words(const uint4 v, float inv, uint32_t& lo, uint32_t& hi) {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[2] = {0u, 0u};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t hbits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
-        float r = rintf(bl_bf16_to_f32(hbits) * inv);
-        r = fminf(fmaxf(r, -127.0f), 127.0f);
-        o[j >> 2] |= ((uint32_t)(int)r & 0xFFu) << (8 * (j & 3));
-    }
-    lo = o[0];
-    hi = o[1];
-}
 
-__device__ __forceinline__ float bl_absmax8_bf16(const uint4 v) {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    float m = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        m = fmaxf(m, fabsf(bl_bf16_to_f32(w[j] & 0xFFFFu)));
-        m = fmaxf(m, fabsf(bl_bf16_to_f32(w[j] >> 16)));
-    }
-    return m;
-}
 
 /* One k chunk of the VALU path: the four bit-pair levels of the four packed
  * words against the staged activation dwords of one token.  Levels are
@@ -136,16 +109,18 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     const int groups = K / 16;
     uint4 xv[4];
     uint4 qv = make_uint4(0, 0, 0, 0);
-    if (P.x) {
+    const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16;
+    const bool first_block = blockIdx.x == (unsigned)P.block0;
+    if (pre_bf16) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int u = tid + j * 256;
             if (u < groups) {
-                xv[2 * j] = ((const uint4*)P.x)[2 * u];
-                xv[2 * j + 1] = ((const uint4*)P.x)[2 * u + 1];
+                xv[2 * j] = ((const uint4*)P.prod.in0)[2 * u];
+                xv[2 * j + 1] = ((const uint4*)P.prod.in0)[2 * u + 1];
             }
         }
-    } else if (tid < M * groups) {
+    } else if (!P.fused && tid < M * groups) {
         qv = *(const uint4*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
     }
 
@@ -164,33 +139,32 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     int* sq = Q + M * (K / 4);          /* M row sums                        */
     float* fs = (float*)(sq + M);       /* M scales, then 4 per-wave scratch */
     int* red = (int*)(fs + M + 4);      /* 4 waves * R * M partial sums      */
-    if (P.x) {
+    if (P.fused) {
         /* fused producer: absmax + int8 quantisation of the bf16 row, per token.
          * Each thread keeps its (at most two) 16-element groups in registers. */
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
-            const uint4* xr = (const uint4*)(P.x + (int64_t)m * K);
             float mx = 0.0f;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int u = tid + j * 256;
                 if (u < groups) {
-                    if (m > 0) {
-                        xv[2 * j] = xr[2 * u];
-                        xv[2 * j + 1] = xr[2 * u + 1];
-                    }
+                    if (m > 0 || !pre_bf16) bl_produce16(P.prod, m, u, K, first_block, xv[2 * j], xv[2 * j + 1]);
                     mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }
-            for (int u = tid + 512; u < groups; u += 256)
-                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xr[2 * u]), bl_absmax8_bf16(xr[2 * u + 1])));
+            for (int u = tid + 512; u < groups; u += 256) {
+                uint4 lo, hi;
+                bl_produce16(P.prod, m, u, K, false, lo, hi);
+                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+            }
             mx = bl_wave_max(mx);
             if (lane == 0) fs[M + w] = mx;
             __syncthreads();
             const float gamma = fmaxf(fmaxf(fs[M], fs[M + 1]), fmaxf(fs[M + 2], fs[M + 3]));
             const float gg = fmaxf(gamma, 1e-5f);
             const float inv = bl_div_rn(127.0f, gg);
-            const bool emit = P.q_out && blockIdx.x == (unsigned)P.block0;
+            const bool emit = P.q_out && first_block;
             int part = 0;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -206,8 +180,10 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
             }
             for (int u = tid + 512; u < groups; u += 256) {
                 uint32_t a0, a1, a2, a3;
-                bl_quant8_words(xr[2 * u], inv, a0, a1);
-                bl_quant8_words(xr[2 * u + 1], inv, a2, a3);
+                uint4 lo, hi;
+                bl_produce16(P.prod, m, u, K, first_block, lo, hi);
+                bl_quant8_words(lo, inv, a0, a1);
+                bl_quant8_words(hi, inv, a2, a3);
                 part += bl_sum16(a0, a1, a2, a3);
                 if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
                 bl_put16(Q + m * (K / 4), u, P.layout, a0, a1, a2, a3);
@@ -219,7 +195,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
                 sq[m] = red[0] + red[1] + red[2] + red[3];
                 const float sc = bl_div_rn(gg, 127.0f);
                 fs[m] = P.fixed_scale > 0.0f ? P.fixed_scale : sc;
-                if (P.scale_out && blockIdx.x == (unsigned)P.block0) P.scale_out[m] = sc;
+                if (P.scale_out && first_block) P.scale_out[m] = sc;
             }
         }
         __syncthreads();
@@ -256,24 +232,36 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
 #pragma unroll
     for (int m = 0; m < M; ++m)
         v[m] = bl_group_sum<G>(A[m][0] + (A[m][1] >> 2) + ((A[m][2] + A[m][3]) >> 4));
+    /* Lanes 0..R-1 of the first wave of a row group write rows 0..R-1: one
+     * contiguous R*4-byte store per token instead of R scattered dwords. */
+    int o[M];
     if (ksplit > 1) {
         if (g == 0) {
 #pragma unroll
             for (int m = 0; m < M; ++m) red[(w * R + r) * M + m] = v[m];
         }
         __syncthreads();
-        if (kp == 0 && g == 0) {
+        if (kp == 0 && lane < R) {
 #pragma unroll
-            for (int m = 0; m < M; ++m)
-                for (int j = 1; j < ksplit; ++j) v[m] += red[((w + j) * R + r) * M + m];
+            for (int m = 0; m < M; ++m) {
+                o[m] = 0;
+                for (int j = 0; j < ksplit; ++j) o[m] += red[((w + j) * R + lane) * M + m];
+            }
         }
+    } else {
+#pragma unroll
+        for (int m = 0; m < M; ++m) o[m] = __shfl(v[m], (lane & (R - 1)) * G);
     }
-    if (kp == 0 && g == 0 && row_ok) {
+    const int n_out = ((int)blockIdx.x - P.block0) * rows_per_block + rg * R + lane;
+    if (kp == 0 && lane < R && n_out < N) {
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-            const int val = v[m] - sq[m];
-            if (P.acc) P.acc[(int64_t)m * N + n] = val;
-            if (P.y) P.y[(int64_t)m * N + n] = (float)val * (bt * fs[m]);
+            const int val = o[m] - sq[m];
+            if (P.acc) P.acc[(int64_t)m * N + n_out] = val;
+            if (P.y) {
+                const float t = (float)val * (bt * fs[m]);
+                P.y[(int64_t)m * N + n_out] = P.residual ? P.residual[(int64_t)m * N + n_out] + t : t;
+            }
         }
     }
 }
@@ -319,16 +307,18 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     /* 1. activation loads first (token 0 of the fused path, or the first q groups) */
     uint4 xv[4];
     uint4 qv = make_uint4(0, 0, 0, 0);
-    if (P.x) {
+    const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16;
+    const bool first_block = blockIdx.x == (unsigned)P.block0;
+    if (pre_bf16) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int u = tid + j * 256;
             if (u < groups) {
-                xv[2 * j] = ((const uint4*)P.x)[2 * u];
-                xv[2 * j + 1] = ((const uint4*)P.x)[2 * u + 1];
+                xv[2 * j] = ((const uint4*)P.prod.in0)[2 * u];
+                xv[2 * j + 1] = ((const uint4*)P.prod.in0)[2 * u + 1];
             }
         }
-    } else if (tid < M * groups) {
+    } else if (!P.fused && tid < M * groups) {
         qv = *(const uint4*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
     }
 
@@ -345,27 +335,23 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     }
 
     /* 3. stage the activations */
-    if (P.x) {
+    if (P.fused) {
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
-            const uint4* xr = (const uint4*)(P.x + (int64_t)m * K);
             float mx = 0.0f;
-            if (m > 0) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int u = tid + j * 256;
-                    if (u < groups) {
-                        xv[2 * j] = xr[2 * u];
-                        xv[2 * j + 1] = xr[2 * u + 1];
-                    }
+            for (int j = 0; j < 2; ++j) {
+                const int u = tid + j * 256;
+                if (u < groups) {
+                    if (m > 0 || !pre_bf16) bl_produce16(P.prod, m, u, K, first_block, xv[2 * j], xv[2 * j + 1]);
+                    mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                if (tid + j * 256 < groups)
-                    mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
-            for (int u = tid + 512; u < groups; u += 256)
-                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xr[2 * u]), bl_absmax8_bf16(xr[2 * u + 1])));
+            for (int u = tid + 512; u < groups; u += 256) {
+                uint4 lo, hi;
+                bl_produce16(P.prod, m, u, K, false, lo, hi);
+                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+            }
             mx = bl_wave_max(mx);
             if (m > 0) __syncthreads();                 /* previous token's fs[] readers are done */
             if (lane == 0) fs[w] = mx;
@@ -373,7 +359,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
             const float gg = fmaxf(gamma, 1e-5f);
             const float inv = bl_div_rn(127.0f, gg);
-            const bool emit = P.q_out && blockIdx.x == (unsigned)P.block0;
+            const bool emit = P.q_out && first_block;
             int* Qm = (int*)(Q + m * qstride);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -388,15 +374,17 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             }
             for (int u = tid + 512; u < groups; u += 256) {
                 uint32_t a0, a1, a2, a3;
-                bl_quant8_words(xr[2 * u], inv, a0, a1);
-                bl_quant8_words(xr[2 * u + 1], inv, a2, a3);
+                uint4 lo, hi;
+                bl_produce16(P.prod, m, u, K, first_block, lo, hi);
+                bl_quant8_words(lo, inv, a0, a1);
+                bl_quant8_words(hi, inv, a2, a3);
                 if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
                 bl_put16(Qm, u, P.layout, a0, a1, a2, a3);
             }
             if (tid == 0) {
                 const float sc = bl_div_rn(gg, 127.0f);
                 fscale[m] = P.fixed_scale > 0.0f ? P.fixed_scale : sc;
-                if (P.scale_out && blockIdx.x == (unsigned)P.block0) P.scale_out[m] = sc;
+                if (P.scale_out && first_block) P.scale_out[m] = sc;
             }
         }
     } else {
@@ -473,8 +461,9 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                     const int val = D[t][v] - (need_sum ? 0 : P.rowsum[tok]);
                     if (P.acc) P.acc[(int64_t)tok * N + n] = val;
                     if (P.y) {
-                        const float sc = P.x ? fscale[tok] : P.scale[tok];
-                        P.y[(int64_t)tok * N + n] = (float)val * (bt * sc);
+                        const float sc = P.fused ? fscale[tok] : P.scale[tok];
+                        const float t = (float)val * (bt * sc);
+                        P.y[(int64_t)tok * N + n] = P.residual ? P.residual[(int64_t)tok * N + n] + t : t;
                     }
                 }
             }
@@ -508,7 +497,7 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, int max
     const size_t lds = (size_t)M * (maxK + BL_MMA_PAD) + (size_t)(MT * 4 * 256 * 2 + 4 + 64) * 4;
     bool have_sums = true;   /* every product brings its own row sums */
     for (int i = 0; i < grp.count; ++i)
-        if (grp.p[i].x || !grp.p[i].rowsum) have_sums = false;
+        if (grp.p[i].fused || !grp.p[i].rowsum) have_sums = false;
     auto kern = have_sums ? bl_gemv_mma<L, MT, false> : bl_gemv_mma<L, MT, true>;
     if (lds > 160 * 1024) return BL_ERR_SHAPE;
     if (lds > 64 * 1024) {
@@ -581,7 +570,7 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
 
 bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
                            const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
-                           int32_t* acc, float* y, void* workspace, hipStream_t st);
+                           const float* residual, int32_t* acc, float* y, void* workspace, hipStream_t st);
 
 extern "C" bl_status bl_gemv_w158a8(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
                                     const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
@@ -596,26 +585,29 @@ extern "C" bl_status bl_gemv_w158a8(const uint8_t* packed, const float* beta, in
         return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
     if (K > 8192 || M * (K + BL_MMA_PAD) > 96 * 1024)
-        return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, acc, y, workspace, st);
+        return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, nullptr, acc, y, workspace, st);
 
     bl_gemv_group grp;
     grp.count = 1;
-    grp.p[0] = bl_gemv_prob{(const bl_v4i*)packed, q, nullptr, beta, scale, rowsum, acc, y, nullptr, nullptr,
-                            (int)N, (int)K, layout, 0, 1, 0.0f};
+    bl_gemv_prob& P0 = grp.p[0];
+    P0 = bl_gemv_prob{};
+    P0.packed = (const bl_v4i*)packed; P0.q = q; P0.beta = beta; P0.scale = scale; P0.rowsum = rowsum;
+    P0.acc = acc; P0.y = y; P0.N = (int)N; P0.K = (int)K; P0.layout = layout; P0.ksplit = 1;
     return bl_gemv_launch_group(grp, (int)M, st);
 }
 
 static bl_status check_decode_desc(const bl_decode_desc& d, int64_t M, int layout) {
     if (!d.packed || !d.beta) return BL_ERR_NULL;
-    if (!d.X && !d.q) return BL_ERR_NULL;
+    const bool fused = d.X || d.prod.in0;
+    if (!fused && !d.q) return BL_ERR_NULL;
     if (!d.acc && !d.y) return BL_ERR_NULL;
-    if (!d.X && d.y && !d.scale) return BL_ERR_NULL;
+    if (!fused && d.y && !d.scale) return BL_ERR_NULL;
     if (M < 1 || M > 16 || !bl_shape_ok(d.N, d.K) || d.K > 8192 || M * (d.K + BL_MMA_PAD) > 96 * 1024)
         return BL_ERR_SHAPE;
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
         !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||
-        !bl_aligned(d.rowsum, 4) || !bl_aligned(d.scale_out, 4))
+        !bl_aligned(d.rowsum, 4) || !bl_aligned(d.scale_out, 4) || !bl_aligned(d.residual, 4))
         return BL_ERR_ALIGN;
     return BL_OK;
 }
@@ -630,8 +622,14 @@ extern "C" bl_status bl_bitlinear_decode_group(const bl_decode_desc* descs, int 
         const bl_decode_desc& d = descs[i];
         const bl_status st = check_decode_desc(d, M, layout);
         if (st != BL_OK) return st;
-        grp.p[i] = bl_gemv_prob{(const bl_v4i*)d.packed, d.X ? nullptr : d.q, d.X, d.beta, d.scale, d.rowsum,
-                                d.acc, d.y, d.q_out, d.scale_out, (int)d.N, (int)d.K, layout, 0, 1, d.fixed_scale};
+        bl_gemv_prob& P = grp.p[i];
+        P = bl_gemv_prob{};
+        P.fused = (d.X || d.prod.in0) ? 1 : 0;
+        if (P.fused && !bl_make_prod(d.prod, d.X, d.K, &P.prod)) return BL_ERR_VALUE;
+        P.packed = (const bl_v4i*)d.packed; P.q = P.fused ? nullptr : d.q; P.beta = d.beta; P.scale = d.scale;
+        P.rowsum = d.rowsum; P.acc = d.acc; P.y = d.y; P.q_out = d.q_out; P.scale_out = d.scale_out;
+        P.N = (int)d.N; P.K = (int)d.K; P.layout = layout; P.ksplit = 1; P.fixed_scale = d.fixed_scale;
+        P.residual = d.residual;
     }
     return bl_gemv_launch_group(grp, (int)M, (hipStream_t)s);
 }

@@ -4,6 +4,7 @@
  * cache.  HBM-bound at prefill sizes, latency-bound at decode sizes. */
 #include "bl_device.h"
 #include "bl_host.h"
+#include "bl_producer.h"
 
 #define QUANT_THREADS 256
 
@@ -76,6 +77,87 @@ __global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows(const uint4* __re
             rowsum[m] = t;
         }
     }
+}
+
+/* Producer + quantiser: the bf16 row is produced on the fly (bl_produce16) and
+ * kept in registers between the absmax pass and the quantise pass (two
+ * 16-element groups per thread cover K <= 8192; longer rows are produced twice). */
+__global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows_ex(const bl_prod_dev pd, int K,
+                                                                   int8_t* __restrict__ q, float* __restrict__ scale,
+                                                                   int32_t* __restrict__ rowsum) {
+    __shared__ float smax[QUANT_THREADS / BL_WAVE];
+    __shared__ int ssum[QUANT_THREADS / BL_WAVE];
+    const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int groups = K / 16;
+    uint4 xv[4];
+    float mx = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int u = tid + j * QUANT_THREADS;
+        if (u < groups) {
+            bl_produce16(pd, m, u, K, true, xv[2 * j], xv[2 * j + 1]);
+            mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
+        }
+    }
+    for (int u = tid + 2 * QUANT_THREADS; u < groups; u += QUANT_THREADS) {
+        uint4 lo, hi;
+        bl_produce16(pd, m, u, K, true, lo, hi);
+        mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+    }
+    mx = bl_wave_max(mx);
+    if (lane == 0) smax[w] = mx;
+    __syncthreads();
+    float gamma = smax[0];
+#pragma unroll
+    for (int i = 1; i < QUANT_THREADS / BL_WAVE; ++i) gamma = fmaxf(gamma, smax[i]);
+    const float g = fmaxf(gamma, 1e-5f);
+    const float inv = bl_div_rn(127.0f, g);
+    int8_t* qo = q + (int64_t)m * K;
+    int sum = 0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int u = tid + j * QUANT_THREADS;
+        if (u < groups) {
+            uint32_t a0, a1, a2, a3;
+            bl_quant8_words(xv[2 * j], inv, a0, a1);
+            bl_quant8_words(xv[2 * j + 1], inv, a2, a3);
+            sum += bl_sum16(a0, a1, a2, a3);
+            *(uint4*)(qo + u * 16) = make_uint4(a0, a1, a2, a3);
+        }
+    }
+    for (int u = tid + 2 * QUANT_THREADS; u < groups; u += QUANT_THREADS) {
+        uint4 lo, hi;
+        uint32_t a0, a1, a2, a3;
+        bl_produce16(pd, m, u, K, false, lo, hi);
+        bl_quant8_words(lo, inv, a0, a1);
+        bl_quant8_words(hi, inv, a2, a3);
+        sum += bl_sum16(a0, a1, a2, a3);
+        *(uint4*)(qo + u * 16) = make_uint4(a0, a1, a2, a3);
+    }
+    sum = bl_wave_sum(sum);
+    if (lane == 0) ssum[w] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        scale[m] = bl_div_rn(g, 127.0f);
+        if (rowsum) {
+            int t = 0;
+#pragma unroll
+            for (int i = 0; i < QUANT_THREADS / BL_WAVE; ++i) t += ssum[i];
+            rowsum[m] = t;
+        }
+    }
+}
+
+extern "C" bl_status bl_quant_act_ex(const bl_producer* prod, int64_t M, int64_t K, int8_t* q, float* scale,
+                                     int32_t* rowsum, bl_stream s) {
+    if (!prod || !q || !scale) return BL_ERR_NULL;
+    if (M < 1 || M > BL_MAX_DIM || K < 64 || K % 64 != 0 || K > BL_MAX_DIM) return BL_ERR_SHAPE;
+    if (!bl_aligned(q, 16) || !bl_aligned(scale, 4) || !bl_aligned(rowsum, 4)) return BL_ERR_ALIGN;
+    bl_prod_dev pd;
+    if (!prod->in0) return BL_ERR_NULL;
+    if (!bl_make_prod(*prod, nullptr, K, &pd)) return BL_ERR_VALUE;
+    bl_quant_rows_ex<<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>(pd, (int)K, q, scale, rowsum);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
 extern "C" bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K, int8_t* q, float* scale,

@@ -1,0 +1,166 @@
+"""GPU parity of the fused producers and of the synthetic layer chain
+(benchmark config 4) against the CPU oracle."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from helpers import assert_y_close, to_dev
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+SHAPES = synth.LAYER_SHAPES
+
+
+@pytest.fixture(scope="module")
+def bl():
+    from paper_2504_12285_amd import binding
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def chain():
+    from paper_2504_12285_amd import chain as c
+    return c
+
+
+def _layer_weights(seed, layer):
+    """Oracle-side (Wt, beta) and latent W of the four matrices of one layer."""
+    out = {}
+    for name, (N, K) in SHAPES.items():
+        W = synth.latent_weights(seed, N, K, layer=layer, matrix=name)
+        beta, mean64 = oracle.absmean_beta(W, return_mean64=True)
+        assert oracle.beta_guard_ok(mean64)
+        out[name] = (oracle.ternarize(W, beta), beta, W)
+    return out
+
+
+def _to_gpu_weights(bl, ow, layout=1):
+    gw = {}
+    for name, (Wt, beta, W) in ow.items():
+        packed, b = bl.bl_pack_ternary(to_dev(W), layout)
+        gw[name] = (packed, b)
+    return gw
+
+
+# ------------------------------------------------------------------ producers
+@pytest.mark.parametrize("M", [1, 5])
+def test_producers_match_oracle_glue(bl, M):
+    rng = np.random.default_rng(7)
+    dev = "cuda:0"
+    x = (rng.standard_normal((M, 2560)) * 3).astype(np.float32)
+    o = rng.standard_normal((M, 2560)).astype(np.float32)
+    qkv = rng.standard_normal((M, 3840)).astype(np.float32)
+    gu = rng.standard_normal((M, 13824)).astype(np.float32)
+    gu[:, 5] = 0.0
+    # the descriptor holds raw pointers: keep the device tensors alive in `keep`
+    keep = dict(x=to_dev(x), qkv=to_dev(qkv), gu=to_dev(gu), xb=to_dev(oracle.f32_to_bf16(x)))
+    cases = [
+        (bl.make_producer(bl.BL_PROD_F32, keep["x"]), 2560, oracle.f32_to_bf16(x)),
+        (bl.make_producer(bl.BL_PROD_ATTN_V, keep["qkv"], n_q=20, n_kv=5, head_dim=128), 2560,
+         oracle.chain_attn_stub(qkv)),
+        (bl.make_producer(bl.BL_PROD_RELU2_GATE, keep["gu"]), 6912, oracle.chain_relu2_gate(gu)),
+        (bl.make_producer(bl.BL_PROD_BF16, keep["xb"]), 2560, oracle.f32_to_bf16(x)),
+    ]
+    for prod, K, want_bits in cases:
+        q_o, s_o, r_o = oracle.quant_act(want_bits)
+        q, s, r = bl.bl_quant_act_ex(prod, M, K, dev)
+        torch.cuda.synchronize()
+        assert np.array_equal(q.cpu().numpy(), q_o)
+        assert np.array_equal(s.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
+        assert np.array_equal(r.cpu().numpy(), r_o)
+    # residual: also stores the fp32 sum
+    xd, od = to_dev(x), to_dev(o)
+    h1 = torch.empty((M, 2560), dtype=torch.float32, device=dev)
+    q, s, r = bl.bl_quant_act_ex(bl.make_producer(bl.BL_PROD_RESIDUAL, xd, od, h1), M, 2560, dev)
+    torch.cuda.synchronize()
+    h1_o = oracle.chain_residual(x, o)
+    assert np.array_equal(h1.cpu().numpy().view(np.uint32), h1_o.view(np.uint32))
+    q_o, s_o, _ = oracle.quant_act(oracle.f32_to_bf16(h1_o))
+    assert np.array_equal(q.cpu().numpy(), q_o) and np.array_equal(s.cpu().numpy(), s_o)
+
+
+def test_bad_producer_is_rejected(bl):
+    x = torch.zeros((1, 2560), device="cuda:0")
+    with pytest.raises(bl.BitLinearError):
+        bl.bl_quant_act_ex(bl.make_producer(9, x), 1, 2560, "cuda:0")
+    with pytest.raises(bl.BitLinearError):   # head geometry does not give K
+        bl.bl_quant_act_ex(bl.make_producer(bl.BL_PROD_ATTN_V, x, n_q=20, n_kv=5, head_dim=64), 1, 2560, "cuda:0")
+    with pytest.raises(bl.BitLinearError):   # residual needs a second operand
+        bl.bl_quant_act_ex(bl.make_producer(bl.BL_PROD_RESIDUAL, x), 1, 2560, "cuda:0")
+
+
+# ---------------------------------------------------------------------- chain
+def _oracle_chain(x0, layers):
+    x = x0
+    traces = []
+    for ow in layers:
+        tr = []
+        x = oracle.chain_layer(x, {k: (v[0], v[1]) for k, v in ow.items()}, trace=tr)
+        traces.append(tr)
+    return x, traces
+
+
+def _compare_records(recs, traces, rows=None):
+    for lrec, ltr in zip(recs, traces):
+        for r, t in zip(lrec, ltr):
+            assert r["name"] == t["name"]
+            sel = slice(None) if rows is None else rows
+            assert np.array_equal(r["q"].cpu().numpy()[sel], t["q"]), ("q", t["name"])
+            assert np.array_equal(r["scale"].cpu().numpy()[sel], t["scale"]), ("scale", t["name"])
+            assert np.array_equal(r["acc"].cpu().numpy()[sel], t["acc"]), ("acc", t["name"])
+
+
+@pytest.mark.parametrize("mode,M", [("decode", 1), ("decode", 4), ("decode", 9), ("prefill", 4), ("prefill", 150)])
+def test_chain_two_layers(bl, chain, mode, M):
+    layers = [_layer_weights(3, l) for l in range(2)]
+    gws = [_to_gpu_weights(bl, ow) for ow in layers]
+    x0 = synth.bf16_bits_to_f32(synth.activations_bf16(3, M, 2560, layer=99))
+    want, traces = _oracle_chain(x0, layers)
+    recs = []
+    got = chain.run_chain(gws, 1, to_dev(x0), mode=mode, records=recs)
+    torch.cuda.synchronize()
+    _compare_records(recs, traces)
+    assert_y_close(got.cpu().numpy(), want)
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_stack_decode_and_prefill(bl, chain):
+    """30 layers of the 2B shapes.  Decode at M=1 is compared in full; prefill at
+    M=4096 runs in full on the GPU and is compared on sampled token rows (tokens
+    are independent in this chain, so the oracle runs just those rows)."""
+    n_layers, Mp = synth.N_LAYERS, 4096
+    sample = np.array([0, 1, 777, 2048, 4095])
+    x_dec = synth.bf16_bits_to_f32(synth.activations_bf16(0, 1, 2560, layer=100))
+    x_pre = synth.bf16_bits_to_f32(synth.activations_bf16(0, Mp, 2560, layer=101))
+    dev_dec, dev_pre = to_dev(x_dec), to_dev(x_pre)
+    o_dec, o_pre = x_dec, x_pre[sample]
+    Bd = chain.ChainBuffers(1, dev_dec.device)
+    Bp = chain.ChainBuffers(Mp, dev_pre.device)
+    for l in range(n_layers):
+        ow = _layer_weights(0, l)
+        gw = _to_gpu_weights(bl, ow)
+        if l == 0:
+            for name in SHAPES:
+                assert np.array_equal(gw[name][0].cpu().numpy(), oracle.pack(ow[name][0], 1))
+                assert gw[name][1].item() == float(ow[name][1])
+        wts = {k: (v[0], v[1]) for k, v in ow.items()}
+        tr_d, tr_p = [], []
+        o_dec = oracle.chain_layer(o_dec, wts, trace=tr_d)
+        o_pre = oracle.chain_layer(o_pre, wts, trace=tr_p)
+        rec_d, rec_p = [], []
+        out = chain.layer_decode(gw, 1, dev_dec, Bd, rec_d)
+        Bd.x_next, dev_dec = dev_dec, out
+        out = chain.layer_prefill(gw, 1, dev_pre, Bp, rec_p)
+        Bp.x_next, dev_pre = dev_pre, out
+        torch.cuda.synchronize()
+        _compare_records([rec_d], [tr_d])
+        _compare_records([rec_p], [tr_p], rows=sample)
+        assert_y_close(dev_dec.cpu().numpy(), o_dec)
+        assert_y_close(dev_pre.cpu().numpy()[sample], o_pre)
+        print("layer %d ok (|x| max %.3g)" % (l, float(np.abs(o_dec).max())), file=sys.stderr, flush=True)
+        del gw, ow, wts
