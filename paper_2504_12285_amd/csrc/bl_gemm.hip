@@ -229,13 +229,7 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * Workgroups are numbered so that the 32 that share an XCD (and its L2) at a
  * time form an 8 x 4 patch of tiles: 8 activation row tiles x 4 weight tiles.
  * Requires layout 1, K % 128 == 0. */
-#define G3_BM 256
-#define G3_BN 256
 #define G3_BK 128
-#define G3_STAGES 3
-#define G3_A_BYTES (G3_BM * G3_BK)
-#define G3_W_BYTES (G3_BN * G3_BK / 4)
-#define G3_STAGE_BYTES (G3_A_BYTES + G3_W_BYTES)
 
 typedef const __attribute__((address_space(1))) void* bl_gptr;
 typedef __attribute__((address_space(3))) void* bl_lptr;
@@ -243,7 +237,7 @@ typedef __attribute__((address_space(3))) void* bl_lptr;
 /* s_waitcnt vmcnt(n) only (n < 16): expcnt = 7, lgkmcnt = 15 left open */
 #define BL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
-template <int WM, int WN, int DBG>
+template <int BM, int BN, int STAGES, int WM, int WN, int DBG>
 __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
                                                                 const int32_t* __restrict__ rowsum,
@@ -253,7 +247,9 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                                                                 const float* __restrict__ residual,
                                                                 int32_t* __restrict__ acc, float* __restrict__ y) {
     constexpr int NW = WM * WN, THREADS = NW * 64;
-    constexpr int MI = G3_BM / WM / 32, NI = G3_BN / WN / 32;
+    constexpr int G3_BM = BM, G3_A_BYTES = BM * G3_BK;
+    constexpr int G3_W_BYTES = BN * G3_BK / 4, G3_STAGE_BYTES = G3_A_BYTES + G3_W_BYTES;
+    constexpr int MI = G3_BM / WM / 32, NI = BN / WN / 32;
     constexpr int A_LOADS = G3_A_BYTES / 16 / THREADS;      /* direct loads per thread and stage */
     constexpr int W_LOADS = G3_W_BYTES / 16 / THREADS;
     constexpr int LOADS = A_LOADS + W_LOADS;
@@ -268,7 +264,7 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (tile >= total) return;
     const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
-    const int m0 = tm * G3_BM, n0 = tn * G3_BN;
+    const int m0 = tm * G3_BM, n0 = tn * BN;
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
     const int kb = K / 4;
 
@@ -320,18 +316,19 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
 
     const int steps = K / G3_BK;
     issue(0, 0);
-    if (steps > 1) issue(1, 1);
+    if (STAGES > 2 && steps > 1) issue(1, 1);
     for (int kk = 0; kk < steps; ++kk) {
         if (!(DBG & 2)) {
-            if (kk + 1 < steps) BL_WAIT_VM(LOADS);
+            /* stage kk must have landed; with three stages the loads of stage kk+1 may stay in flight */
+            if (STAGES > 2 && kk + 1 < steps) BL_WAIT_VM(LOADS);
             else BL_WAIT_VM(0);
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
-        if (!(DBG & 1) && kk + 2 < steps) issue(kk + 2, (kk + 2) % G3_STAGES);
+        if (!(DBG & 1) && kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
         if (DBG & 4) continue;
-        const uint8_t* st = smem + (kk % G3_STAGES) * G3_STAGE_BYTES;
+        const uint8_t* st = smem + (kk % STAGES) * G3_STAGE_BYTES;
         if (NW == 8) {
             /* Two waves share a SIMD.  A wave's own VALU and MFMA instructions do
              * not overlap, but one wave's MFMAs run while the other unpacks and
@@ -401,7 +398,7 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     asm volatile("" ::: "memory");
     int* rs_s = (int*)smem;
     float* cf_s = (float*)(smem + G3_BM * 4);
-    if (tid < G3_BM) {
+    if (tid < G3_BM) {   /* THREADS >= BM for every instantiation */
         const int m = m0 + tid;
         rs_s[tid] = m < M ? rowsum[m] : 0;
         cf_s[tid] = (y && m < M) ? *beta * scale[m] : 0.0f;
@@ -443,19 +440,20 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
         }
 }
 
-template <int WM, int WN, int DBG>
+template <int BM, int BN, int STAGES, int WM, int WN, int DBG>
 static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, const int8_t* q, const float* scale,
                                   const int32_t* rowsum, int M, int N, int K, const float* residual,
                                   int32_t* acc, float* y, hipStream_t st) {
-    constexpr int lds = G3_STAGES * G3_STAGE_BYTES;
-    auto kern = bl_gemm_tile256<WM, WN, DBG>;
+    constexpr int G3_BM = BM;
+    constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4);
+    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN, DBG>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return BL_ERR_HIP;
         attr_set = true;
     }
-    const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + G3_BN - 1) / G3_BN;
+    const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
     const int blocks = ((total + 7) / 8) * 8;
     kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, residual,
@@ -463,17 +461,26 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
-/* variant: 0 = 2x2 waves, 1 = 2x4 waves, 2 = 4x2 waves; dbg selects timing experiments */
+/* variant: 0 = 256x256 2x2 waves, 1 = 256x256 2x4 waves, 2 = 256x256 4x2 waves,
+ * 3 = 256x128 2x2 waves with two stages (two workgroups per CU), 4 / 5 = 128x128 2x2 waves with
+ * two / three stages (three / two workgroups per CU); dbg selects timing experiments */
 static bl_status launch_tile256(int variant, const uint8_t* packed, const float* beta, const int8_t* q,
                                 const float* scale, const int32_t* rowsum, int M, int N, int K,
                                 const float* residual, int32_t* acc, float* y, hipStream_t st) {
     const char* e = getenv("BL_GEMM_DBG");
     const int dbg = e && *e ? atoi(e) : 0;
-#define BL_T256(WMv, WNv, D) launch_tile256_t<WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
+#define BL_T256(WMv, WNv, D) launch_tile256_t<256, 256, 3, WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
+#define BL_T128(D) launch_tile256_t<256, 128, 2, 2, 2, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
+#define BL_TS(ST, D) launch_tile256_t<128, 128, ST, 2, 2, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
+    if (variant == 4) return dbg == 8 ? BL_TS(2, 8) : dbg == 11 ? BL_TS(2, 11) : BL_TS(2, 0);
+    if (variant == 5) return dbg == 8 ? BL_TS(3, 8) : dbg == 11 ? BL_TS(3, 11) : BL_TS(3, 0);
+    if (variant == 3) return dbg == 8 ? BL_T128(8) : dbg == 11 ? BL_T128(11) : BL_T128(0);
     if (variant == 1) return dbg == 8 ? BL_T256(2, 4, 8) : dbg == 11 ? BL_T256(2, 4, 11) : BL_T256(2, 4, 0);
     if (variant == 2) return dbg == 8 ? BL_T256(4, 2, 8) : dbg == 11 ? BL_T256(4, 2, 11) : BL_T256(4, 2, 0);
     return dbg == 8 ? BL_T256(2, 2, 8) : dbg == 11 ? BL_T256(2, 2, 11) : BL_T256(2, 2, 0);
 #undef BL_T256
+#undef BL_T128
+#undef BL_TS
 }
 
 /* rowsum[m] = sum_k q[m][k]; one wave per row. */
@@ -506,18 +513,23 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
         bl_rowsum_kernel<<<(unsigned)((M + 3) / 4), 256, 0, st>>>(q, (int)M, (int)K, rs);
         rowsum = rs;
     }
-    /* Tile choice.  Measured on MI355X at M = 2048: 128x128 tiles with k step
-     * 128 (three workgroups per CU) win on every 2B-layer shape; the 256x256
-     * direct-to-LDS kernel ties on the widest (N = 13824).  BL_GEMM_TILE
-     * overrides for experiments: 0 = 128x128x64, 5 = 128x128x128,
-     * 6/7/8 = 256x256x128 with 2x2 / 2x4 / 4x2 waves. */
+    /* Tile choice.  Measured on MI355X at M = 2048 on the four 2B-layer shapes:
+     * 128x128 tiles, k step 128, two LDS stages filled by direct global->LDS
+     * loads, XCD-aware tile order, three workgroups per CU (tile id 10) wins
+     * everywhere (1527 TOPS over the layer against 1311 for the register-staged
+     * 128x128 kernel and ~950 for 256x256 tiles).  It needs layout 1 and
+     * K % 128 == 0; other inputs use the register-staged kernel, which permutes
+     * the activation bytes for layout 0.  BL_GEMM_TILE overrides for experiments:
+     * 0 = 128x128x64 staged, 5 = 128x128x128 staged, 6/7/8 = 256x256 with 2x2 /
+     * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages. */
     const char* e = getenv("BL_GEMM_TILE");
     const int m = (int)M, n = (int)N, k = (int)K;
     int tile = e && *e ? atoi(e) : -1;
-    if (tile < 0) tile = (k % 128 == 0) ? 5 : 0;
-    if (tile >= 6 && tile <= 8 && (layout != 1 || k % G3_BK)) tile = (k % 128 == 0) ? 5 : 0;
+    const bool direct_ok = layout == 1 && k % G3_BK == 0;
+    if (tile < 0) tile = direct_ok ? 10 : (k % 128 == 0) ? 5 : 0;
+    if (tile >= 6 && tile <= 11 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
     if (tile == 5 && k % 128) tile = 0;
-    if (tile >= 6 && tile <= 8)
+    if (tile >= 6 && tile <= 11)
         return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
     if (tile == 5)
         return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
