@@ -432,7 +432,9 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                         if (acc) acc[(int64_t)m * N + n] = val;
                         if (y) {
                             const float t = (float)val * c;
-                            y[(int64_t)m * N + n] = residual ? residual[(int64_t)m * N + n] + t : t;
+                            const float out = residual ? residual[(int64_t)m * N + n] + t : t;
+                            if (DBG & 32) y[(int64_t)m * N + n] = out;
+                            else __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
                         }
                     }
                 }
@@ -472,7 +474,7 @@ static bl_status launch_tile256(int variant, const uint8_t* packed, const float*
 #define BL_T256(WMv, WNv, D) launch_tile256_t<256, 256, 3, WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
 #define BL_T128(D) launch_tile256_t<256, 128, 2, 2, 2, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
 #define BL_TS(ST, D) launch_tile256_t<128, 128, ST, 2, 2, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
-    if (variant == 4) return dbg == 8 ? BL_TS(2, 8) : dbg == 11 ? BL_TS(2, 11) : BL_TS(2, 0);
+    if (variant == 4) return dbg == 8 ? BL_TS(2, 8) : dbg == 11 ? BL_TS(2, 11) : dbg == 32 ? BL_TS(2, 32) : BL_TS(2, 0);
     if (variant == 5) return dbg == 8 ? BL_TS(3, 8) : dbg == 11 ? BL_TS(3, 11) : BL_TS(3, 0);
     if (variant == 3) return dbg == 8 ? BL_T128(8) : dbg == 11 ? BL_T128(11) : BL_T128(0);
     if (variant == 1) return dbg == 8 ? BL_T256(2, 4, 8) : dbg == 11 ? BL_T256(2, 4, 11) : BL_T256(2, 4, 0);
