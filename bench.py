@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--layout", type=int, default=1)
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-chain", action="store_true")
+    ap.add_argument("--no-batched", action="store_true")
     ap.add_argument("--prefill-m", type=int, default=2048)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling HBM byte counters)")
@@ -319,6 +321,86 @@ def main():
                           "roofline": {"bound": "mfma", "achieved": round(tops, 2), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "traffic": None,
                                        "kernel": "bl_gemm_mfma"}}
+
+    # ------------------------------------------- config 2: batched decode, M in {8, 32, 64}
+    if not args.no_batched:
+        cfg2 = {}
+        for Mb in (8, 32, 64):
+            bb = make_decode_buffers(bl, torch, synth, Mb, dev)
+            for name in SHAPE_ORDER:
+                b = bb[name]
+                lib.bl_quant_act_int8(b.X.data_ptr(), Mb, b.K, b.q.data_ptr(), b.scale.data_ptr(), b.rowsum.data_ptr(),
+                                      torch.cuda.current_stream().cuda_stream)
+            ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+
+            def run_b():
+                s = torch.cuda.current_stream().cuda_stream
+                for l in range(nl):
+                    for name in SHAPE_ORDER:
+                        b = bb[name]
+                        rc = lib.bl_gemv_w158a8(layers[l].packed[name].data_ptr(), layers[l].beta[name].data_ptr(),
+                                                layout, b.q.data_ptr(), b.scale.data_ptr(), b.rowsum.data_ptr(), Mb,
+                                                b.N, b.K, None, b.y.data_ptr(), ws.data_ptr(), s)
+                        assert rc == 0, rc
+            with torch.cuda.stream(side):
+                run_b()
+                torch.cuda.synchronize()
+                g = capture(torch, run_b)
+                g.replay()
+                t_b, _ = time_graph_steps(torch, [(g, nl, 5)], 5 * nl)
+            t_b /= 5 * nl
+            cfg2["M=%d" % Mb] = {"us_per_layer": round(t_b * 1e6, 2), "GBps_packed": round(layer_bytes / t_b / 1e9, 1),
+                                 "tops": round(sum(2.0 * Mb * n * k for n, k in synth.LAYER_SHAPES.values()) / t_b / 1e12, 2)}
+            del bb
+        out["config2_batched_decode"] = cfg2
+        log("[bench] config 2 (bl_gemv_w158a8, 4 launches per layer, int8 inputs): %s" % cfg2)
+
+    # ------------------------------------------- config 4: the chained 30-layer stack
+    if not args.no_chain:
+        from paper_2504_12285_amd import chain
+        wts = [{n: (L.packed[n], L.beta[n]) for n in SHAPE_ORDER} for L in layers]
+        x0 = torch.from_numpy(synth.bf16_bits_to_f32(synth.activations_bf16(0, 1, 2560, layer=100))).to(dev)
+        Bd = chain.ChainBuffers(1, dev)
+        xa, xb = x0.clone(), torch.empty_like(x0)
+
+        def decode_token():
+            x, Bd.x_next = xa, xb
+            for w in wts:
+                nxt = chain.layer_decode(w, layout, x, Bd)
+                Bd.x_next, x = x, nxt
+        with torch.cuda.stream(side):
+            decode_token()
+            torch.cuda.synchronize()
+            g = capture(torch, decode_token)
+            g.replay()
+            n_tok = 50
+            t_tok, _ = time_graph_steps(torch, [(g, 1, n_tok)], n_tok)
+        t_tok /= n_tok
+        Mc = 4096
+        xp = torch.from_numpy(synth.bf16_bits_to_f32(synth.activations_bf16(0, Mc, 2560, layer=101))).to(dev)
+        Bp = chain.ChainBuffers(Mc, dev)
+        chain.run_chain(wts[:2], layout, xp, mode="prefill")
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        x = xp
+        for w in wts:
+            nxt = chain.layer_prefill(w, layout, x, Bp)
+            Bp.x_next, x = x, nxt
+        e1.record()
+        torch.cuda.synchronize()
+        t_stack = e0.elapsed_time(e1) * 1e-3
+        ops_stack = nl * sum(2.0 * Mc * n * k for n, k in synth.LAYER_SHAPES.values())
+        out["config4"] = {
+            "decode_chain": {"workload": "%d chained layers, M=1, 4 fused launches per layer (producer+quantiser+"
+                                         "product+rescale+residual), hip graph" % nl,
+                             "us_per_token": round(t_tok * 1e6, 1), "us_per_launch": round(t_tok * 1e6 / (4 * nl), 2),
+                             "GBps": round(nl * layer_bytes / t_tok / 1e9, 1)},
+            "prefill_chain": {"workload": "%d chained layers, M=%d, producer+quantiser kernel then product" % (nl, Mc),
+                              "ms": round(t_stack * 1e3, 3), "tops_products_only_ops": round(ops_stack / t_stack / 1e12, 1)}}
+        log("[bench] config 4: %s" % out["config4"])
+        del xp, Bp
 
     # ------------------------------------------------------ CPU oracle baseline
     if not args.no_cpu:

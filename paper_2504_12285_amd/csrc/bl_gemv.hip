@@ -140,6 +140,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     float* fs = (float*)(sq + M);       /* M scales, then 4 per-wave scratch */
     int* red = (int*)(fs + M + 4);      /* 4 waves * R * M partial sums      */
     if (P.fused) {
+        if (tid < M) sq[tid] = 0;                  /* ordered before the atomics by the absmax barrier */
         /* fused producer: absmax + int8 quantisation of the bf16 row, per token.
          * Each thread keeps its (at most two) 16-element groups in registers. */
 #pragma unroll 1
@@ -189,16 +190,14 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
                 bl_put16(Q + m * (K / 4), u, P.layout, a0, a1, a2, a3);
             }
             part = bl_wave_sum(part);
-            if (lane == 0) red[w] = part;
-            __syncthreads();                       /* also orders fs[M..] reuse and Q writes */
+            if (lane == 0) atomicAdd(&sq[m], part);   /* four LDS atomics per token */
             if (tid == 0) {
-                sq[m] = red[0] + red[1] + red[2] + red[3];
                 const float sc = bl_div_rn(gg, 127.0f);
                 fs[m] = P.fixed_scale > 0.0f ? P.fixed_scale : sc;
                 if (P.scale_out && first_block) P.scale_out[m] = sc;
             }
+            __syncthreads();                       /* Q, sq[m], fs[m] complete; fs[M..] reusable */
         }
-        __syncthreads();
     } else {
         const bool need_sum = P.rowsum == nullptr;
         if (tid < M) {
@@ -524,17 +523,17 @@ static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks
 
 /* Lays the products of a group out over workgroups and launches them.  All
  * products of a group share M.  k is split over the waves of a workgroup when
- * a product alone would give fewer than about two workgroups per compute unit.
+ * a product alone would give fewer than about 150 workgroups.
  * Path: the VALU dot4 + DPP kernel for M <= 4 (measured faster there), the
  * matrix-core kernel above that; BL_GEMV_PATH=mma forces the latter.  Returns BL_ERR_SHAPE if a K is too long for the
  * register-resident row scheme (the caller then uses the prefill kernel). */
 bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
     const char* path_env = getenv("BL_GEMV_PATH");
     const bool dot4 = M <= 4 && !(path_env && path_env[0] == 'm');
-    int G = dot4 ? bl_env_int("BL_GEMV_G", grp.count > 1 ? 4 : 8) : 4;
+    int G = dot4 ? bl_env_int("BL_GEMV_G", 8) : 4;
     if (G != 4 && G != 8) G = 8;
     const int force_split = bl_env_int("BL_GEMV_KSPLIT", 0);
-    const int want_blocks = bl_env_int("BL_GEMV_BLOCKS", 400);
+    const int want_blocks = bl_env_int("BL_GEMV_BLOCKS", 150);   /* measured best of 60..700 */
     const int R = 64 / G;
     int blocks = 0, maxK = 0, L = 0;
     for (int i = 0; i < grp.count; ++i) {
