@@ -243,7 +243,7 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                                                                 const int32_t* __restrict__ rowsum,
                                                                 const float* __restrict__ beta,
                                                                 const float* __restrict__ scale, int M, int N,
-                                                                int K, int tiles_m, int tiles_n,
+                                                                int K, int tiles_m, int tiles_n, int gm,
                                                                 const float* __restrict__ residual,
                                                                 int32_t* __restrict__ acc, float* __restrict__ y) {
     constexpr int NW = WM * WN, THREADS = NW * 64;
@@ -258,12 +258,15 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
 
-    /* XCD-aware tile id: workgroup L runs on XCD L%8 */
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = (total + 7) / 8;
-    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (tile >= total) return;
-    const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+    /* XCD-aware tile order: workgroup L runs on XCD L%8.  The tile grid is cut
+     * into gm x gn = 8 rectangular regions, one per XCD, narrow enough in M that
+     * a region's activation panel stays in that XCD's 4 MB L2 while its weight
+     * tiles stream through; inside a region the row tiles vary fastest. */
+    const int gn = 8 / gm;
+    const int rm = (tiles_m + gm - 1) / gm, rn = (tiles_n + gn - 1) / gn;
+    const int xcd = (int)blockIdx.x & 7, idx = (int)blockIdx.x >> 3;
+    const int tm = (xcd / gn) * rm + idx % rm, tn = (xcd % gn) * rn + idx / rm;
+    if (tm >= tiles_m || tn >= tiles_n) return;
     const int m0 = tm * G3_BM, n0 = tn * BN;
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
     const int kb = K / 4;
@@ -456,9 +459,16 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
         attr_set = true;
     }
     const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + BN - 1) / BN;
-    const int total = tiles_m * tiles_n;
-    const int blocks = ((total + 7) / 8) * 8;
-    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, residual,
+    /* rows of activations per XCD region: at most ~1.5 MB of int8, unless the
+     * problem is much wider than tall (then whole-M regions measured faster) */
+    int gm = 1;
+    if (tiles_n < 4 * tiles_m)
+        while (gm < 8 && (int64_t)((tiles_m + gm - 1) / gm) * BM * K > (3 << 19)) gm *= 2;
+    const char* eg = getenv("BL_GEMM_GM");
+    if (eg && *eg) { const int v = atoi(eg); if (v == 1 || v == 2 || v == 4 || v == 8) gm = v; }
+    const int gn = 8 / gm;
+    const int blocks = 8 * ((tiles_m + gm - 1) / gm) * ((tiles_n + gn - 1) / gn);
+    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, residual,
                                             acc, y);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
