@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     /* activation loads first, so that staging needs to wait for them only */
     const int groups = K / 16;
     uint4 xv[4];
-    uint4 qv = make_uint4(0, 0, 0, 0);
+    bl_v4i qv = {0, 0, 0, 0};
     const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16;
     const bool first_block = blockIdx.x == (unsigned)P.block0;
     if (pre_bf16) {
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
             }
         }
     } else if (!P.fused && tid < M * groups) {
-        qv = *(const uint4*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
+        qv = *(const bl_v4i*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
     }
 
     bl_v4i p[L];
@@ -207,9 +207,10 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
         if (need_sum) __syncthreads();
         for (int u = tid; u < M * groups; u += 256) {
             const int m = u / groups, c16 = u - m * groups;
-            const uint4 v = u < 256 ? qv : *(const uint4*)(P.q + (int64_t)m * K + (int64_t)c16 * 16);
-            if (need_sum) atomicAdd(&sq[m], bl_sum16(v.x, v.y, v.z, v.w));
-            bl_put16(Q + m * (K / 4), c16, P.layout, v.x, v.y, v.z, v.w);
+            bl_v4i v = qv;
+            if (u >= 256) v = *(const bl_v4i*)(P.q + (int64_t)m * K + (int64_t)c16 * 16);
+            if (need_sum) atomicAdd(&sq[m], bl_sum16((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]));
+            bl_put16(Q + m * (K / 4), c16, P.layout, (uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
         }
         __syncthreads();
     }
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
 
     /* 1. activation loads first (token 0 of the fused path, or the first q groups) */
     uint4 xv[4];
-    uint4 qv = make_uint4(0, 0, 0, 0);
+    bl_v4i qv = {0, 0, 0, 0};
     const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16;
     const bool first_block = blockIdx.x == (unsigned)P.block0;
     if (pre_bf16) {
@@ -318,7 +319,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             }
         }
     } else if (!P.fused && tid < M * groups) {
-        qv = *(const uint4*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
+        qv = *(const bl_v4i*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
     }
 
     /* 2. every weight load of this lane */
@@ -388,7 +389,8 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
         }
     } else {
         if (tid < M * groups)
-            bl_put16((int*)(Q + (tid / groups) * qstride), tid % groups, P.layout, qv.x, qv.y, qv.z, qv.w);
+            bl_put16((int*)(Q + (tid / groups) * qstride), tid % groups, P.layout, (uint32_t)qv[0], (uint32_t)qv[1],
+                     (uint32_t)qv[2], (uint32_t)qv[3]);
         for (int u = tid + 256; u < M * groups; u += 256) {
             const int m = u / groups, c16 = u - m * groups;
             const uint4 v = *(const uint4*)(P.q + (int64_t)m * K + (int64_t)c16 * 16);
