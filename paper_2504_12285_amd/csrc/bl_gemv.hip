@@ -266,24 +266,28 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     }
 }
 
-#define BL_MMA_PAD 16   /* bytes added to each staged activation row (LDS bank spread) */
+#define BL_MMA_PAD 16    /* bytes added to each staged activation row (LDS bank spread) */
+#define BL_MMA_HEAD 144  /* ints in front of the rows: 4 wave maxima, 64 token scales, 64 row sums */
 
 /* Matrix-core decode kernel, M <= 16*MT tokens, up to four products per launch.
  * Same work split as bl_gemv_rows with G = 4: lane (c, kg) owns weight row c of
- * a 16-row group and k chunks (i*ksplit+kp)*4+kg.  Each 16-byte weight load
- * feeds four v_mfma_i32_16x16x64_i8, one per bit-pair level s: the B operand is
- * the lane's four packed words masked to level s (no shift except the top
- * level), the A operand the activation bytes of token l%16 that pair with that
- * level, read from the LDS image [chunk][s][d] by the lanes of real tokens only.
- * The four levels accumulate separately with factors 1, 4, 16, 16 (four
- * independent MFMA chains) and are recombined once with exact shifts.  The k
+ * a 16-row group and k chunks (i*ksplit+kp)*4+kg, and issues all of its 16-byte
+ * weight loads first.  Each packed word d of a chunk is opened into its four
+ * bit-pair levels by shift and mask (plus a 4x4 byte transpose for layout 0),
+ * which puts the sixteen codes of k = 16d .. 16d+15 in natural order: the B
+ * operand of one v_mfma_i32_16x16x64_i8 whose A operand is sixteen consecutive
+ * int8 of token l%16, read from LDS rows that hold q as it is in memory.  The k
  * reduction happens inside the matrix core: no cross-lane step.  sum_k q comes
- * from a fifth chain with an all-ones B operand when no rowsum was given.
- * The activation loads are issued before the weight loads so that staging can
- * proceed while the weights are still in flight.
- * Dynamic LDS: M*(K+16) bytes + (MT*2*4*256 + 4 + 64) ints. */
+ * from a second chain with an all-ones B operand when no rowsum was given.
+ * Tokens beyond M read the last real row (their results are never stored).
+ *
+ * int8 inputs: the rows are staged 1024 << LF columns at a time (so that 64
+ * tokens fit), wave w copying tokens/column blocks w, w+4, ..; the loads of the
+ * next phase are in flight during the products of the current one.  Fused
+ * inputs: produced, quantised and staged whole, one token at a time.
+ * Dynamic LDS: BL_MMA_HEAD ints, then max(M*(row+16), MT*4096) bytes. */
 template <int L, int MT, bool NEED_SUM>
-__global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M) {
+__global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LF) {
     extern __shared__ int lds[];
     int pi = 0;
 #pragma unroll
@@ -291,23 +295,50 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
         if (i < grp.count && (int)blockIdx.x >= grp.p[i].block0) pi = i;
     const bl_gemv_prob& P = grp.p[pi];
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kg = lane >> 4;
     const int rg = w / ksplit, kp = w - rg * ksplit;
     const int rows_per_block = (4 / ksplit) * 16;
     const int n = ((int)blockIdx.x - P.block0) * rows_per_block + rg * 16 + c;
     const bool row_ok = n < N;
     const int groups = K / 16;
-    const int qstride = K + BL_MMA_PAD;                 /* bytes per staged token row */
-    uint8_t* Q = (uint8_t*)lds;
-    int* red = (int*)(Q + M * qstride);                 /* C and Cs of 4 waves, MT tiles */
-    float* fs = (float*)(red + MT * 4 * 256 * 2);       /* 4 wave maxima                 */
-    float* fscale = fs + 4;                             /* M scales (fused path)         */
+    const bool fused = P.fused != 0;
+    const int PK = fused ? K : (1024 << LF);              /* columns per staging phase */
+    const int qstride = (PK < K ? PK : K) + BL_MMA_PAD;   /* bytes per staged token row */
+    float* fs = (float*)lds;                              /* 4 wave maxima              */
+    float* fscale = fs + 4;                               /* M <= 64 input scales       */
+    int* frs = (int*)(fscale + 64);                       /* M <= 64 input row sums     */
+    uint8_t* Q = (uint8_t*)(lds + BL_MMA_HEAD);
+    int* red = (int*)Q;                                   /* D of 4 waves, MT tiles: reuses the rows */
 
-    /* 1. activation loads first (token 0 of the fused path, or the first q groups) */
+    /* Staging slot j of this wave: token m, 64 sixteen-byte groups starting at column block jj. */
+    constexpr int NS = 4 * MT;
+    bl_v4i stg[NS];
+    /* Workgroups run in step and all want the same rows: each starts at a different phase
+     * and a different slot, so that at any moment they ask different L2 channels. */
+    const int nph = (K + PK - 1) / PK;
+    const int rot_ph = (int)blockIdx.x % nph, rot_j = ((int)blockIdx.x / nph) & (NS - 1);
+    auto stage_load = [&](int k0) {
+        const int kw = K - k0 < PK ? K - k0 : PK;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int t = w + 4 * ((j + rot_j) & (NS - 1)), m = t >> LF, c16 = lane + 64 * (t & ((1 << LF) - 1));
+            const bool ok = m < M && c16 * 16 < kw;
+            stg[j] = *(const bl_v4i*)(P.q + (ok ? (int64_t)m * K + k0 + (int64_t)c16 * 16 : 0));
+        }
+    };
+    auto stage_put = [&](int k0) {
+        const int kw = K - k0 < PK ? K - k0 : PK;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int t = w + 4 * ((j + rot_j) & (NS - 1)), m = t >> LF, c16 = lane + 64 * (t & ((1 << LF) - 1));
+            if (m < M && c16 * 16 < kw) *(bl_v4i*)(Q + m * qstride + c16 * 16) = stg[j];
+        }
+    };
+
+    /* 1. activation loads first (token 0 of the fused path, or the first phase of q) */
     uint4 xv[4];
-    bl_v4i qv = {0, 0, 0, 0};
-    const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16;
+    const bool pre_bf16 = fused && P.prod.kind == BL_PROD_BF16;
     const bool first_block = blockIdx.x == (unsigned)P.block0;
     if (pre_bf16) {
 #pragma unroll
@@ -318,8 +349,13 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                 xv[2 * j + 1] = ((const uint4*)P.prod.in0)[2 * u + 1];
             }
         }
-    } else if (!P.fused && tid < M * groups) {
-        qv = *(const bl_v4i*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
+    }
+    if (!fused) {
+        stage_load(rot_ph * PK);
+        if (tid < M) {
+            fscale[tid] = P.scale ? P.scale[tid] : 0.0f;
+            frs[tid] = P.rowsum ? P.rowsum[tid] : 0;
+        }
     }
 
     /* 2. every weight load of this lane */
@@ -334,8 +370,8 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
         }
     }
 
-    /* 3. stage the activations */
-    if (P.fused) {
+    /* 3. fused path: produce, quantise and stage every token */
+    if (fused) {
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
             float mx = 0.0f;
@@ -360,7 +396,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             const float gg = fmaxf(gamma, 1e-5f);
             const float inv = bl_div_rn(127.0f, gg);
             const bool emit = P.q_out && first_block;
-            int* Qm = (int*)(Q + m * qstride);
+            uint8_t* Qm = Q + m * qstride;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int u = tid + j * 256;
@@ -369,7 +405,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                     bl_quant8_words(xv[2 * j], inv, a0, a1);
                     bl_quant8_words(xv[2 * j + 1], inv, a2, a3);
                     if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
-                    bl_put16(Qm, u, P.layout, a0, a1, a2, a3);
+                    *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
                 }
             }
             for (int u = tid + 512; u < groups; u += 256) {
@@ -379,7 +415,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                 bl_quant8_words(lo, inv, a0, a1);
                 bl_quant8_words(hi, inv, a2, a3);
                 if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
-                bl_put16(Qm, u, P.layout, a0, a1, a2, a3);
+                *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
             }
             if (tid == 0) {
                 const float sc = bl_div_rn(gg, 127.0f);
@@ -387,48 +423,57 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                 if (P.scale_out && first_block) P.scale_out[m] = sc;
             }
         }
-    } else {
-        if (tid < M * groups)
-            bl_put16((int*)(Q + (tid / groups) * qstride), tid % groups, P.layout, (uint32_t)qv[0], (uint32_t)qv[1],
-                     (uint32_t)qv[2], (uint32_t)qv[3]);
-        for (int u = tid + 256; u < M * groups; u += 256) {
-            const int m = u / groups, c16 = u - m * groups;
-            const uint4 v = *(const uint4*)(P.q + (int64_t)m * K + (int64_t)c16 * 16);
-            bl_put16((int*)(Q + m * qstride), c16, P.layout, v.x, v.y, v.z, v.w);
-        }
+        __syncthreads();
     }
-    __syncthreads();
 
-    /* 4. products: four levels, four accumulators per token tile */
+    /* 4. products */
     constexpr bool need_sum = NEED_SUM;   /* the launcher checked: no product of the group has a rowsum */
-    const bl_v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
-    bl_v4i C[MT][4], Cs[MT];
+    bl_v4i C[MT], Cs[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) C[t][0] = C[t][1] = C[t][2] = C[t][3] = Cs[t] = bl_v4i{0, 0, 0, 0};
+    for (int t = 0; t < MT; ++t) C[t] = Cs[t] = bl_v4i{0, 0, 0, 0};
+    const uint8_t* arow[MT];
 #pragma unroll
-    for (int i = 0; i < L; ++i) {
-        const int chunk = (i * ksplit + kp) * 4 + kg;
-        const bool cv = chunk < nchunks;
-        if ((i * ksplit + kp) * 4 < nchunks) {          /* wave-uniform: some lane has work */
-            const bl_v4i pw = p[i];
+    for (int t = 0; t < MT; ++t) {
+        const int tok = t * 16 + c;
+        arow[t] = Q + (tok < M ? tok : M - 1) * qstride;
+    }
+    for (int ph = 0; ph < nph; ++ph) {
+        const int php = ph + rot_ph < nph ? ph + rot_ph : ph + rot_ph - nph;
+        const int k0 = php * PK;                          /* first k of this phase */
+        if (!fused) {
+            if (ph > 0) __syncthreads();                  /* the previous phase has been consumed */
+            stage_put(k0);
+            __syncthreads();
+            if (ph + 1 < nph) stage_load(php + 1 < nph ? k0 + PK : 0);
+        }
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                bl_v4i b;
+        for (int i = 0; i < L; ++i) {
+            const int chunk = (i * ksplit + kp) * 4 + kg;
+            const bool cv = chunk < nchunks;
+            const int kfirst = (i * ksplit + kp) * 256;   /* wave-uniform: first k of this step */
+            if (kfirst >= k0 && kfirst < k0 + PK && kfirst < K) {
+                const int coff = cv ? chunk * 64 - k0 : 0;
+                bl_v4i a[MT][4];
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) a[t][d] = *(const bl_v4i*)(arow[t] + coff + d * 16);
+                const bl_v4i pw = p[i];
+                const int one = cv ? 0x01010101 : 0;
+                const bl_v4i ones = {one, one, one, one};
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    const uint32_t wd = (uint32_t)pw[d];
-                    b[d] = (int)(s == 0 ? (wd & 0x03030303u)
-                               : s == 1 ? (wd & 0x0C0C0C0Cu)
-                               : s == 2 ? (wd & 0x30303030u)
-                                        : ((wd >> 2) & 0x30303030u));
-                }
+                    uint32_t wd = (uint32_t)pw[d];
+                    asm volatile("" : "+v"(wd));          /* unpack here, not hoisted out of the phase loop */
+                    uint32_t l0 = wd & 0x03030303u, l1 = (wd >> 2) & 0x03030303u, l2 = (wd >> 4) & 0x03030303u,
+                             l3 = (wd >> 6) & 0x03030303u;
+                    if (P.layout == 0) bl_transpose4x4(l0, l1, l2, l3);
+                    const bl_v4i b = {(int)l0, (int)l1, (int)l2, (int)l3};
 #pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    const int tok = t * 16 + c;
-                    bl_v4i a = {0, 0, 0, 0};
-                    if (cv && tok < M) a = *(const bl_v4i*)(Q + tok * qstride + chunk * 64 + s * 16);
-                    C[t][s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, C[t][s], 0, 0, 0);
-                    if (need_sum) Cs[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, Cs[t], 0, 0, 0);
+                    for (int t = 0; t < MT; ++t) {
+                        C[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t][d], b, C[t], 0, 0, 0);
+                        if (need_sum) Cs[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t][d], ones, Cs[t], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -436,12 +481,10 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     bl_v4i D[MT];
     bl_mfma_fence();
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-            D[t][v] = C[t][0][v] + (C[t][1][v] >> 2) + ((C[t][2][v] + C[t][3][v]) >> 4) - Cs[t][v];
+    for (int t = 0; t < MT; ++t) D[t] = C[t] - Cs[t];
 
     if (ksplit > 1) {
+        __syncthreads();                                  /* every wave is done reading the rows */
 #pragma unroll
         for (int t = 0; t < MT; ++t) *(bl_v4i*)(red + ((t * 4 + w) * 64 + lane) * 4) = D[t];
         __syncthreads();
@@ -454,20 +497,23 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     if (kp == 0 && row_ok) {
         const float bt = *P.beta;
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t) {
+            const bl_v4i rs4 = *(const bl_v4i*)(frs + t * 16 + kg * 4);
+            const float4 sc4 = *(const float4*)(fscale + t * 16 + kg * 4);
+            const float scv[4] = {sc4.x, sc4.y, sc4.z, sc4.w};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int tok = t * 16 + kg * 4 + v;
                 if (tok < M) {
-                    const int val = D[t][v] - (need_sum ? 0 : P.rowsum[tok]);
+                    const int val = D[t][v] - (need_sum ? 0 : rs4[v]);
                     if (P.acc) P.acc[(int64_t)tok * N + n] = val;
                     if (P.y) {
-                        const float sc = P.fused ? fscale[tok] : P.scale[tok];
-                        const float t = (float)val * (bt * sc);
-                        P.y[(int64_t)tok * N + n] = P.residual ? P.residual[(int64_t)tok * N + n] + t : t;
+                        const float r = (float)val * (bt * scv[v]);
+                        P.y[(int64_t)tok * N + n] = P.residual ? P.residual[(int64_t)tok * N + n] + r : r;
                     }
                 }
             }
+        }
     }
 }
 
@@ -494,11 +540,20 @@ static bl_status launch_rows_l(int L, const bl_gemv_group& grp, int blocks, int 
 }
 
 template <int L, int MT>
-static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, int maxK, hipStream_t st) {
-    const size_t lds = (size_t)M * (maxK + BL_MMA_PAD) + (size_t)(MT * 4 * 256 * 2 + 4 + 64) * 4;
+static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStream_t st) {
+    /* int8 inputs are staged 1024 << LF columns at a time: the largest power of two that
+     * keeps a phase within the kernel's 4*MT staging slots per wave */
+    int LF = 0;
+    while ((M << (LF + 1)) <= 16 * MT) ++LF;
     bool have_sums = true;   /* every product brings its own row sums */
-    for (int i = 0; i < grp.count; ++i)
-        if (grp.p[i].fused || !grp.p[i].rowsum) have_sums = false;
+    size_t rows = (size_t)MT * 4096;
+    for (int i = 0; i < grp.count; ++i) {
+        const bl_gemv_prob& P = grp.p[i];
+        if (P.fused || !P.rowsum) have_sums = false;
+        const size_t row = P.fused || P.K < (1024 << LF) ? (size_t)P.K : (size_t)(1024 << LF);
+        if ((size_t)M * (row + BL_MMA_PAD) > rows) rows = (size_t)M * (row + BL_MMA_PAD);
+    }
+    const size_t lds = rows + BL_MMA_HEAD * 4;
     auto kern = have_sums ? bl_gemv_mma<L, MT, false> : bl_gemv_mma<L, MT, true>;
     if (lds > 160 * 1024) return BL_ERR_SHAPE;
     if (lds > 64 * 1024) {
@@ -510,17 +565,17 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, int max
             done[have_sums] = true;
         }
     }
-    kern<<<blocks, 256, lds, st>>>(grp, M);
+    kern<<<blocks, 256, lds, st>>>(grp, M, LF);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
 template <int MT>
-static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks, int maxK, hipStream_t st) {
-    if (L <= 2) return launch_mma<2, MT>(grp, M, blocks, maxK, st);
-    if (L <= 4) return launch_mma<4, MT>(grp, M, blocks, maxK, st);
-    if (L <= 8) return launch_mma<8, MT>(grp, M, blocks, maxK, st);
-    if (L <= 16) return launch_mma<16, MT>(grp, M, blocks, maxK, st);
-    return launch_mma<32, MT>(grp, M, blocks, maxK, st);
+static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks, hipStream_t st) {
+    if (L <= 2) return launch_mma<2, MT>(grp, M, blocks, st);
+    if (L <= 4) return launch_mma<4, MT>(grp, M, blocks, st);
+    if (L <= 8) return launch_mma<8, MT>(grp, M, blocks, st);
+    if (L <= 16) return launch_mma<16, MT>(grp, M, blocks, st);
+    return launch_mma<32, MT>(grp, M, blocks, st);
 }
 
 /* Lays the products of a group out over workgroups and launches them.  All
@@ -553,9 +608,9 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
     }
     if (L > 32) return BL_ERR_SHAPE;
     if (!dot4) {
-        if (M <= 16) return launch_mma_l<1>(L, grp, M, blocks, maxK, st);
-        if (M <= 32) return launch_mma_l<2>(L, grp, M, blocks, maxK, st);
-        return launch_mma_l<4>(L, grp, M, blocks, maxK, st);
+        if (M <= 16) return launch_mma_l<1>(L, grp, M, blocks, st);
+        if (M <= 32) return launch_mma_l<2>(L, grp, M, blocks, st);
+        return launch_mma_l<4>(L, grp, M, blocks, st);
     }
     switch (M * 10 + G) {
         case 14: return launch_rows_l<1, 4>(L, grp, blocks, maxK, st);
@@ -585,7 +640,7 @@ extern "C" bl_status bl_gemv_w158a8(const uint8_t* packed, const float* beta, in
         !bl_aligned(scale, 4) || !bl_aligned(beta, 4) || !bl_aligned(rowsum, 4))
         return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
-    if (K > 8192 || M * (K + BL_MMA_PAD) > 96 * 1024)
+    if (K > 8192)
         return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, nullptr, acc, y, workspace, st);
 
     bl_gemv_group grp;
