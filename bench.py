@@ -99,12 +99,19 @@ def decode_step_fused(lib, stream, L, buf, layout):
         assert rc == 0, rc
 
 
-def make_group_descs(bl, layers, buf):
-    """One bl_decode_desc array per layer: the four shapes, fused quantiser, fp32 outputs."""
+def make_group_descs(bl, layers, buf, fused=True):
+    """One bl_decode_desc array per layer: the four shapes, fp32 outputs; inputs bf16
+    (fused quantiser) or already quantised int8 with scales and row sums."""
     out = []
     for L in layers:
-        items = [dict(packed=L.packed[n], beta=L.beta[n], X=buf[n].X, N=buf[n].N, K=buf[n].K, y=buf[n].y)
-                 for n in SHAPE_ORDER]
+        items = []
+        for n in SHAPE_ORDER:
+            it = dict(packed=L.packed[n], beta=L.beta[n], N=buf[n].N, K=buf[n].K, y=buf[n].y)
+            if fused:
+                it["X"] = buf[n].X
+            else:
+                it.update(q=buf[n].q, scale=buf[n].scale, rowsum=buf[n].rowsum)
+            items.append(it)
         out.append(bl.make_decode_descs(items))
     return out
 
@@ -343,18 +350,40 @@ def main():
                                                 layout, b.q.data_ptr(), b.scale.data_ptr(), b.rowsum.data_ptr(), Mb,
                                                 b.N, b.K, None, b.y.data_ptr(), ws.data_ptr(), s)
                         assert rc == 0, rc
+            descs_q = make_group_descs(bl, layers, bb, fused=False)
+
+            def run_g():
+                s = torch.cuda.current_stream().cuda_stream
+                for l in range(nl):
+                    rc = lib.bl_bitlinear_decode_group(descs_q[l], 4, layout, Mb, s)
+                    assert rc == 0, rc
+            variants = {"calls": run_b, "grouped": run_g}
+            if Mb * (6912 + 16) <= 96 * 1024:
+                descs_x = make_group_descs(bl, layers, bb, fused=True)
+
+                def run_f():
+                    s = torch.cuda.current_stream().cuda_stream
+                    for l in range(nl):
+                        rc = lib.bl_bitlinear_decode_group(descs_x[l], 4, layout, Mb, s)
+                        assert rc == 0, rc
+                variants["grouped_fused"] = run_f
+            ops2 = sum(2.0 * Mb * n * k for n, k in synth.LAYER_SHAPES.values())
+            res = {}
             with torch.cuda.stream(side):
-                run_b()
-                torch.cuda.synchronize()
-                g = capture(torch, run_b)
-                g.replay()
-                t_b, _ = time_graph_steps(torch, [(g, nl, 5)], 5 * nl)
-            t_b /= 5 * nl
-            cfg2["M=%d" % Mb] = {"us_per_layer": round(t_b * 1e6, 2), "GBps_packed": round(layer_bytes / t_b / 1e9, 1),
-                                 "tops": round(sum(2.0 * Mb * n * k for n, k in synth.LAYER_SHAPES.values()) / t_b / 1e12, 2)}
+                for vname, fn in variants.items():
+                    fn()
+                    torch.cuda.synchronize()
+                    g = capture(torch, fn)
+                    g.replay()
+                    t_b, _ = time_graph_steps(torch, [(g, nl, 5)], 5 * nl)
+                    t_b /= 5 * nl
+                    res[vname] = {"us_per_layer": round(t_b * 1e6, 2), "GBps_packed": round(layer_bytes / t_b / 1e9, 1),
+                                  "tops": round(ops2 / t_b / 1e12, 2)}
+            cfg2["M=%d" % Mb] = res
             del bb
         out["config2_batched_decode"] = cfg2
-        log("[bench] config 2 (bl_gemv_w158a8, 4 launches per layer, int8 inputs): %s" % cfg2)
+        log("[bench] config 2 (calls: 4 bl_gemv_w158a8 launches per layer, int8 inputs; grouped: one "
+            "bl_bitlinear_decode_group launch, int8 inputs; grouped_fused: one launch, bf16 inputs): %s" % cfg2)
 
     # ------------------------------------------- config 4: the chained 30-layer stack
     if not args.no_chain:

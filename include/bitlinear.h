@@ -194,10 +194,13 @@ typedef struct {
     const float* residual;
 } bl_decode_desc;
 
-/* Up to four INDEPENDENT decode products (same M <= 4, same layout, K <= 8192
- * each) in one kernel launch, e.g. the four BitLinear shapes of a layer on
+/* Up to four INDEPENDENT decode products (same M, same layout, K <= 8192 each)
+ * in one kernel launch, e.g. the four BitLinear shapes of a layer on
  * independent inputs.  Results are identical to separate calls; the point is
- * one launch and one continuous weight stream instead of four. */
+ * one launch and one continuous weight stream instead of four.
+ * Limits: a product with a fused input (X or prod) needs M <= 16 and
+ * M*(K+16) <= 96 KiB; a product with int8 input (q) takes M <= 64.
+ * Errors: BL_ERR_SHAPE outside these limits or for count outside 1..4. */
 bl_status bl_bitlinear_decode_group(const bl_decode_desc* descs, int count, int layout, int64_t M, bl_stream s);
 
 /* Producer + per-token absmax int8 quantiser for prefill (Section 2): like

@@ -287,7 +287,8 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
  * inputs: produced, quantised and staged whole, one token at a time.
  * Dynamic LDS: BL_MMA_HEAD ints, then max(M*(row+16), MT*4096) bytes. */
 template <int L, int MT, bool NEED_SUM>
-__global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LF) {
+__global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LFD) {
+    const int LF = LFD & 0xff, dbg = LFD >> 8;
     extern __shared__ int lds[];
     int pi = 0;
 #pragma unroll
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
         for (int j = 0; j < NS; ++j) {
             const int t = w + 4 * ((j + rot_j) & (NS - 1)), m = t >> LF, c16 = lane + 64 * (t & ((1 << LF) - 1));
             const bool ok = m < M && c16 * 16 < kw;
-            stg[j] = *(const bl_v4i*)(P.q + (ok ? (int64_t)m * K + k0 + (int64_t)c16 * 16 : 0));
+            if (!(dbg & 1)) stg[j] = *(const bl_v4i*)(P.q + (ok ? (int64_t)m * K + k0 + (int64_t)c16 * 16 : 0));
         }
     };
     auto stage_put = [&](int k0) {
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
             const int t = w + 4 * ((j + rot_j) & (NS - 1)), m = t >> LF, c16 = lane + 64 * (t & ((1 << LF) - 1));
-            if (m < M && c16 * 16 < kw) *(bl_v4i*)(Q + m * qstride + c16 * 16) = stg[j];
+            if (m < M && c16 * 16 < kw && !(dbg & 8)) *(bl_v4i*)(Q + m * qstride + c16 * 16) = stg[j];
         }
     };
 
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             const int chunk = (i * ksplit + kp) * 4 + kg;
             const bool cv = chunk < nchunks;
             const int kfirst = (i * ksplit + kp) * 256;   /* wave-uniform: first k of this step */
-            if (kfirst >= k0 && kfirst < k0 + PK && kfirst < K) {
+            if (!(dbg & 2) && kfirst >= k0 && kfirst < k0 + PK && kfirst < K) {
                 const int coff = cv ? chunk * 64 - k0 : 0;
                 bl_v4i a[MT][4];
 #pragma unroll
@@ -501,10 +502,11 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             const bl_v4i rs4 = *(const bl_v4i*)(frs + t * 16 + kg * 4);
             const float4 sc4 = *(const float4*)(fscale + t * 16 + kg * 4);
             const float scv[4] = {sc4.x, sc4.y, sc4.z, sc4.w};
+            const int val0 = D[t][0] ^ D[t][1] ^ D[t][2] ^ D[t][3];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int tok = t * 16 + kg * 4 + v;
-                if (tok < M) {
+                if (tok < M && (!(dbg & 4) || val0 == 12345)) {
                     const int val = D[t][v] - (need_sum ? 0 : rs4[v]);
                     if (P.acc) P.acc[(int64_t)tok * N + n] = val;
                     if (P.y) {
@@ -565,7 +567,7 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStre
             done[have_sums] = true;
         }
     }
-    kern<<<blocks, 256, lds, st>>>(grp, M, LF);
+    kern<<<blocks, 256, lds, st>>>(grp, M, LF | (bl_env_int("BL_GEMV_DBG", 0) << 8));
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
@@ -658,8 +660,8 @@ static bl_status check_decode_desc(const bl_decode_desc& d, int64_t M, int layou
     if (!fused && !d.q) return BL_ERR_NULL;
     if (!d.acc && !d.y) return BL_ERR_NULL;
     if (!fused && d.y && !d.scale) return BL_ERR_NULL;
-    if (M < 1 || M > 16 || !bl_shape_ok(d.N, d.K) || d.K > 8192 || M * (d.K + BL_MMA_PAD) > 96 * 1024)
-        return BL_ERR_SHAPE;
+    if (M < 1 || M > 64 || !bl_shape_ok(d.N, d.K) || d.K > 8192) return BL_ERR_SHAPE;
+    if (fused && (M > 16 || M * (d.K + BL_MMA_PAD) > 96 * 1024)) return BL_ERR_SHAPE;
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
         !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||

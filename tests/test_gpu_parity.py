@@ -136,6 +136,16 @@ def test_gemv_batched(bl, layout, M):
     assert_y_close(y, c.y)
 
 
+@pytest.mark.parametrize("M,N,K", [(9, 2564, 1024), (16, 52, 320), (33, 2560, 6912), (48, 200, 8192), (64, 20, 64)])
+def test_gemv_batched_phases_and_tails(bl, M, N, K):
+    """Staging phases with a short last phase, ragged row groups, K at the limit."""
+    c = Case(35, M, N, K)
+    for layout in (0, 1):
+        acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(layout == 1))
+        assert np.array_equal(acc, c.acc)
+        assert_y_close(y, c.y)
+
+
 @pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
 @pytest.mark.parametrize("M", [1, 4])
 def test_gemv_layer_shapes(bl, name, M):
@@ -267,12 +277,15 @@ def test_fused_decode_zero_and_tiny_rows(bl):
     assert_y_close(y.cpu().numpy(), ref["y"])
 
 
-@pytest.mark.parametrize("M", [1, 4])
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("M,fused", [(1, False), (1, True), (4, False), (4, True), (8, False), (8, True),
+                                     (8, "mixed"), (40, False), (64, False)])
 def test_grouped_decode_whole_layer(bl, M, fused):
     """The four shapes of one layer in ONE launch equal four oracle products."""
     cases, items, keep = [], [], []
+    mixed = fused == "mixed"
     for name in ["qkv", "o", "gate_up", "down"]:
+        if mixed:
+            fused = name in ("o", "down")
         N, K = synth.LAYER_SHAPES[name]
         c = Case(0, M, N, K, layer=1, matrix=name, relu2=(name == "down"))
         it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=N, K=K,
