@@ -74,6 +74,15 @@ __device__ __forceinline__ void bl_transpose4x4(uint32_t& a0, uint32_t& a1, uint
     a3 = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
+/* Direct global->LDS loads (16 bytes per lane): the LDS destination is a wave-uniform
+ * base, lane l's bytes land at base + 16*l.  They count on vmcnt like any load. */
+typedef const __attribute__((address_space(1))) void* bl_gptr;
+typedef __attribute__((address_space(3))) void* bl_lptr;
+
+/* s_waitcnt vmcnt(n) only, n < 64: expcnt = 7, lgkmcnt = 15 left open (gfx9 encoding:
+ * vmcnt bits 3:0 in imm[3:0], bits 5:4 in imm[15:14]) */
+#define BL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
 /* Wait for in-flight matrix-core results before ordinary vector instructions
  * read an accumulator.  The hardware has no interlock for that read, and the
  * compiler's wait-state count for the gfx950 16x16x64 int8 MFMA proved too

@@ -231,11 +231,6 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * Requires layout 1, K % 128 == 0. */
 #define G3_BK 128
 
-typedef const __attribute__((address_space(1))) void* bl_gptr;
-typedef __attribute__((address_space(3))) void* bl_lptr;
-
-/* s_waitcnt vmcnt(n) only (n < 16): expcnt = 7, lgkmcnt = 15 left open */
-#define BL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
 template <int BM, int BN, int STAGES, int WM, int WN, int DBG>
 __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,

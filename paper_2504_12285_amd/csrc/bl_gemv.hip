@@ -41,6 +41,27 @@ struct bl_gemv_group {
     int count;
 };
 
+/* The descriptor of workgroup's product, fetched from the kernel arguments ONCE and held in
+ * scalar registers.  Without the pins the compiler re-reads a field from the argument
+ * buffer at every use (a scalar-cache round trip in front of each store of the epilogue). */
+template <typename T>
+__device__ __forceinline__ void bl_pin(T& v) {
+    asm volatile("" : "+s"(v));
+}
+__device__ __forceinline__ bl_gemv_prob bl_fetch_prob(const bl_gemv_group& grp) {
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < BL_GEMV_MAX_GROUP; ++i)
+        if (i < grp.count && (int)blockIdx.x >= grp.p[i].block0) pi = i;
+    bl_gemv_prob P = grp.p[pi];
+    bl_pin(P.packed); bl_pin(P.q); bl_pin(P.prod.kind); bl_pin(P.prod.in0); bl_pin(P.prod.in1);
+    bl_pin(P.prod.aux_out); bl_pin(P.prod.voff); bl_pin(P.prod.group); bl_pin(P.prod.hd);
+    bl_pin(P.prod.in_stride); bl_pin(P.fused); bl_pin(P.residual); bl_pin(P.beta); bl_pin(P.scale);
+    bl_pin(P.rowsum); bl_pin(P.acc); bl_pin(P.y); bl_pin(P.q_out); bl_pin(P.scale_out); bl_pin(P.N);
+    bl_pin(P.K); bl_pin(P.layout); bl_pin(P.block0); bl_pin(P.ksplit); bl_pin(P.fixed_scale);
+    return P;
+}
+
 /* LDS image of the activations.  For token m and 64-wide k chunk c, sixteen
  * dwords indexed [s][d]: the bytes that pair with bit-pair level s of packed
  * word d of the chunk.
@@ -92,11 +113,7 @@ template <int M, int G, int L>
 __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     extern __shared__ int lds[];
     constexpr int R = 64 / G;
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < BL_GEMV_MAX_GROUP; ++i)
-        if (i < grp.count && (int)blockIdx.x >= grp.p[i].block0) pi = i;
-    const bl_gemv_prob& P = grp.p[pi];
+    const bl_gemv_prob P = bl_fetch_prob(grp);
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane / G, g = lane % G;
@@ -266,6 +283,13 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     }
 }
 
+#ifdef BL_TRACE   /* development aid: per-workgroup time stamps (100 MHz clock) */
+__device__ unsigned long long* bl_trace_ptr;
+extern "C" int bl_trace_set(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(bl_trace_ptr), &p, sizeof(p)); }
+#define BL_STAMP(i) do { if (threadIdx.x == 0 && bl_trace_ptr) bl_trace_ptr[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define BL_STAMP(i)
+#endif
 #define BL_MMA_PAD 16    /* bytes added to each staged activation row (LDS bank spread) */
 #define BL_MMA_HEAD 144  /* ints in front of the rows: 4 wave maxima, 64 token scales, 64 row sums */
 
@@ -287,14 +311,13 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
  * inputs: produced, quantised and staged whole, one token at a time.
  * Dynamic LDS: BL_MMA_HEAD ints, then max(M*(row+16), MT*4096) bytes. */
 template <int L, int MT, bool NEED_SUM>
-__global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LFD) {
-    const int LF = LFD & 0xff, dbg = LFD >> 8;
+__global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LF, const int budget) {
     extern __shared__ int lds[];
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < BL_GEMV_MAX_GROUP; ++i)
-        if (i < grp.count && (int)blockIdx.x >= grp.p[i].block0) pi = i;
-    const bl_gemv_prob& P = grp.p[pi];
+    BL_STAMP(0);
+    const bl_gemv_prob P = bl_fetch_prob(grp);
+#ifdef BL_TRACE
+    if (threadIdx.x == 0 && bl_trace_ptr) bl_trace_ptr[blockIdx.x * 8 + 6] = wall_clock64() + (P.N == 0x7fffffff);
+#endif
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kg = lane >> 4;
@@ -304,36 +327,52 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     const bool row_ok = n < N;
     const int groups = K / 16;
     const bool fused = P.fused != 0;
-    const int PK = fused ? K : (1024 << LF);              /* columns per staging phase */
-    const int qstride = (PK < K ? PK : K) + BL_MMA_PAD;   /* bytes per staged token row */
+    /* int8 inputs: everything at once when M rows of K fit the LDS budget, else two
+     * buffers of PK = 1024 << LF columns (the launcher sized LF so that a phase is 64
+     * (token, 1024-column) pieces: 16 loads per wave) */
+    const bool whole = fused || M * (K + BL_MMA_PAD) <= budget;
+    const int PK = whole ? K : (1024 << LF);              /* columns per staging phase */
+    const int qstride = PK + BL_MMA_PAD;                  /* bytes per staged token row */
+    const int bufsz = M * qstride;
     float* fs = (float*)lds;                              /* 4 wave maxima              */
     float* fscale = fs + 4;                               /* M <= 64 input scales       */
     int* frs = (int*)(fscale + 64);                       /* M <= 64 input row sums     */
     uint8_t* Q = (uint8_t*)(lds + BL_MMA_HEAD);
     int* red = (int*)Q;                                   /* D of 4 waves, MT tiles: reuses the rows */
 
-    /* Staging slot j of this wave: token m, 64 sixteen-byte groups starting at column block jj. */
-    constexpr int NS = 4 * MT;
-    bl_v4i stg[NS];
     /* Workgroups run in step and all want the same rows: each starts at a different phase
-     * and a different slot, so that at any moment they ask different L2 channels. */
+     * and a different piece, so that at any moment they ask different L2 channels. */
     const int nph = (K + PK - 1) / PK;
-    const int rot_ph = (int)blockIdx.x % nph, rot_j = ((int)blockIdx.x / nph) & (NS - 1);
-    auto stage_load = [&](int k0) {
-        const int kw = K - k0 < PK ? K - k0 : PK;
+    const int rot_ph = (int)blockIdx.x % nph;
+    constexpr int NS = 16;                                /* loads per wave and phase (phased mode) */
+    /* phase php of the phased mode into buffer buf: exactly NS loads per wave, so that the
+     * vmcnt immediates below are right; a piece outside M x kw re-loads piece (0, 0) */
+    auto stage_phase = [&](int php, int buf) {
+        const int k0 = php * PK, kw = K - k0 < PK ? K - k0 : PK;
+        uint8_t* base = Q + buf * bufsz;
+        const int rot_j = ((int)blockIdx.x / nph) & (NS - 1);
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
-            const int t = w + 4 * ((j + rot_j) & (NS - 1)), m = t >> LF, c16 = lane + 64 * (t & ((1 << LF) - 1));
-            const bool ok = m < M && c16 * 16 < kw;
-            if (!(dbg & 1)) stg[j] = *(const bl_v4i*)(P.q + (ok ? (int64_t)m * K + k0 + (int64_t)c16 * 16 : 0));
+            const int t = w + 4 * ((j + rot_j) & (NS - 1));
+            int m = t >> LF, jj = t & ((1 << LF) - 1);
+            if (m >= M || jj * 1024 >= kw) m = jj = 0;
+            const int c16 = lane + 64 * jj;
+            if (c16 * 16 < kw)
+                __builtin_amdgcn_global_load_lds((bl_gptr)(P.q + (int64_t)m * K + k0 + c16 * 16),
+                                                 (bl_lptr)(base + m * qstride + jj * 1024), 16, 0, 0);
         }
     };
-    auto stage_put = [&](int k0) {
-        const int kw = K - k0 < PK ? K - k0 : PK;
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            const int t = w + 4 * ((j + rot_j) & (NS - 1)), m = t >> LF, c16 = lane + 64 * (t & ((1 << LF) - 1));
-            if (m < M && c16 * 16 < kw && !(dbg & 8)) *(bl_v4i*)(Q + m * qstride + c16 * 16) = stg[j];
+    /* whole mode: wave w copies pieces w, w+4, .. of the M x ceil(K/1024) grid, rotated */
+    auto stage_whole = [&]() {
+        const int cols = (K + 1023) / 1024, pieces = M * cols;
+        const int rot = (int)(blockIdx.x * 5u) % pieces;
+        for (int t = w; t < pieces; t += 4) {
+            const int tt = t + rot < pieces ? t + rot : t + rot - pieces;
+            const int m = tt / cols, jj = tt - m * cols;
+            const int c16 = lane + 64 * jj;
+            if (c16 * 16 < K)
+                __builtin_amdgcn_global_load_lds((bl_gptr)(P.q + (int64_t)m * K + c16 * 16),
+                                                 (bl_lptr)(Q + m * qstride + jj * 1024), 16, 0, 0);
         }
     };
 
@@ -351,26 +390,44 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             }
         }
     }
-    if (!fused) {
-        stage_load(rot_ph * PK);
-        if (tid < M) {
-            fscale[tid] = P.scale ? P.scale[tid] : 0.0f;
-            frs[tid] = P.rowsum ? P.rowsum[tid] : 0;
-        }
+    /* small loads go out now and are used late: nothing below waits for them alone */
+    const float bt = *P.beta;
+    float sc_in = 0.0f;
+    int rs_in = 0;
+    if (!fused && tid < M) {
+        if (P.scale) sc_in = P.scale[tid];
+        if (P.rowsum) rs_in = P.rowsum[tid];
     }
 
-    /* 2. every weight load of this lane */
+    /* 2. every weight load of this wave.  The matrix core wants lane 16*kg+c to hold chunk kg
+     * of row c, but four consecutive lanes should fetch 64 consecutive bytes: lane l loads
+     * chunk l%4 of row l/4, and a lane permutation at the point of use puts it in place. */
     bl_v4i p[L];
     {
-        const bl_v4i* wrow = P.packed + (int64_t)(row_ok ? n : 0) * nchunks;
+        const int lrow = lane >> 2, lkg = lane & 3;
+        const int ln = n - c + lrow;                      /* the row this lane fetches */
+        const bool lok = ln < N;
+        const bl_v4i* wrow = P.packed + (int64_t)(lok ? ln : 0) * nchunks;
 #pragma unroll
         for (int i = 0; i < L; ++i) {
-            const int chunk = (i * ksplit + kp) * 4 + kg;
+            const int chunk = (i * ksplit + kp) * 4 + lkg;
             p[i] = bl_v4i{0, 0, 0, 0};
-            if (row_ok && chunk < nchunks) p[i] = __builtin_nontemporal_load(wrow + chunk);
+            if (lok && chunk < nchunks) p[i] = __builtin_nontemporal_load(wrow + chunk);
+        }
+    }
+    const int perm_src = (4 * c + kg) * 4;                /* byte index of the lane that fetched for this one */
+    BL_STAMP(7);
+
+    if (!fused) {
+        if (whole) {
+            stage_whole();
+        } else {
+            stage_phase(rot_ph, 0);
+            stage_phase(rot_ph + 1 < nph ? rot_ph + 1 : 0, 1);   /* nph >= 2 in phased mode */
         }
     }
 
+    BL_STAMP(1);
     /* 3. fused path: produce, quantise and stage every token */
     if (fused) {
 #pragma unroll 1
@@ -429,60 +486,101 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
 
     /* 4. products */
     constexpr bool need_sum = NEED_SUM;   /* the launcher checked: no product of the group has a rowsum */
-    bl_v4i C[MT], Cs[MT];
+    /* one accumulator per packed word d: four independent MFMA chains per token tile */
+    bl_v4i C[MT][4], Cs[MT][2];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) C[t] = Cs[t] = bl_v4i{0, 0, 0, 0};
-    const uint8_t* arow[MT];
+    for (int t = 0; t < MT; ++t) {
+        C[t][0] = C[t][1] = C[t][2] = C[t][3] = bl_v4i{0, 0, 0, 0};
+        Cs[t][0] = Cs[t][1] = bl_v4i{0, 0, 0, 0};
+    }
+    int arow[MT];                                         /* byte offset of this lane's token row */
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         const int tok = t * 16 + c;
-        arow[t] = Q + (tok < M ? tok : M - 1) * qstride;
+        arow[t] = (tok < M ? tok : M - 1) * qstride;
     }
-    for (int ph = 0; ph < nph; ++ph) {
-        const int php = ph + rot_ph < nph ? ph + rot_ph : ph + rot_ph - nph;
-        const int k0 = php * PK;                          /* first k of this phase */
-        if (!fused) {
-            if (ph > 0) __syncthreads();                  /* the previous phase has been consumed */
-            stage_put(k0);
-            __syncthreads();
-            if (ph + 1 < nph) stage_load(php + 1 < nph ? k0 + PK : 0);
+    /* one load step: chunk (i*ksplit+kp)*4+kg of this lane's row against the staged rows at
+     * qb, whose column 0 is k0.  A lane whose chunk lies beyond K has zero weights and reads
+     * column 0. */
+    auto step = [&](const bl_v4i praw, int i, const uint8_t* qb, int k0, bool fence) {
+        bl_v4i pw;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) pw[d] = __builtin_amdgcn_ds_bpermute(perm_src, praw[d]);
+        const int chunk = (i * ksplit + kp) * 4 + kg;
+        const bool cv = chunk < nchunks;
+        const int coff = cv ? chunk * 64 - k0 : 0;
+        bl_v4i a[MT][4];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) a[t][d] = *(const bl_v4i*)(qb + arow[t] + coff + d * 16);
+        const int one = cv ? 0x01010101 : 0;
+        const bl_v4i ones = {one, one, one, one};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t wd = (uint32_t)pw[d];
+            if (fence) asm volatile("" : "+v"(wd));       /* unpack here, not hoisted out of the phase loop */
+            uint32_t l0 = wd & 0x03030303u, l1 = (wd >> 2) & 0x03030303u, l2 = (wd >> 4) & 0x03030303u,
+                     l3 = (wd >> 6) & 0x03030303u;
+            if (P.layout == 0) bl_transpose4x4(l0, l1, l2, l3);
+            const bl_v4i b = {(int)l0, (int)l1, (int)l2, (int)l3};
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                C[t][d] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t][d], b, C[t][d], 0, 0, 0);
+                if (need_sum)
+                    Cs[t][d & 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t][d], ones, Cs[t][d & 1], 0, 0, 0);
+            }
         }
+    };
+    if (nph == 1) {
+        /* everything is staged at once: the first half of the load steps is in range for every
+         * wave (L is the smallest variant that covers K), so that part is straight-line code */
+        if (!fused) {
+            BL_WAIT_VM(0);
+            asm volatile("" ::: "memory");
+            if (tid < M) {
+                fscale[tid] = sc_in;
+                frs[tid] = rs_in;
+            }
+            __syncthreads();
+        }
+        BL_STAMP(2);
 #pragma unroll
-        for (int i = 0; i < L; ++i) {
-            const int chunk = (i * ksplit + kp) * 4 + kg;
-            const bool cv = chunk < nchunks;
-            const int kfirst = (i * ksplit + kp) * 256;   /* wave-uniform: first k of this step */
-            if (!(dbg & 2) && kfirst >= k0 && kfirst < k0 + PK && kfirst < K) {
-                const int coff = cv ? chunk * 64 - k0 : 0;
-                bl_v4i a[MT][4];
+        for (int i = 0; i < L; ++i)
+            if (i < L / 2 || (i * ksplit + kp) * 256 < K) step(p[i], i, Q, 0, false);
+    } else {
+        for (int ph = 0; ph < nph; ++ph) {
+            const int php = ph + rot_ph < nph ? ph + rot_ph : ph + rot_ph - nph;
+            const int k0 = php * PK;                      /* first k of this phase */
+            const uint8_t* qb = Q + (ph & 1) * bufsz;
+            /* this phase has landed (the next one, issued after it, may still be in flight) */
+            if (ph + 1 < nph) BL_WAIT_VM(NS);
+            else BL_WAIT_VM(0);
+            asm volatile("" ::: "memory");
+            if (ph == 0 && tid < M) {
+                fscale[tid] = sc_in;
+                frs[tid] = rs_in;
+            }
+            __syncthreads();
+            if (ph == 0) BL_STAMP(2);
 #pragma unroll
-                for (int t = 0; t < MT; ++t)
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) a[t][d] = *(const bl_v4i*)(arow[t] + coff + d * 16);
-                const bl_v4i pw = p[i];
-                const int one = cv ? 0x01010101 : 0;
-                const bl_v4i ones = {one, one, one, one};
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    uint32_t wd = (uint32_t)pw[d];
-                    asm volatile("" : "+v"(wd));          /* unpack here, not hoisted out of the phase loop */
-                    uint32_t l0 = wd & 0x03030303u, l1 = (wd >> 2) & 0x03030303u, l2 = (wd >> 4) & 0x03030303u,
-                             l3 = (wd >> 6) & 0x03030303u;
-                    if (P.layout == 0) bl_transpose4x4(l0, l1, l2, l3);
-                    const bl_v4i b = {(int)l0, (int)l1, (int)l2, (int)l3};
-#pragma unroll
-                    for (int t = 0; t < MT; ++t) {
-                        C[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t][d], b, C[t], 0, 0, 0);
-                        if (need_sum) Cs[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[t][d], ones, Cs[t], 0, 0, 0);
-                    }
-                }
+            for (int i = 0; i < L; ++i) {
+                const int kfirst = (i * ksplit + kp) * 256;   /* wave-uniform: first k of this step */
+                if (kfirst >= k0 && kfirst < k0 + PK && kfirst < K) step(p[i], i, qb, k0, true);
+            }
+            if (ph + 2 < nph) {
+                asm volatile("" ::: "memory");
+                __syncthreads();                          /* every wave is done with this buffer */
+                const int nx = ph + 2 + rot_ph;
+                stage_phase(nx < nph ? nx : nx - nph, ph & 1);
             }
         }
     }
     bl_v4i D[MT];
     bl_mfma_fence();
+    BL_STAMP(3);
 #pragma unroll
-    for (int t = 0; t < MT; ++t) D[t] = C[t] - Cs[t];
+    for (int t = 0; t < MT; ++t) D[t] = (C[t][0] + C[t][1]) + (C[t][2] + C[t][3]) - (Cs[t][0] + Cs[t][1]);
 
     if (ksplit > 1) {
         __syncthreads();                                  /* every wave is done reading the rows */
@@ -495,18 +593,17 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                 for (int t = 0; t < MT; ++t) D[t] += *(const bl_v4i*)(red + ((t * 4 + w + j) * 64 + lane) * 4);
         }
     }
+    BL_STAMP(4);
     if (kp == 0 && row_ok) {
-        const float bt = *P.beta;
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const bl_v4i rs4 = *(const bl_v4i*)(frs + t * 16 + kg * 4);
             const float4 sc4 = *(const float4*)(fscale + t * 16 + kg * 4);
             const float scv[4] = {sc4.x, sc4.y, sc4.z, sc4.w};
-            const int val0 = D[t][0] ^ D[t][1] ^ D[t][2] ^ D[t][3];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int tok = t * 16 + kg * 4 + v;
-                if (tok < M && (!(dbg & 4) || val0 == 12345)) {
+                if (tok < M) {
                     const int val = D[t][v] - (need_sum ? 0 : rs4[v]);
                     if (P.acc) P.acc[(int64_t)tok * N + n] = val;
                     if (P.y) {
@@ -517,6 +614,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             }
         }
     }
+    BL_STAMP(5);
 }
 
 static int bl_env_int(const char* name, int dflt) {
@@ -543,17 +641,21 @@ static bl_status launch_rows_l(int L, const bl_gemv_group& grp, int blocks, int 
 
 template <int L, int MT>
 static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStream_t st) {
-    /* int8 inputs are staged 1024 << LF columns at a time: the largest power of two that
-     * keeps a phase within the kernel's 4*MT staging slots per wave */
+    /* LDS budget for the staged rows: nearly all of it when every workgroup gets a CU of its
+     * own, else small enough for two workgroups per CU.  int8 inputs that do not fit whole
+     * are staged 1024 << LF columns at a time in two buffers; a phase is at most 64
+     * (token, 1024-column) pieces: the kernel's 16 loads per wave. */
+    const int budget = bl_env_int("BL_GEMV_LDS", 150) * 1024;
     int LF = 0;
-    while ((M << (LF + 1)) <= 16 * MT) ++LF;
+    while ((M << (LF + 1)) <= 64 && 2 * (size_t)M * ((1024 << (LF + 1)) + BL_MMA_PAD) <= (size_t)budget) ++LF;
     bool have_sums = true;   /* every product brings its own row sums */
     size_t rows = (size_t)MT * 4096;
     for (int i = 0; i < grp.count; ++i) {
         const bl_gemv_prob& P = grp.p[i];
         if (P.fused || !P.rowsum) have_sums = false;
-        const size_t row = P.fused || P.K < (1024 << LF) ? (size_t)P.K : (size_t)(1024 << LF);
-        if ((size_t)M * (row + BL_MMA_PAD) > rows) rows = (size_t)M * (row + BL_MMA_PAD);
+        size_t need = (size_t)M * (P.K + BL_MMA_PAD);
+        if (!P.fused && need > (size_t)budget) need = 2 * (size_t)M * ((1024 << LF) + BL_MMA_PAD);
+        if (need > rows) rows = need;
     }
     const size_t lds = rows + BL_MMA_HEAD * 4;
     auto kern = have_sums ? bl_gemv_mma<L, MT, false> : bl_gemv_mma<L, MT, true>;
@@ -567,7 +669,7 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStre
             done[have_sums] = true;
         }
     }
-    kern<<<blocks, 256, lds, st>>>(grp, M, LF | (bl_env_int("BL_GEMV_DBG", 0) << 8));
+    kern<<<blocks, 256, lds, st>>>(grp, M, LF, budget);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
@@ -592,7 +694,10 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
     int G = dot4 ? bl_env_int("BL_GEMV_G", 8) : 4;
     if (G != 4 && G != 8) G = 8;
     const int force_split = bl_env_int("BL_GEMV_KSPLIT", 0);
-    const int want_blocks = bl_env_int("BL_GEMV_BLOCKS", 150);   /* measured best of 60..700 */
+    /* workgroups wanted per product, measured: 150 for a product alone (best of 40..700) and
+     * for the dot4 kernel; the matrix-core kernel, whose workgroups each stage all M rows,
+     * does best with about 300 over the whole group */
+    const int want_blocks = bl_env_int("BL_GEMV_BLOCKS", dot4 || grp.count < 2 ? 150 : 300 / grp.count);
     const int R = 64 / G;
     int blocks = 0, maxK = 0, L = 0;
     for (int i = 0; i < grp.count; ++i) {
