@@ -416,23 +416,41 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int ml = wm0 + mi * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-            const int m = m0 + ml;
-            if (m < M) {
-                const int rs = rs_s[ml];
-                const float c = cf_s[ml];
+        for (int vq = 0; vq < 4; ++vq) {
+            /* the residual values of four rows first, then their stores back to back: a load
+             * between two stores would make each store wait for the one before it */
+            float rres[4][NI];
+            if (residual && y) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int n = n0 + wn0 + ni * 32 + l32;
-                    if (n < N) {
-                        const int val = C[mi][ni][v] - rs;
-                        if (acc) acc[(int64_t)m * N + n] = val;
-                        if (y) {
-                            const float t = (float)val * c;
-                            const float out = residual ? residual[(int64_t)m * N + n] + t : t;
-                            if (DBG & 32) y[(int64_t)m * N + n] = out;
-                            else __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int m = m0 + wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int n = n0 + wn0 + ni * 32 + l32;
+                        rres[v4][ni] = (m < M && n < N) ? residual[(int64_t)m * N + n] : 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int v = vq * 4 + v4;
+                const int ml = wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+                const int m = m0 + ml;
+                if (m < M) {
+                    const int rs = rs_s[ml];
+                    const float c = cf_s[ml];
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int n = n0 + wn0 + ni * 32 + l32;
+                        if (n < N) {
+                            const int val = C[mi][ni][v] - rs;
+                            if (acc) acc[(int64_t)m * N + n] = val;
+                            if (y) {
+                                const float t = (float)val * c;
+                                const float out = residual ? rres[v4][ni] + t : t;
+                                if (DBG & 32) y[(int64_t)m * N + n] = out;
+                                else __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
+                            }
                         }
                     }
                 }

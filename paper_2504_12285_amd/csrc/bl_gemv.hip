@@ -41,7 +41,19 @@ struct bl_gemv_group {
     int count;
 };
 
-/* The descriptor of workgroup's product, fetched from the kernel arguments ONCE and held in
+#ifdef BL_TRACE   /* development aid: per-workgroup time stamps (100 MHz clock) */
+__device__ unsigned long long* bl_trace_ptr;
+extern "C" int bl_trace_set(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(bl_trace_ptr), &p, sizeof(p)); }
+#define BL_STAMP_DECL unsigned long long bl_ts[6] = {0, 0, 0, 0, 0, 0}
+#define BL_STAMP(i) bl_ts[i] = wall_clock64()
+#define BL_STAMP_FLUSH do { if (threadIdx.x == 0 && bl_trace_ptr) for (int i_ = 0; i_ < 6; ++i_) bl_trace_ptr[blockIdx.x * 8 + i_] = bl_ts[i_]; } while (0)
+#else
+#define BL_STAMP_DECL
+#define BL_STAMP(i)
+#define BL_STAMP_FLUSH
+#endif
+
+/* The descriptor of a workgroup's product, fetched from the kernel arguments ONCE and held in
  * scalar registers.  Without the pins the compiler re-reads a field from the argument
  * buffer at every use (a scalar-cache round trip in front of each store of the epilogue). */
 template <typename T>
@@ -113,6 +125,8 @@ template <int M, int G, int L>
 __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     extern __shared__ int lds[];
     constexpr int R = 64 / G;
+    BL_STAMP_DECL;
+    BL_STAMP(0);
     const bl_gemv_prob P = bl_fetch_prob(grp);
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -140,17 +154,24 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     } else if (!P.fused && tid < M * groups) {
         qv = *(const bl_v4i*)(P.q + (int64_t)(tid / groups) * K + (int64_t)(tid % groups) * 16);
     }
+    /* small loads go out before the weight stream and are used late */
+    const float bt = *P.beta;
+    float sc_in = 0.0f;
+    int rs_in = 0;
+    if (!P.fused && tid < M) {
+        if (P.scale) sc_in = P.scale[tid];
+        if (P.rowsum) rs_in = P.rowsum[tid];
+    }
 
     bl_v4i p[L];
-    {
-        const bl_v4i* wrow = P.packed + (int64_t)(row_ok ? n : 0) * nchunks;
+    const bl_v4i* wrow = P.packed + (int64_t)(row_ok ? n : 0) * nchunks;
 #pragma unroll
-        for (int i = 0; i < L; ++i) {
-            const int chunk = (i * ksplit + kp) * G + g;
-            p[i] = bl_v4i{0, 0, 0, 0};
-            if (row_ok && chunk < nchunks) p[i] = __builtin_nontemporal_load(wrow + chunk);
-        }
+    for (int i = 0; i < L; ++i) {
+        const int chunk = (i * ksplit + kp) * G + g;
+        p[i] = bl_v4i{0, 0, 0, 0};
+        if (row_ok && chunk < nchunks) p[i] = __builtin_nontemporal_load(wrow + chunk);
     }
+    BL_STAMP(1);
 
     int* Q = lds;                       /* M*K/4 dwords                      */
     int* sq = Q + M * (K / 4);          /* M row sums                        */
@@ -218,8 +239,8 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     } else {
         const bool need_sum = P.rowsum == nullptr;
         if (tid < M) {
-            sq[tid] = need_sum ? 0 : P.rowsum[tid];
-            fs[tid] = P.scale ? P.scale[tid] : 0.0f;
+            sq[tid] = rs_in;
+            fs[tid] = sc_in;
         }
         if (need_sum) __syncthreads();
         for (int u = tid; u < M * groups; u += 256) {
@@ -231,6 +252,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
         }
         __syncthreads();
     }
+    BL_STAMP(2);
 
     int A[M][4];
 #pragma unroll
@@ -244,7 +266,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
                 bl_dot_chunk(p[i], (const bl_v4i*)(Q + (m * nchunks + chunk) * 16), A[m]);
         }
     }
-    const float bt = *P.beta;
+    BL_STAMP(3);
     int v[M];
 #pragma unroll
     for (int m = 0; m < M; ++m)
@@ -269,6 +291,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
 #pragma unroll
         for (int m = 0; m < M; ++m) o[m] = __shfl(v[m], (lane & (R - 1)) * G);
     }
+    BL_STAMP(4);
     const int n_out = ((int)blockIdx.x - P.block0) * rows_per_block + rg * R + lane;
     if (kp == 0 && lane < R && n_out < N) {
 #pragma unroll
@@ -281,15 +304,10 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
             }
         }
     }
+    BL_STAMP(5);
+    BL_STAMP_FLUSH;
 }
 
-#ifdef BL_TRACE   /* development aid: per-workgroup time stamps (100 MHz clock) */
-__device__ unsigned long long* bl_trace_ptr;
-extern "C" int bl_trace_set(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(bl_trace_ptr), &p, sizeof(p)); }
-#define BL_STAMP(i) do { if (threadIdx.x == 0 && bl_trace_ptr) bl_trace_ptr[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define BL_STAMP(i)
-#endif
 #define BL_MMA_PAD 16    /* bytes added to each staged activation row (LDS bank spread) */
 #define BL_MMA_HEAD 144  /* ints in front of the rows: 4 wave maxima, 64 token scales, 64 row sums */
 
@@ -313,11 +331,9 @@ extern "C" int bl_trace_set(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(
 template <int L, int MT, bool NEED_SUM>
 __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LF, const int budget) {
     extern __shared__ int lds[];
+    BL_STAMP_DECL;
     BL_STAMP(0);
     const bl_gemv_prob P = bl_fetch_prob(grp);
-#ifdef BL_TRACE
-    if (threadIdx.x == 0 && bl_trace_ptr) bl_trace_ptr[blockIdx.x * 8 + 6] = wall_clock64() + (P.N == 0x7fffffff);
-#endif
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kg = lane >> 4;
@@ -416,7 +432,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
         }
     }
     const int perm_src = (4 * c + kg) * 4;                /* byte index of the lane that fetched for this one */
-    BL_STAMP(7);
 
     if (!fused) {
         if (whole) {
@@ -615,6 +630,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
         }
     }
     BL_STAMP(5);
+    BL_STAMP_FLUSH;
 }
 
 static int bl_env_int(const char* name, int dflt) {
