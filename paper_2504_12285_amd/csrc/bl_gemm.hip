@@ -232,7 +232,7 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
 #define G3_BK 128
 
 
-template <int BM, int BN, int STAGES, int WM, int WN, int DBG>
+template <int BM, int BN, int STAGES, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
                                                                 const int32_t* __restrict__ rowsum,
@@ -316,16 +316,13 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     issue(0, 0);
     if (STAGES > 2 && steps > 1) issue(1, 1);
     for (int kk = 0; kk < steps; ++kk) {
-        if (!(DBG & 2)) {
-            /* stage kk must have landed; with three stages the loads of stage kk+1 may stay in flight */
-            if (STAGES > 2 && kk + 1 < steps) BL_WAIT_VM(LOADS);
-            else BL_WAIT_VM(0);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-        }
-        if (!(DBG & 1) && kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
-        if (DBG & 4) continue;
+        /* stage kk must have landed; with three stages the loads of stage kk+1 may stay in flight */
+        if (STAGES > 2 && kk + 1 < steps) BL_WAIT_VM(LOADS);
+        else BL_WAIT_VM(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
         const uint8_t* st = smem + (kk % STAGES) * G3_STAGE_BYTES;
         if (NW == 8) {
             /* Two waves share a SIMD.  A wave's own VALU and MFMA instructions do
@@ -402,17 +399,6 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
         cf_s[tid] = (y && m < M) ? *beta * scale[m] : 0.0f;
     }
     __syncthreads();
-    if (DBG & 8) {   /* timing experiment: keep the accumulators alive, write almost nothing */
-        int sum = 0;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sum += C[mi][ni][v];
-        if (sum == 0x7fffffff) y[0] = 1.0f;
-        return;
-    }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -448,8 +434,7 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                             if (y) {
                                 const float t = (float)val * c;
                                 const float out = residual ? rres[v4][ni] + t : t;
-                                if (DBG & 32) y[(int64_t)m * N + n] = out;
-                                else __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
+                                __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
                             }
                         }
                     }
@@ -458,13 +443,13 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
         }
 }
 
-template <int BM, int BN, int STAGES, int WM, int WN, int DBG>
+template <int BM, int BN, int STAGES, int WM, int WN>
 static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, const int8_t* q, const float* scale,
                                   const int32_t* rowsum, int M, int N, int K, const float* residual,
                                   int32_t* acc, float* y, hipStream_t st) {
     constexpr int G3_BM = BM;
     constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4);
-    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN, DBG>;
+    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
@@ -486,26 +471,26 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
-/* variant: 0 = 256x256 2x2 waves, 1 = 256x256 2x4 waves, 2 = 256x256 4x2 waves,
- * 3 = 256x128 2x2 waves with two stages (two workgroups per CU), 4 / 5 = 128x128 2x2 waves with
- * two / three stages (three / two workgroups per CU); dbg selects timing experiments */
+/* variant: 0 / 1 / 2 = 256x256 with 2x2 / 2x4 / 4x2 waves and three stages, 3 = 256x128 2x2 waves
+ * with two stages, 4 / 5 = 128x128 2x2 waves with two / three stages (three / two workgroups
+ * per CU), 6 = 64x256 1x4 waves with three stages (a tile wider in N than in M moves fewer
+ * bytes per operation, packed weights costing a quarter of a byte; measured equal to 128x128
+ * at M = 2048) */
 static bl_status launch_tile256(int variant, const uint8_t* packed, const float* beta, const int8_t* q,
                                 const float* scale, const int32_t* rowsum, int M, int N, int K,
                                 const float* residual, int32_t* acc, float* y, hipStream_t st) {
-    const char* e = getenv("BL_GEMM_DBG");
-    const int dbg = e && *e ? atoi(e) : 0;
-#define BL_T256(WMv, WNv, D) launch_tile256_t<256, 256, 3, WMv, WNv, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
-#define BL_T128(D) launch_tile256_t<256, 128, 2, 2, 2, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
-#define BL_TS(ST, D) launch_tile256_t<128, 128, ST, 2, 2, D>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
-    if (variant == 4) return dbg == 8 ? BL_TS(2, 8) : dbg == 11 ? BL_TS(2, 11) : dbg == 32 ? BL_TS(2, 32) : BL_TS(2, 0);
-    if (variant == 5) return dbg == 8 ? BL_TS(3, 8) : dbg == 11 ? BL_TS(3, 11) : BL_TS(3, 0);
-    if (variant == 3) return dbg == 8 ? BL_T128(8) : dbg == 11 ? BL_T128(11) : BL_T128(0);
-    if (variant == 1) return dbg == 8 ? BL_T256(2, 4, 8) : dbg == 11 ? BL_T256(2, 4, 11) : BL_T256(2, 4, 0);
-    if (variant == 2) return dbg == 8 ? BL_T256(4, 2, 8) : dbg == 11 ? BL_T256(4, 2, 11) : BL_T256(4, 2, 0);
-    return dbg == 8 ? BL_T256(2, 2, 8) : dbg == 11 ? BL_T256(2, 2, 11) : BL_T256(2, 2, 0);
-#undef BL_T256
-#undef BL_T128
-#undef BL_TS
+#define BL_TILE(BMv, BNv, ST, WMv, WNv) \
+    launch_tile256_t<BMv, BNv, ST, WMv, WNv>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
+    switch (variant) {
+        case 1: return BL_TILE(256, 256, 3, 2, 4);
+        case 2: return BL_TILE(256, 256, 3, 4, 2);
+        case 3: return BL_TILE(256, 128, 2, 2, 2);
+        case 4: return BL_TILE(128, 128, 2, 2, 2);
+        case 5: return BL_TILE(128, 128, 3, 2, 2);
+        case 6: return BL_TILE(64, 256, 3, 1, 4);
+        default: return BL_TILE(256, 256, 3, 2, 2);
+    }
+#undef BL_TILE
 }
 
 /* rowsum[m] = sum_k q[m][k]; one wave per row. */
@@ -546,15 +531,15 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
      * K % 128 == 0; other inputs use the register-staged kernel, which permutes
      * the activation bytes for layout 0.  BL_GEMM_TILE overrides for experiments:
      * 0 = 128x128x64 staged, 5 = 128x128x128 staged, 6/7/8 = 256x256 with 2x2 /
-     * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages. */
+     * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages, 12 = 64x256. */
     const char* e = getenv("BL_GEMM_TILE");
     const int m = (int)M, n = (int)N, k = (int)K;
     int tile = e && *e ? atoi(e) : -1;
     const bool direct_ok = layout == 1 && k % G3_BK == 0;
     if (tile < 0) tile = direct_ok ? 10 : (k % 128 == 0) ? 5 : 0;
-    if (tile >= 6 && tile <= 11 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
+    if (tile >= 6 && tile <= 12 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
     if (tile == 5 && k % 128) tile = 0;
-    if (tile >= 6 && tile <= 11)
+    if (tile >= 6 && tile <= 12)
         return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
     if (tile == 5)
         return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
