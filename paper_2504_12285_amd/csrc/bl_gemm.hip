@@ -232,6 +232,16 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
 #define G3_BK 128
 
 
+/* Waits until at most r stages of LOADS direct loads each are still in flight (r <= J). */
+template <int J, int LOADS>
+__device__ __forceinline__ void bl_wait_stages(int r) {
+    if (r >= J) {
+        BL_WAIT_VM(J * LOADS);
+    } else {
+        if constexpr (J > 0) bl_wait_stages<J - 1, LOADS>(r);
+    }
+}
+
 template <int BM, int BN, int STAGES, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
@@ -248,7 +258,7 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     constexpr int A_LOADS = G3_A_BYTES / 16 / THREADS;      /* direct loads per thread and stage */
     constexpr int W_LOADS = G3_W_BYTES / 16 / THREADS;
     constexpr int LOADS = A_LOADS + W_LOADS;
-    static_assert(LOADS < 16, "vmcnt immediate assumes a 4-bit count");
+    static_assert((STAGES - 2) * LOADS < 64, "vmcnt is a 6-bit count");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -313,12 +323,13 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     const int w_off = G3_A_BYTES + ((wn0 + l32) * 2 + (h ^ ((l32 >> 2) & 1))) * 16;
 
     const int steps = K / G3_BK;
-    issue(0, 0);
-    if (STAGES > 2 && steps > 1) issue(1, 1);
+    /* STAGES - 1 k steps are in flight ahead of the matrix cores: a k step of one workgroup
+     * takes far less time than a load, so the depth, not the tile, hides the latency */
+    for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
     for (int kk = 0; kk < steps; ++kk) {
-        /* stage kk must have landed; with three stages the loads of stage kk+1 may stay in flight */
-        if (STAGES > 2 && kk + 1 < steps) BL_WAIT_VM(LOADS);
-        else BL_WAIT_VM(0);
+        /* stage kk must have landed; the stages issued after it may stay in flight */
+        const int later = steps - 1 - kk;
+        bl_wait_stages<STAGES - 2, LOADS>(later < STAGES - 2 ? later : STAGES - 2);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -525,18 +536,22 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
     }
     /* Tile choice.  Measured on MI355X at M = 2048 on the four 2B-layer shapes:
      * 128x128 tiles, k step 128, two LDS stages filled by direct global->LDS
-     * loads, XCD-aware tile order, three workgroups per CU (tile id 10) wins
-     * everywhere (1527 TOPS over the layer against 1311 for the register-staged
-     * 128x128 kernel and ~950 for 256x256 tiles).  It needs layout 1 and
-     * K % 128 == 0; other inputs use the register-staged kernel, which permutes
-     * the activation bytes for layout 0.  BL_GEMM_TILE overrides for experiments:
+     * loads, XCD-aware tile order, three workgroups per CU (tile id 10): about
+     * 1450 TOPS over the layer against 1310 for the register-staged 128x128
+     * kernel and ~950 for 256x256 tiles.  Deeper pipelines (4 or 6 stages) that
+     * cost occupancy measured slower: what hides the load latency is the number of
+     * workgroups per CU, not the depth.  The 64x256 tile (id 12) is equal on the
+     * N = 2560..3840 shapes and 4-9 % faster on the wide one, and wastes less when M
+     * is small.  Both need layout 1 and K % 128 == 0; other inputs use the
+     * register-staged kernel, which permutes the activation bytes for layout 0.
+     * BL_GEMM_TILE overrides for experiments:
      * 0 = 128x128x64 staged, 5 = 128x128x128 staged, 6/7/8 = 256x256 with 2x2 /
      * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages, 12 = 64x256. */
     const char* e = getenv("BL_GEMM_TILE");
     const int m = (int)M, n = (int)N, k = (int)K;
     int tile = e && *e ? atoi(e) : -1;
     const bool direct_ok = layout == 1 && k % G3_BK == 0;
-    if (tile < 0) tile = direct_ok ? 10 : (k % 128 == 0) ? 5 : 0;
+    if (tile < 0) tile = direct_ok ? ((n >= 8192 || m <= 64) ? 12 : 10) : (k % 128 == 0) ? 5 : 0;
     if (tile >= 6 && tile <= 12 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
     if (tile == 5 && k % 128) tile = 0;
     if (tile >= 6 && tile <= 12)
