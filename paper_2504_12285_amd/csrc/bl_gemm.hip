@@ -540,9 +540,9 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
      * 1450 TOPS over the layer against 1310 for the register-staged 128x128
      * kernel and ~950 for 256x256 tiles.  Deeper pipelines (4 or 6 stages) that
      * cost occupancy measured slower: what hides the load latency is the number of
-     * workgroups per CU, not the depth.  The 64x256 tile (id 12) is equal on the
-     * N = 2560..3840 shapes and 4-9 % faster on the wide one, and wastes less when M
-     * is small.  Both need layout 1 and K % 128 == 0; other inputs use the
+     * workgroups per CU, not the depth (forcing four per CU instead of three is no
+     * gain either).  The 64x256 tile (id 12) is equal within run-to-run noise and
+     * wastes less when M is small.  Both need layout 1 and K % 128 == 0; other inputs use the
      * register-staged kernel, which permutes the activation bytes for layout 0.
      * BL_GEMM_TILE overrides for experiments:
      * 0 = 128x128x64 staged, 5 = 128x128x128 staged, 6/7/8 = 256x256 with 2x2 /
@@ -551,7 +551,7 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
     const int m = (int)M, n = (int)N, k = (int)K;
     int tile = e && *e ? atoi(e) : -1;
     const bool direct_ok = layout == 1 && k % G3_BK == 0;
-    if (tile < 0) tile = direct_ok ? ((n >= 8192 || m <= 64) ? 12 : 10) : (k % 128 == 0) ? 5 : 0;
+    if (tile < 0) tile = direct_ok ? (m <= 64 ? 12 : 10) : (k % 128 == 0) ? 5 : 0;
     if (tile >= 6 && tile <= 12 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
     if (tile == 5 && k % 128) tile = 0;
     if (tile >= 6 && tile <= 12)
