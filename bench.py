@@ -27,6 +27,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
+# HBM bytes per launch, read + written, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
+# this same command (profiles/bench_decode_m1_prefill_m2048.md; counters scaled by what they read for
+# a plain 256 MiB copy: fetch x2.0, write x1.0).  Decode: the one grouped launch of a layer
+# (17.82 MB + 0.09 MB).  Prefill: the four launches of a layer at M = 2048 (252.9 MB + 186.7 MB).
+DECODE_TRAFFIC_BYTES = 17.91e6
+PREFILL_TRAFFIC_BYTES = 439.6e6
 SHAPE_ORDER = ["qkv", "o", "gate_up", "down"]
 
 
@@ -258,7 +264,7 @@ def main():
                    "packed_bytes_per_step": layer_bytes, "layout": layout, "launch": "hip graph; one bl_bitlinear_decode_group launch per step "
                                                       "(four shapes, absmax int8 quantiser fused)"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES,
                      "kernel": "bl_gemv_rows", "bytes_per_launch": bytes_per_launch,
                      "avg_launch_us": round(gemv_avg_s * 1e6, 3)},
         "decode_alternatives": alt,
@@ -326,7 +332,8 @@ def main():
                           "tops": round(tops, 2), "unit": "TOP/s", "us_per_layer": round(t_pre * 1e6, 2),
                           "per_shape": per_shape,
                           "roofline": {"bound": "mfma", "achieved": round(tops, 2), "peak": INT8_PEAK_TOPS,
-                                       "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "traffic": None,
+                                       "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
+                                       "traffic": PREFILL_TRAFFIC_BYTES if Mp == 2048 else None,
                                        "kernel": "bl_gemm_mfma"}}
 
     # ------------------------------------------- config 2: batched decode, M in {8, 32, 64}
