@@ -160,6 +160,16 @@ bl_status bl_bitlinear_decode(const uint8_t* packed, const float* beta, int layo
  *                      is given, t is also stored there (fp32 [M][K]).
  *   BL_PROD_RELU2_GATE in0 fp32 [M][2K] = [g | u]: X = bf16((max(g,0)*max(g,0))*u)
  *                      (the squared-ReLU gated FFN activation, Section 2).
+ * norm != 0 adds the sub-layer normalisation in front of the quantiser (Section 2,
+ * "Normalization"; the report names the scheme but gives no formula, so this is the
+ * bias-free RMS form): with t[k] the fp32 value of the kind above BEFORE narrowing,
+ *   ss = sum_k t[k]^2 in fp64 in a FIXED order (256 leaves: leaf j sums, ascending, the
+ *        16-element groups u = j, j+256, ..; leaves are joined by a butterfly over
+ *        strides 1,2,..,32 inside each block of 64, then (b0+b1)+(b2+b3)),
+ *   r = fp32(1 / sqrt(ss/K + eps)) in fp64,   X[k] = bf16((t[k]*r)*gain[k])
+ * (gain NULL: no second multiply).  Every step is a single rounded IEEE operation, so
+ * the result does not depend on the launch shape.  BL_PROD_RESIDUAL still stores the
+ * un-normalised sum in aux_out.
  * All pointers are device pointers, 16-byte aligned. */
 enum { BL_PROD_BF16 = 0, BL_PROD_F32 = 1, BL_PROD_ATTN_V = 2, BL_PROD_RESIDUAL = 3, BL_PROD_RELU2_GATE = 4 };
 typedef struct {
@@ -168,6 +178,9 @@ typedef struct {
     const float* in1;
     float* aux_out;
     int n_q, n_kv, head_dim;
+    int norm;               /* 0: none; 1: RMS normalisation as above */
+    const float* gain;      /* fp32 [K] or NULL */
+    float eps;              /* added to the mean square (fp32) */
 } bl_producer;
 
 /* One decode product of a group.  Give either X (bf16, fused quantiser), a

@@ -62,6 +62,12 @@ def _load():
         lib.orc_chain_residual.restype = None
         lib.orc_chain_relu2_gate.argtypes = [vp, i64, i64, vp]
         lib.orc_chain_relu2_gate.restype = None
+        lib.orc_rmsnorm_rows.argtypes = [vp, i64, i64, vp, f32, vp]
+        lib.orc_rmsnorm_rows.restype = None
+        lib.orc_chain_attn_f32.argtypes = [vp, i64, ci, ci, ci, vp]
+        lib.orc_chain_attn_f32.restype = None
+        lib.orc_chain_relu2_gate_f32.argtypes = [vp, i64, i64, vp]
+        lib.orc_chain_relu2_gate_f32.restype = None
         lib.orc_omp_threads.argtypes = []
         lib.orc_omp_threads.restype = ci
         _lib = lib
@@ -227,10 +233,58 @@ def chain_relu2_gate(gu):
     return f
 
 
-def chain_layer(x, weights, trace=None):
+def rmsnorm_rows(t, gain=None, eps=1e-5):
+    """bf16 bits of the RMS-normalised rows of t (fp32 [M][K]); fixed fp64 summation
+    order, see orc_rmsnorm_rows."""
+    t = _c(t, np.float32)
+    M, K = t.shape
+    assert K % 16 == 0
+    g = None if gain is None else _c(gain, np.float32)
+    assert g is None or g.shape == (K,)
+    out = np.empty((M, K), dtype=np.uint16)
+    _load().orc_rmsnorm_rows(_p(t), M, K, None if g is None else _p(g), float(np.float32(eps)), _p(out))
+    return out
+
+
+def chain_attn_f32(qkv, n_q=20, n_kv=5, hd=128):
+    qkv = _c(qkv, np.float32)
+    M = qkv.shape[0]
+    a = np.empty((M, n_q * hd), dtype=np.float32)
+    _load().orc_chain_attn_f32(_p(qkv), M, n_q, n_kv, hd, _p(a))
+    return a
+
+
+def chain_relu2_gate_f32(gu):
+    gu = _c(gu, np.float32)
+    M, F2 = gu.shape
+    f = np.empty((M, F2 // 2), dtype=np.float32)
+    _load().orc_chain_relu2_gate_f32(_p(gu), M, F2 // 2, _p(f))
+    return f
+
+
+def chain_layer(x, weights, trace=None, gains=None, eps=1e-5):
     """One synthetic layer of the chain on fp32 residual x [M][H].
     weights: dict name -> (Wt int8 [N][K], beta) for qkv, o, gate_up, down.
-    If trace is a list, the inputs/outputs of every BitLinear are appended."""
+    If trace is a list, the inputs/outputs of every BitLinear are appended.
+    gains: None = the norm stand-in (every BitLinear rescales with 1/127); a dict
+    name -> fp32 [K] (or None) = RMS normalisation in front of every quantiser and the
+    true absmax/127 rescale."""
+    if gains is not None:
+        def bln(name, t):
+            Wt, beta = weights[name]
+            xb = rmsnorm_rows(t, gains.get(name), eps)
+            r = bitlinear(xb, Wt, beta)
+            if trace is not None:
+                trace.append(dict(name=name, x_bf16=xb, **r))
+            return r["y"]
+
+        qkv = bln("qkv", x)
+        o = bln("o", chain_attn_f32(qkv))
+        h1 = chain_residual(x, o)
+        gu = bln("gate_up", h1)
+        dn = bln("down", chain_relu2_gate_f32(gu))
+        return chain_residual(h1, dn)
+
     def bl(name, xb):
         Wt, beta = weights[name]
         r = bitlinear(xb, Wt, beta, unit_scale=True)

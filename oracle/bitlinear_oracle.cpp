@@ -253,6 +253,68 @@ void orc_chain_relu2_gate(const float* gu, int64_t M, int64_t F, uint16_t* f) {
         }
 }
 
+/* Sub-layer normalisation in front of the quantiser (Section 2, "Normalization": the
+ * report names sub-LN and removes all biases but prints no formula; this is the bias-free
+ * RMS form).  For each row t[K] (fp32):
+ *   ss = sum_k t[k]^2, every square and every addition in fp64, in this FIXED order:
+ *        256 leaves; leaf j adds, in ascending k, the 16-element groups u = j, j+256, ..
+ *        (group u = elements 16u..16u+15); the leaves are joined inside each block of 64
+ *        by a butterfly over strides 1, 2, 4, 8, 16, 32 (new[j] = old[j] + old[j^s]) and
+ *        the four block sums as (b0 + b1) + (b2 + b3);
+ *   r  = fp32( 1 / sqrt(ss/K + eps) )   (fp64 operations, one final narrowing);
+ *   out[k] = bf16( (t[k]*r) * gain[k] )  (fp32 multiplies; gain == NULL: no second one).
+ * K % 16 == 0.  Parity pinned by closed forms and against the fp64 formula in the tests;
+ * the summation order itself is this file's reading. */
+void orc_rmsnorm_rows(const float* t, int64_t M, int64_t K, const float* gain, float eps, uint16_t* out) {
+    const int64_t groups = K / 16;
+    for (int64_t m = 0; m < M; ++m) {
+        const float* row = t + m * K;
+        double leaf[256];
+        for (int j = 0; j < 256; ++j) {
+            double p = 0.0;
+            for (int64_t u = j; u < groups; u += 256)
+                for (int e = 0; e < 16; ++e) {
+                    const double v = (double)row[u * 16 + e];
+                    p += v * v;
+                }
+            leaf[j] = p;
+        }
+        for (int s = 1; s < 64; s <<= 1) {
+            double next[256];
+            for (int j = 0; j < 256; ++j) next[j] = leaf[j] + leaf[j ^ s];
+            for (int j = 0; j < 256; ++j) leaf[j] = next[j];
+        }
+        const double ss = (leaf[0] + leaf[64]) + (leaf[128] + leaf[192]);
+        const float r = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+        for (int64_t k = 0; k < K; ++k) {
+            float v = row[k] * r;
+            if (gain) v = v * gain[k];
+            out[m * K + k] = f32_to_bf16_bits(v);
+        }
+    }
+}
+
+/* fp32 forms of the chain glue, for use in front of orc_rmsnorm_rows. */
+void orc_chain_attn_f32(const float* qkv, int64_t M, int n_q, int n_kv, int hd, float* a) {
+    const int64_t row = (int64_t)(n_q + 2 * n_kv) * hd;
+    const int group = n_q / n_kv;
+    for (int64_t m = 0; m < M; ++m)
+        for (int h = 0; h < n_q; ++h)
+            for (int d = 0; d < hd; ++d)
+                a[m * (int64_t)n_q * hd + (int64_t)h * hd + d] =
+                    qkv[m * row + (int64_t)(n_q + n_kv) * hd + (int64_t)(h / group) * hd + d];
+}
+void orc_chain_relu2_gate_f32(const float* gu, int64_t M, int64_t F, float* f) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < F; ++j) {
+            const float g = gu[m * 2 * F + j];
+            const float u = gu[m * 2 * F + F + j];
+            const float r = g > 0.0f ? g : 0.0f;
+            const float r2 = r * r;
+            f[m * F + j] = r2 * u;
+        }
+}
+
 int orc_omp_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

@@ -39,13 +39,16 @@ BL_PROD_BF16, BL_PROD_F32, BL_PROD_ATTN_V, BL_PROD_RESIDUAL, BL_PROD_RELU2_GATE 
 class Producer(ctypes.Structure):
     """Mirror of bl_producer."""
     _fields_ = [("kind", _ci), ("in0", _vp), ("in1", _vp), ("aux_out", _vp),
-                ("n_q", _ci), ("n_kv", _ci), ("head_dim", _ci)]
+                ("n_q", _ci), ("n_kv", _ci), ("head_dim", _ci),
+                ("norm", _ci), ("gain", _vp), ("eps", ctypes.c_float)]
 
 
-def make_producer(kind, in0, in1=None, aux_out=None, n_q=0, n_kv=0, head_dim=0):
+def make_producer(kind, in0, in1=None, aux_out=None, n_q=0, n_kv=0, head_dim=0, norm=False, gain=None, eps=1e-5):
+    """norm=True: RMS normalisation (optional fp32 gains [K]) in front of the quantiser."""
     p = Producer()
     p.kind, p.in0, p.in1, p.aux_out = int(kind), _ptr(in0), _ptr(in1), _ptr(aux_out)
     p.n_q, p.n_kv, p.head_dim = int(n_q), int(n_kv), int(head_dim)
+    p.norm, p.gain, p.eps = int(bool(norm)), _ptr(gain), float(eps)
     return p
 
 

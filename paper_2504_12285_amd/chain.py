@@ -5,7 +5,10 @@ arithmetic step runs inside the HIP kernels reached through the C-ABI.
 Layer, per token (tokens are independent; the glue is a stand-in, not the
 model's attention):  qkv = BL_qkv(bf16(x));  o = BL_o(bf16(V broadcast over its
 GQA group));  h1 = x + o;  gu = BL_gu(bf16(h1));  x' = h1 + BL_down(bf16(relu(g)^2 * u)).
-Every BitLinear rescales with 1/127 instead of absmax/127 (norm stand-in).
+Without gains every BitLinear rescales with 1/127 instead of absmax/127 (norm
+stand-in).  With gains (a dict name -> fp32 [K] device tensor or None per layer) the
+producers apply the RMS normalisation in front of each quantiser and the rescale uses the
+true absmax/127.
 """
 import numpy as np
 
@@ -35,28 +38,31 @@ class ChainBuffers:
         self.rowsum = torch.empty(M, dtype=torch.int32, device=device)
 
 
-def _producers(x, B):
+def _producers(x, B, gains=None, eps=1e-5):
+    def n(name):
+        return {} if gains is None else dict(norm=True, gain=gains.get(name), eps=eps)
     return {
-        "qkv": bl.make_producer(bl.BL_PROD_F32, x),
-        "o": bl.make_producer(bl.BL_PROD_ATTN_V, B.qkv, n_q=N_Q, n_kv=N_KV, head_dim=HEAD_DIM),
-        "gate_up": bl.make_producer(bl.BL_PROD_RESIDUAL, x, B.o, B.h1),
-        "down": bl.make_producer(bl.BL_PROD_RELU2_GATE, B.gu),
+        "qkv": bl.make_producer(bl.BL_PROD_F32, x, **n("qkv")),
+        "o": bl.make_producer(bl.BL_PROD_ATTN_V, B.qkv, n_q=N_Q, n_kv=N_KV, head_dim=HEAD_DIM, **n("o")),
+        "gate_up": bl.make_producer(bl.BL_PROD_RESIDUAL, x, B.o, B.h1, **n("gate_up")),
+        "down": bl.make_producer(bl.BL_PROD_RELU2_GATE, B.gu, **n("down")),
     }
 
 
-def layer_decode(weights, layout, x, B, records=None):
+def layer_decode(weights, layout, x, B, records=None, gains=None):
     """One layer for M <= 16 tokens: four fused launches (producer + quantiser +
     product + rescale [+ residual]).  weights: name -> (packed, beta).  x: fp32
     [M][2560].  Returns B.x_next (swap with x for the next layer).  If records is
     a list, int32 accumulators and quantised inputs of each BitLinear are kept."""
     import torch
     M = B.M
-    prods = _producers(x, B)
+    prods = _producers(x, B, gains)
     outs = {"qkv": B.qkv, "o": B.o, "gate_up": B.gu, "down": B.x_next}
     for name in ("qkv", "o", "gate_up", "down"):
         N, K = SHAPES[name]
         packed, beta = weights[name]
-        item = dict(packed=packed, beta=beta, N=N, K=K, y=outs[name], prod=prods[name], fixed_scale=UNIT_SCALE,
+        item = dict(packed=packed, beta=beta, N=N, K=K, y=outs[name], prod=prods[name],
+                    fixed_scale=UNIT_SCALE if gains is None else 0.0,
                     residual=B.h1 if name == "down" else None)
         if records is not None:
             item["acc"] = torch.empty((M, N), dtype=torch.int32, device=B.device)
@@ -69,12 +75,12 @@ def layer_decode(weights, layout, x, B, records=None):
     return B.x_next
 
 
-def layer_prefill(weights, layout, x, B, records=None):
+def layer_prefill(weights, layout, x, B, records=None, gains=None):
     """One layer for any M: producer+quantiser kernel, then the matrix-core
     product (residual fused into the last epilogue)."""
     import torch
     M = B.M
-    prods = _producers(x, B)
+    prods = _producers(x, B, gains)
     outs = {"qkv": B.qkv, "o": B.o, "gate_up": B.gu, "down": B.x_next}
     for name in ("qkv", "o", "gate_up", "down"):
         N, K = SHAPES[name]
@@ -82,23 +88,25 @@ def layer_prefill(weights, layout, x, B, records=None):
         q = B.q["f" if K == 6912 else "h"]
         bl.bl_quant_act_ex(prods[name], M, K, B.device, q=q, scale=B.scale, rowsum=B.rowsum)
         acc = torch.empty((M, N), dtype=torch.int32, device=B.device) if records is not None else None
-        bl.bl_gemm_w158a8_res(packed, beta, layout, q, B.unit, B.rowsum, N, B.h1 if name == "down" else None,
+        bl.bl_gemm_w158a8_res(packed, beta, layout, q, B.unit if gains is None else B.scale, B.rowsum, N,
+                              B.h1 if name == "down" else None,
                               want_acc=records is not None, acc=acc, y=outs[name])
         if records is not None:
             records.append(dict(name=name, acc=acc, q=q.clone(), scale=B.scale.clone(), y=outs[name].clone()))
     return B.x_next
 
 
-def run_chain(layer_weights, layout, x0, mode="decode", records=None):
+def run_chain(layer_weights, layout, x0, mode="decode", records=None, layer_gains=None):
     """Runs x0 (fp32 [M][2560], device) through the given layers.  mode: "decode"
-    (M <= 16, fused launches) or "prefill".  Returns the final x (a device tensor)."""
+    (M <= 16, fused launches) or "prefill".  layer_gains: None, or one gains dict per layer
+    (RMS normalisation on).  Returns the final x (a device tensor)."""
     M = x0.shape[0]
     B = ChainBuffers(M, x0.device)
     x = x0.clone()
     step = layer_decode if mode == "decode" else layer_prefill
     for li, w in enumerate(layer_weights):
         rec = [] if records is not None else None
-        out = step(w, layout, x, B, rec)
+        out = step(w, layout, x, B, rec, None if layer_gains is None else layer_gains[li])
         if records is not None:
             records.append(rec)
         B.x_next, x = x, out          # ping-pong: the old input becomes the next output buffer

@@ -121,7 +121,7 @@ __device__ __forceinline__ void bl_dot_chunk(const bl_v4i p, const bl_v4i* __res
  * before anything else, so the HBM latency overlaps the activation staging; the
  * G lanes of a row are summed with DPP, k-parts through LDS.
  * Dynamic LDS: M*K bytes of staged activations + M ints + (M+4) floats + 64*M ints. */
-template <int M, int G, int L>
+template <int M, int G, int L, bool NORM>
 __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     extern __shared__ int lds[];
     constexpr int R = 64 / G;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     const int groups = K / 16;
     uint4 xv[4];
     bl_v4i qv = {0, 0, 0, 0};
-    const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16;
+    const bool pre_bf16 = P.fused && P.prod.kind == BL_PROD_BF16 && !(NORM && P.prod.norm);
     const bool first_block = blockIdx.x == (unsigned)P.block0;
     if (pre_bf16) {
 #pragma unroll
@@ -183,18 +183,20 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
          * Each thread keeps its (at most two) 16-element groups in registers. */
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
+            float rn = 1.0f;
+            if (NORM && P.prod.norm) rn = bl_norm_factor(P.prod, m, K, (double*)red);
             float mx = 0.0f;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int u = tid + j * 256;
                 if (u < groups) {
-                    if (m > 0 || !pre_bf16) bl_produce16(P.prod, m, u, K, first_block, xv[2 * j], xv[2 * j + 1]);
+                    if (m > 0 || !pre_bf16) bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, xv[2 * j], xv[2 * j + 1]);
                     mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }
             for (int u = tid + 512; u < groups; u += 256) {
                 uint4 lo, hi;
-                bl_produce16(P.prod, m, u, K, false, lo, hi);
+                bl_produce16<NORM>(P.prod, m, u, K, false, rn, lo, hi);
                 mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
             }
             mx = bl_wave_max(mx);
@@ -220,7 +222,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
             for (int u = tid + 512; u < groups; u += 256) {
                 uint32_t a0, a1, a2, a3;
                 uint4 lo, hi;
-                bl_produce16(P.prod, m, u, K, first_block, lo, hi);
+                bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, lo, hi);
                 bl_quant8_words(lo, inv, a0, a1);
                 bl_quant8_words(hi, inv, a2, a3);
                 part += bl_sum16(a0, a1, a2, a3);
@@ -328,7 +330,7 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
  * next phase are in flight during the products of the current one.  Fused
  * inputs: produced, quantised and staged whole, one token at a time.
  * Dynamic LDS: BL_MMA_HEAD ints, then max(M*(row+16), MT*4096) bytes. */
-template <int L, int MT, bool NEED_SUM>
+template <int L, int MT, bool NEED_SUM, bool NORM>
 __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LF, const int budget) {
     extern __shared__ int lds[];
     BL_STAMP_DECL;
@@ -394,7 +396,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
 
     /* 1. activation loads first (token 0 of the fused path, or the first phase of q) */
     uint4 xv[4];
-    const bool pre_bf16 = fused && P.prod.kind == BL_PROD_BF16;
+    const bool pre_bf16 = fused && P.prod.kind == BL_PROD_BF16 && !(NORM && P.prod.norm);
     const bool first_block = blockIdx.x == (unsigned)P.block0;
     if (pre_bf16) {
 #pragma unroll
@@ -447,18 +449,20 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     if (fused) {
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
+            float rn = 1.0f;
+            if (NORM && P.prod.norm) rn = bl_norm_factor(P.prod, m, K, (double*)frs);
             float mx = 0.0f;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int u = tid + j * 256;
                 if (u < groups) {
-                    if (m > 0 || !pre_bf16) bl_produce16(P.prod, m, u, K, first_block, xv[2 * j], xv[2 * j + 1]);
+                    if (m > 0 || !pre_bf16) bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, xv[2 * j], xv[2 * j + 1]);
                     mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }
             for (int u = tid + 512; u < groups; u += 256) {
                 uint4 lo, hi;
-                bl_produce16(P.prod, m, u, K, false, lo, hi);
+                bl_produce16<NORM>(P.prod, m, u, K, false, rn, lo, hi);
                 mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
             }
             mx = bl_wave_max(mx);
@@ -484,7 +488,7 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             for (int u = tid + 512; u < groups; u += 256) {
                 uint32_t a0, a1, a2, a3;
                 uint4 lo, hi;
-                bl_produce16(P.prod, m, u, K, first_block, lo, hi);
+                bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, lo, hi);
                 bl_quant8_words(lo, inv, a0, a1);
                 bl_quant8_words(hi, inv, a2, a3);
                 if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
@@ -638,24 +642,24 @@ static int bl_env_int(const char* name, int dflt) {
     return e && *e ? atoi(e) : dflt;
 }
 
-template <int M, int G, int L>
+template <int M, int G, int L, bool NORM>
 static bl_status launch_rows(const bl_gemv_group& grp, int blocks, int maxK, hipStream_t st) {
     const size_t lds = (size_t)M * maxK + (size_t)M * 4 + (size_t)(M + 4) * 4 + (size_t)64 * M * 4;
     if (lds > 64 * 1024) return BL_ERR_SHAPE;
-    bl_gemv_rows<M, G, L><<<blocks, 256, lds, st>>>(grp);
+    bl_gemv_rows<M, G, L, NORM><<<blocks, 256, lds, st>>>(grp);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
-template <int M, int G>
+template <int M, int G, bool NORM = false>
 static bl_status launch_rows_l(int L, const bl_gemv_group& grp, int blocks, int maxK, hipStream_t st) {
-    if (L <= 2) return launch_rows<M, G, 2>(grp, blocks, maxK, st);
-    if (L <= 4) return launch_rows<M, G, 4>(grp, blocks, maxK, st);
-    if (L <= 8) return launch_rows<M, G, 8>(grp, blocks, maxK, st);
-    if (L <= 16) return launch_rows<M, G, 16>(grp, blocks, maxK, st);
-    return launch_rows<M, G, 32>(grp, blocks, maxK, st);
+    if (L <= 2) return launch_rows<M, G, 2, NORM>(grp, blocks, maxK, st);
+    if (L <= 4) return launch_rows<M, G, 4, NORM>(grp, blocks, maxK, st);
+    if (L <= 8) return launch_rows<M, G, 8, NORM>(grp, blocks, maxK, st);
+    if (L <= 16) return launch_rows<M, G, 16, NORM>(grp, blocks, maxK, st);
+    return launch_rows<M, G, 32, NORM>(grp, blocks, maxK, st);
 }
 
-template <int L, int MT>
+template <int L, int MT, bool NORM = false>
 static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStream_t st) {
     /* LDS budget for the staged rows: nearly all of it when every workgroup gets a CU of its
      * own, else small enough for two workgroups per CU.  int8 inputs that do not fit whole
@@ -674,7 +678,9 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStre
         if (need > rows) rows = need;
     }
     const size_t lds = rows + BL_MMA_HEAD * 4;
-    auto kern = have_sums ? bl_gemv_mma<L, MT, false> : bl_gemv_mma<L, MT, true>;
+    /* normalising producers are fused inputs: those never bring row sums */
+    auto kern = NORM ? bl_gemv_mma<L, MT, true, NORM>
+                     : (have_sums ? bl_gemv_mma<L, MT, false, false> : bl_gemv_mma<L, MT, true, false>);
     if (lds > 160 * 1024) return BL_ERR_SHAPE;
     if (lds > 64 * 1024) {
         static bool done[2] = {false, false};
@@ -689,13 +695,13 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStre
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
-template <int MT>
+template <int MT, bool NORM = false>
 static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks, hipStream_t st) {
-    if (L <= 2) return launch_mma<2, MT>(grp, M, blocks, st);
-    if (L <= 4) return launch_mma<4, MT>(grp, M, blocks, st);
-    if (L <= 8) return launch_mma<8, MT>(grp, M, blocks, st);
-    if (L <= 16) return launch_mma<16, MT>(grp, M, blocks, st);
-    return launch_mma<32, MT>(grp, M, blocks, st);
+    if (L <= 2) return launch_mma<2, MT, NORM>(grp, M, blocks, st);
+    if (L <= 4) return launch_mma<4, MT, NORM>(grp, M, blocks, st);
+    if (L <= 8) return launch_mma<8, MT, NORM>(grp, M, blocks, st);
+    if (L <= 16) return launch_mma<16, MT, NORM>(grp, M, blocks, st);
+    return launch_mma<32, MT, NORM>(grp, M, blocks, st);
 }
 
 /* Lays the products of a group out over workgroups and launches them.  All
@@ -707,8 +713,10 @@ static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks
 bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
     const char* path_env = getenv("BL_GEMV_PATH");
     const bool dot4 = M <= 4 && !(path_env && path_env[0] == 'm');
+    bool any_norm = false;
+    for (int i = 0; i < grp.count; ++i) any_norm = any_norm || (grp.p[i].fused && grp.p[i].prod.norm);
     int G = dot4 ? bl_env_int("BL_GEMV_G", 8) : 4;
-    if (G != 4 && G != 8) G = 8;
+    if ((G != 4 && G != 8) || (dot4 && any_norm)) G = 8;
     const int force_split = bl_env_int("BL_GEMV_KSPLIT", 0);
     /* workgroups wanted per product, measured: 150 for a product alone (best of 40..700) and
      * for the dot4 kernel; the matrix-core kernel, whose workgroups each stage all M rows,
@@ -730,6 +738,17 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
         if (l > L) L = l;
     }
     if (L > 32) return BL_ERR_SHAPE;
+    if (any_norm) {
+        /* normalising variants exist for the default lane split of the dot4 kernel and for
+         * one token tile of the matrix-core kernel (fused inputs have M <= 16) */
+        if (!dot4) return M <= 16 ? launch_mma_l<1, true>(L, grp, M, blocks, st) : BL_ERR_SHAPE;
+        switch (M) {
+            case 1: return launch_rows_l<1, 8, true>(L, grp, blocks, maxK, st);
+            case 2: return launch_rows_l<2, 8, true>(L, grp, blocks, maxK, st);
+            case 3: return launch_rows_l<3, 8, true>(L, grp, blocks, maxK, st);
+            default: return launch_rows_l<4, 8, true>(L, grp, blocks, maxK, st);
+        }
+    }
     if (!dot4) {
         if (M <= 16) return launch_mma_l<1>(L, grp, M, blocks, st);
         if (M <= 32) return launch_mma_l<2>(L, grp, M, blocks, st);

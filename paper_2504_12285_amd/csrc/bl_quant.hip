@@ -82,26 +82,31 @@ __global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows(const uint4* __re
 /* Producer + quantiser: the bf16 row is produced on the fly (bl_produce16) and
  * kept in registers between the absmax pass and the quantise pass (two
  * 16-element groups per thread cover K <= 8192; longer rows are produced twice). */
+template <bool NORM>
 __global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows_ex(const bl_prod_dev pd, int K,
                                                                    int8_t* __restrict__ q, float* __restrict__ scale,
                                                                    int32_t* __restrict__ rowsum) {
     __shared__ float smax[QUANT_THREADS / BL_WAVE];
     __shared__ int ssum[QUANT_THREADS / BL_WAVE];
+    __shared__ double snorm[4];
+    static_assert(QUANT_THREADS == 256, "the normalisation tree has 256 leaves");
     const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int groups = K / 16;
     uint4 xv[4];
+    float rn = 1.0f;
+    if (NORM) rn = bl_norm_factor(pd, m, K, snorm);
     float mx = 0.0f;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int u = tid + j * QUANT_THREADS;
         if (u < groups) {
-            bl_produce16(pd, m, u, K, true, xv[2 * j], xv[2 * j + 1]);
+            bl_produce16<NORM>(pd, m, u, K, true, rn, xv[2 * j], xv[2 * j + 1]);
             mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
         }
     }
     for (int u = tid + 2 * QUANT_THREADS; u < groups; u += QUANT_THREADS) {
         uint4 lo, hi;
-        bl_produce16(pd, m, u, K, true, lo, hi);
+        bl_produce16<NORM>(pd, m, u, K, true, rn, lo, hi);
         mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
     }
     mx = bl_wave_max(mx);
@@ -128,7 +133,7 @@ __global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows_ex(const bl_prod_
     for (int u = tid + 2 * QUANT_THREADS; u < groups; u += QUANT_THREADS) {
         uint4 lo, hi;
         uint32_t a0, a1, a2, a3;
-        bl_produce16(pd, m, u, K, false, lo, hi);
+        bl_produce16<NORM>(pd, m, u, K, false, rn, lo, hi);
         bl_quant8_words(lo, inv, a0, a1);
         bl_quant8_words(hi, inv, a2, a3);
         sum += bl_sum16(a0, a1, a2, a3);
@@ -156,7 +161,8 @@ extern "C" bl_status bl_quant_act_ex(const bl_producer* prod, int64_t M, int64_t
     bl_prod_dev pd;
     if (!prod->in0) return BL_ERR_NULL;
     if (!bl_make_prod(*prod, nullptr, K, &pd)) return BL_ERR_VALUE;
-    bl_quant_rows_ex<<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>(pd, (int)K, q, scale, rowsum);
+    if (pd.norm) bl_quant_rows_ex<true><<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>(pd, (int)K, q, scale, rowsum);
+    else bl_quant_rows_ex<false><<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>(pd, (int)K, q, scale, rowsum);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 

@@ -84,6 +84,66 @@ def test_producers_match_oracle_glue(bl, M):
     assert np.array_equal(q.cpu().numpy(), q_o) and np.array_equal(s.cpu().numpy(), s_o)
 
 
+def _gain(seed, K):
+    """Synthetic gains around 1 (no trained gains exist here)."""
+    return (1.0 + 0.25 * np.random.default_rng(seed).standard_normal(K)).astype(np.float32)
+
+
+@pytest.mark.parametrize("M", [1, 3, 6])
+@pytest.mark.parametrize("with_gain", [False, True])
+def test_normalising_producers_match_oracle(bl, M, with_gain):
+    """RMS normalisation in front of the quantiser, every producer kind, through the
+    prefill quantiser kernel and through the fused decode kernels (dot4 and matrix-core)."""
+    rng = np.random.default_rng(11)
+    dev = "cuda:0"
+    x = (rng.standard_normal((M, 2560)) * 3).astype(np.float32)
+    x[:, 7] *= 40.0
+    o = rng.standard_normal((M, 2560)).astype(np.float32)
+    qkv = rng.standard_normal((M, 3840)).astype(np.float32)
+    gu = rng.standard_normal((M, 13824)).astype(np.float32)
+    xb = oracle.f32_to_bf16(x)
+    keep = dict(x=to_dev(x), o=to_dev(o), qkv=to_dev(qkv), gu=to_dev(gu), xb=to_dev(xb),
+                h1=torch.empty((M, 2560), dtype=torch.float32, device=dev))
+    gains = {K: (_gain(K, K) if with_gain else None) for K in (2560, 6912)}
+    dgain = {K: (to_dev(g) if g is not None else None) for K, g in gains.items()}
+    nk = lambda K: dict(norm=True, gain=dgain[K], eps=1e-5)
+    cases = [
+        ("f32", bl.make_producer(bl.BL_PROD_F32, keep["x"], **nk(2560)), 2560, x),
+        ("attn", bl.make_producer(bl.BL_PROD_ATTN_V, keep["qkv"], n_q=20, n_kv=5, head_dim=128, **nk(2560)), 2560,
+         oracle.chain_attn_f32(qkv)),
+        ("relu2", bl.make_producer(bl.BL_PROD_RELU2_GATE, keep["gu"], **nk(6912)), 6912,
+         oracle.chain_relu2_gate_f32(gu)),
+        ("bf16", bl.make_producer(bl.BL_PROD_BF16, keep["xb"], **nk(2560)), 2560, synth.bf16_bits_to_f32(xb)),
+        ("residual", bl.make_producer(bl.BL_PROD_RESIDUAL, keep["x"], keep["o"], keep["h1"], **nk(2560)), 2560,
+         oracle.chain_residual(x, o)),
+    ]
+    N = 128
+    for name, prod, K, t in cases:
+        want_bits = oracle.rmsnorm_rows(t, gains[K], 1e-5)
+        q_o, s_o, r_o = oracle.quant_act(want_bits)
+        q, s, r = bl.bl_quant_act_ex(prod, M, K, dev)
+        torch.cuda.synchronize()
+        assert np.array_equal(q.cpu().numpy(), q_o), name
+        assert np.array_equal(s.cpu().numpy().view(np.uint32), s_o.view(np.uint32)), name
+        assert np.array_equal(r.cpu().numpy(), r_o), name
+        if name == "residual":
+            assert np.array_equal(keep["h1"].cpu().numpy().view(np.uint32), t.view(np.uint32))
+        # the same producer inside the decode kernel
+        Wt = synth.uniform_i8(60, (N, K), -1, 1)
+        ref = oracle.bitlinear(want_bits, Wt, np.float32(0.75))
+        it = dict(packed=to_dev(oracle.pack(Wt, 1)), beta=to_dev(np.array([0.75], dtype=np.float32)), N=N, K=K,
+                  prod=prod, acc=torch.empty((M, N), dtype=torch.int32, device=dev),
+                  y=torch.empty((M, N), dtype=torch.float32, device=dev),
+                  q_out=torch.empty((M, K), dtype=torch.int8, device=dev),
+                  scale_out=torch.empty(M, dtype=torch.float32, device=dev))
+        bl.bl_bitlinear_decode_group(bl.make_decode_descs([it]), 1, M)
+        torch.cuda.synchronize()
+        assert np.array_equal(it["q_out"].cpu().numpy(), ref["q"]), name
+        assert np.array_equal(it["scale_out"].cpu().numpy(), ref["scale"]), name
+        assert np.array_equal(it["acc"].cpu().numpy(), ref["acc"]), name
+        assert_y_close(it["y"].cpu().numpy(), ref["y"])
+
+
 def test_bad_producer_is_rejected(bl):
     x = torch.zeros((1, 2560), device="cuda:0")
     with pytest.raises(bl.BitLinearError):
@@ -95,12 +155,13 @@ def test_bad_producer_is_rejected(bl):
 
 
 # ---------------------------------------------------------------------- chain
-def _oracle_chain(x0, layers):
+def _oracle_chain(x0, layers, layer_gains=None):
     x = x0
     traces = []
-    for ow in layers:
+    for li, ow in enumerate(layers):
         tr = []
-        x = oracle.chain_layer(x, {k: (v[0], v[1]) for k, v in ow.items()}, trace=tr)
+        x = oracle.chain_layer(x, {k: (v[0], v[1]) for k, v in ow.items()}, trace=tr,
+                               gains=None if layer_gains is None else layer_gains[li])
         traces.append(tr)
     return x, traces
 
@@ -123,6 +184,24 @@ def test_chain_two_layers(bl, chain, mode, M):
     want, traces = _oracle_chain(x0, layers)
     recs = []
     got = chain.run_chain(gws, 1, to_dev(x0), mode=mode, records=recs)
+    torch.cuda.synchronize()
+    _compare_records(recs, traces)
+    assert_y_close(got.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("mode,M", [("decode", 1), ("decode", 9), ("prefill", 150)])
+def test_chain_two_layers_with_normalisation(bl, chain, mode, M):
+    """The chain with the RMS normalisation in front of every quantiser and the true
+    absmax/127 rescale (no stand-in)."""
+    layers = [_layer_weights(4, l) for l in range(2)]
+    gws = [_to_gpu_weights(bl, ow) for ow in layers]
+    ogains = [{name: _gain(100 * l + i, SHAPES[name][1]) for i, name in enumerate(SHAPES)} for l in range(2)]
+    ogains[1]["o"] = None          # a site without gains
+    dgains = [{k: (to_dev(v) if v is not None else None) for k, v in g.items()} for g in ogains]
+    x0 = synth.bf16_bits_to_f32(synth.activations_bf16(4, M, 2560, layer=98))
+    want, traces = _oracle_chain(x0, layers, ogains)
+    recs = []
+    got = chain.run_chain(gws, 1, to_dev(x0), mode=mode, records=recs, layer_gains=dgains)
     torch.cuda.synchronize()
     _compare_records(recs, traces)
     assert_y_close(got.cpu().numpy(), want)

@@ -425,3 +425,54 @@ def test_chain_layer_stays_bounded_and_is_token_independent():
     assert np.all(np.isfinite(out)) and np.abs(out).max() < 1e4
     one = run(x0[2:3], layers)
     assert np.array_equal(one[0], out[2])
+
+
+# --------------------------------------------------------------- RMS normalisation
+def _bf16_to_f32(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def test_rmsnorm_closed_forms():
+    """Rows whose mean square is known exactly (Section 2 names the normalisation; the
+    formula pinned here is the bias-free RMS form)."""
+    K = 512
+    # constant row c: ss = K*c^2 exactly in fp64, r = 1/sqrt(c^2 + eps)
+    for c in (1.0, -2.0, 0.5, 3.0):
+        t = np.full((1, K), c, dtype=np.float32)
+        r = np.float32(1.0 / np.sqrt(np.float64(c) * np.float64(c) + np.float64(np.float32(1e-5))))
+        want = oracle.f32_to_bf16(np.full((1, K), np.float32(c) * r, dtype=np.float32))
+        assert np.array_equal(oracle.rmsnorm_rows(t, None, 1e-5), want)
+    # zero row: r = 1/sqrt(eps) is finite, output exactly +0
+    z = oracle.rmsnorm_rows(np.zeros((1, K), np.float32), None, 1e-5)
+    assert not z.any()
+    # a single spike s at k=3: ss/K = s^2/K; the output there is s*r, elsewhere 0
+    t = np.zeros((1, K), np.float32)
+    t[0, 3] = 16.0
+    r = np.float32(1.0 / np.sqrt(256.0 / K + np.float64(np.float32(1e-5))))
+    out = _bf16_to_f32(oracle.rmsnorm_rows(t, None, 1e-5))
+    assert out[0, 3] == _bf16_to_f32(oracle.f32_to_bf16(np.array([np.float32(16.0) * r])))[0]
+    assert not np.delete(out[0], 3).any()
+    # eps sits inside the root, added to the MEAN (not the sum): with eps = 3 and a unit row, r = 1/2
+    t = np.ones((2, 64), np.float32)
+    assert np.all(_bf16_to_f32(oracle.rmsnorm_rows(t, None, 3.0)) == 0.5)
+
+
+def test_rmsnorm_against_fp64_formula_and_gains():
+    rng = np.random.default_rng(5)
+    for K in (64, 2560, 6912):
+        t = (rng.standard_normal((5, K)) * rng.uniform(0.1, 30.0, size=(5, 1))).astype(np.float32)
+        t[:, 1] *= 50.0
+        g = (1.0 + 0.3 * rng.standard_normal(K)).astype(np.float32)
+        ref = t.astype(np.float64) / np.sqrt((t.astype(np.float64) ** 2).mean(axis=1, keepdims=True) + 1e-5)
+        for gain, refg in ((None, ref), (g, ref * g.astype(np.float64))):
+            out = _bf16_to_f32(oracle.rmsnorm_rows(t, gain, 1e-5)).astype(np.float64)
+            # bf16 keeps 8 significant bits: half an ulp is at most 2^-8 relative; the fp32 steps add ~1e-7
+            assert np.all(np.abs(out - refg) <= np.abs(refg) * (2.0 ** -8 + 1e-6) + 1e-30)
+            assert np.mean(np.abs(out - refg) <= np.abs(refg) * 2.0 ** -9) > 0.6   # and usually half of that
+        # rows are independent and the gain is elementwise
+        one = oracle.rmsnorm_rows(t[2:3], g, 1e-5)
+        assert np.array_equal(one, oracle.rmsnorm_rows(t, g, 1e-5)[2:3])
+    # unit RMS after normalisation (before narrowing the mean square is 1 up to eps)
+    t = rng.standard_normal((3, 4096)).astype(np.float32) * 7
+    out = _bf16_to_f32(oracle.rmsnorm_rows(t, None, 1e-5)).astype(np.float64)
+    assert np.all(np.abs(np.sqrt((out ** 2).mean(axis=1)) - 1.0) < 2e-3)
