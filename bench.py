@@ -413,6 +413,24 @@ def main():
             n_tok = 50
             t_tok, _ = time_graph_steps(torch, [(g, 1, n_tok)], n_tok)
         t_tok /= n_tok
+        # the same chain with the RMS normalisation in front of every quantiser (gains: ones
+        # perturbed by a seeded 5 %; no trained gains exist here) and the true absmax/127 rescale
+        rng = np.random.default_rng(7)
+        gains = {n: torch.from_numpy((1.0 + 0.05 * rng.standard_normal(synth.LAYER_SHAPES[n][1])).astype(np.float32)).to(dev)
+                 for n in SHAPE_ORDER}
+
+        def decode_token_norm():
+            x, Bd.x_next = xa, xb
+            for w in wts:
+                nxt = chain.layer_decode(w, layout, x, Bd, gains=gains)
+                Bd.x_next, x = x, nxt
+        with torch.cuda.stream(side):
+            decode_token_norm()
+            torch.cuda.synchronize()
+            g = capture(torch, decode_token_norm)
+            g.replay()
+            t_tokn, _ = time_graph_steps(torch, [(g, 1, n_tok)], n_tok)
+        t_tokn /= n_tok
         Mc = 4096
         xp = torch.from_numpy(synth.bf16_bits_to_f32(synth.activations_bf16(0, Mc, 2560, layer=101))).to(dev)
         Bp = chain.ChainBuffers(Mc, dev)
@@ -433,6 +451,9 @@ def main():
                                          "product+rescale+residual), hip graph" % nl,
                              "us_per_token": round(t_tok * 1e6, 1), "us_per_launch": round(t_tok * 1e6 / (4 * nl), 2),
                              "GBps": round(nl * layer_bytes / t_tok / 1e9, 1)},
+            "decode_chain_rmsnorm": {"workload": "the same with the RMS normalisation fused in front of each quantiser",
+                                     "us_per_token": round(t_tokn * 1e6, 1),
+                                     "us_per_launch": round(t_tokn * 1e6 / (4 * nl), 2)},
             "prefill_chain": {"workload": "%d chained layers, M=%d, producer+quantiser kernel then product" % (nl, Mc),
                               "ms": round(t_stack * 1e3, 3), "tops_products_only_ops": round(ops_stack / t_stack / 1e12, 1)}}
         log("[bench] config 4: %s" % out["config4"])
