@@ -184,13 +184,17 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
             float rn = 1.0f;
-            if (NORM && P.prod.norm) rn = bl_norm_factor(P.prod, m, K, (double*)red);
+            bool have_xv = pre_bf16 && m == 0;
+            if (NORM && P.prod.norm) {
+                rn = bl_norm_produce2(P.prod, m, K, first_block, (double*)red, xv);
+                have_xv = true;
+            }
             float mx = 0.0f;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int u = tid + j * 256;
                 if (u < groups) {
-                    if (m > 0 || !pre_bf16) bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, xv[2 * j], xv[2 * j + 1]);
+                    if (!have_xv) bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, xv[2 * j], xv[2 * j + 1]);
                     mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }
@@ -450,13 +454,17 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
             float rn = 1.0f;
-            if (NORM && P.prod.norm) rn = bl_norm_factor(P.prod, m, K, (double*)frs);
+            bool have_xv = pre_bf16 && m == 0;
+            if (NORM && P.prod.norm) {
+                rn = bl_norm_produce2(P.prod, m, K, first_block, (double*)frs, xv);
+                have_xv = true;
+            }
             float mx = 0.0f;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int u = tid + j * 256;
                 if (u < groups) {
-                    if (m > 0 || !pre_bf16) bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, xv[2 * j], xv[2 * j + 1]);
+                    if (!have_xv) bl_produce16<NORM>(P.prod, m, u, K, first_block, rn, xv[2 * j], xv[2 * j + 1]);
                     mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }

@@ -113,13 +113,27 @@ __device__ __forceinline__ void bl_produce16(const bl_prod_dev& pd, int m, int u
                     bl_pack2_bf16(v[14], v[15]));
 }
 
-/* The normalisation factor of token m, computed by a 256-thread workgroup in the fixed
- * order of the public header: thread j is leaf j.  s4: four doubles of LDS, free to reuse
- * after the next barrier of the caller.  Contains one barrier. */
-__device__ __forceinline__ float bl_norm_factor(const bl_prod_dev& pd, int m, int K, double* s4) {
+/* Normalising production of token m by a 256-thread workgroup, in the fixed order of the
+ * public header (thread j is leaf j).  The thread's first two groups (u = tid, tid + 256) are
+ * produced once, kept in registers across the reduction and returned as normalised bf16 words
+ * in xv[0..3]; groups beyond those (K > 8192) only enter the sum and are produced again by the
+ * caller with the returned factor.  store_aux as in bl_produce16_f32.  s4: four doubles of LDS,
+ * free to reuse after the caller's next barrier.  Contains one barrier. */
+__device__ __forceinline__ float bl_norm_produce2(const bl_prod_dev& pd, int m, int K, bool store_aux, double* s4,
+                                                  uint4 xv[4]) {
     const int tid = threadIdx.x, groups = K / 16;
+    float tv[2][16];
     double part = 0.0;
-    for (int u = tid; u < groups; u += 256) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int u = tid + j * 256;
+        if (u < groups) {
+            bl_produce16_f32(pd, m, u, K, store_aux, tv[j]);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) part += (double)tv[j][e] * (double)tv[j][e];
+        }
+    }
+    for (int u = tid + 512; u < groups; u += 256) {
         float v[16];
         bl_produce16_f32(pd, m, u, K, false, v);
 #pragma unroll
@@ -130,7 +144,29 @@ __device__ __forceinline__ float bl_norm_factor(const bl_prod_dev& pd, int m, in
     if ((tid & 63) == 0) s4[tid >> 6] = part;
     __syncthreads();
     const double ss = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-    return (float)(1.0 / sqrt(ss / (double)K + (double)pd.eps));
+    const float rn = (float)(1.0 / sqrt(ss / (double)K + (double)pd.eps));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int u = tid + j * 256;
+        if (u < groups) {
+            float* v = tv[j];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) v[e] = v[e] * rn;
+            if (pd.gain) {
+                const float4* g4 = (const float4*)(pd.gain + (int64_t)u * 16);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 g = g4[q];
+                    v[4 * q] *= g.x; v[4 * q + 1] *= g.y; v[4 * q + 2] *= g.z; v[4 * q + 3] *= g.w;
+                }
+            }
+            xv[2 * j] = make_uint4(bl_pack2_bf16(v[0], v[1]), bl_pack2_bf16(v[2], v[3]), bl_pack2_bf16(v[4], v[5]),
+                                   bl_pack2_bf16(v[6], v[7]));
+            xv[2 * j + 1] = make_uint4(bl_pack2_bf16(v[8], v[9]), bl_pack2_bf16(v[10], v[11]),
+                                       bl_pack2_bf16(v[12], v[13]), bl_pack2_bf16(v[14], v[15]));
+        }
+    }
+    return rn;
 }
 
 /* Quantise 8 bf16 (one uint4) to two dwords of int8: q = clamp(rint(x*inv), -127, 127). */

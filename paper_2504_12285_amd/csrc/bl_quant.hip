@@ -94,13 +94,13 @@ __global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows_ex(const bl_prod_
     const int groups = K / 16;
     uint4 xv[4];
     float rn = 1.0f;
-    if (NORM) rn = bl_norm_factor(pd, m, K, snorm);
+    if (NORM) rn = bl_norm_produce2(pd, m, K, true, snorm, xv);
     float mx = 0.0f;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int u = tid + j * QUANT_THREADS;
         if (u < groups) {
-            bl_produce16<NORM>(pd, m, u, K, true, rn, xv[2 * j], xv[2 * j + 1]);
+            if (!NORM) bl_produce16<NORM>(pd, m, u, K, true, rn, xv[2 * j], xv[2 * j + 1]);
             mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
         }
     }
