@@ -146,6 +146,18 @@ def test_gemv_batched_phases_and_tails(bl, M, N, K):
         assert_y_close(y, c.y)
 
 
+@pytest.mark.parametrize("M", [1, 3, 40])
+def test_long_rows_beyond_the_decode_kernels(bl, M):
+    """K above 8192: the decode entry point hands over to the prefill kernel; the int32 sums
+    reach 16,384 terms.  Both layouts (layout 0 takes the register-staged kernel)."""
+    c = Case(36, M, 68, 16384)
+    for layout in (0, 1):
+        for fn in (bl.bl_gemv_w158a8, bl.bl_gemm_w158a8):
+            acc, y = _run_product(bl, fn, c, layout, use_rowsum=(layout == 0))
+            assert np.array_equal(acc, c.acc)
+            assert_y_close(y, c.y)
+
+
 @pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
 @pytest.mark.parametrize("M", [1, 4])
 def test_gemv_layer_shapes(bl, name, M):
