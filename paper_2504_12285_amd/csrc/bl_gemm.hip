@@ -486,7 +486,8 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
  * with two stages, 4 / 5 = 128x128 2x2 waves with two / three stages (three / two workgroups
  * per CU), 6 = 64x256 1x4 waves with three stages (a tile wider in N than in M moves fewer
  * bytes per operation, packed weights costing a quarter of a byte; measured equal to 128x128
- * at M = 2048) */
+ * at M = 2048), 7 = 64x128 1x4 waves with two stages (twice the workgroups: for problems with
+ * few tiles) */
 static bl_status launch_tile256(int variant, const uint8_t* packed, const float* beta, const int8_t* q,
                                 const float* scale, const int32_t* rowsum, int M, int N, int K,
                                 const float* residual, int32_t* acc, float* y, hipStream_t st) {
@@ -499,6 +500,7 @@ static bl_status launch_tile256(int variant, const uint8_t* packed, const float*
         case 4: return BL_TILE(128, 128, 2, 2, 2);
         case 5: return BL_TILE(128, 128, 3, 2, 2);
         case 6: return BL_TILE(64, 256, 3, 1, 4);
+        case 7: return BL_TILE(64, 128, 2, 1, 4);
         default: return BL_TILE(256, 256, 3, 2, 2);
     }
 #undef BL_TILE
@@ -541,20 +543,24 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
      * kernel and ~950 for 256x256 tiles.  Deeper pipelines (4 or 6 stages) that
      * cost occupancy measured slower: what hides the load latency is the number of
      * workgroups per CU, not the depth (forcing four per CU instead of three is no
-     * gain either).  The 64x256 tile (id 12) is equal within run-to-run noise and
-     * wastes less when M is small.  Both need layout 1 and K % 128 == 0; other inputs use the
+     * gain either).  The 64x256 tile (id 12) is equal within run-to-run noise.  When
+     * the problem has at most ~1.5 tiles of 128x128 per CU, 64x128 tiles (id 13) balance
+     * better: +17..21 % on the N = 2560 shapes at M = 2048 (1220 / 1690 against 1010 /
+     * 1450 TOPS), +22..27 % on every small shape at M = 1024, equal at 480 tiles and
+     * slower on the wide shape.  All need layout 1 and K % 128 == 0; other inputs use the
      * register-staged kernel, which permutes the activation bytes for layout 0.
      * BL_GEMM_TILE overrides for experiments:
      * 0 = 128x128x64 staged, 5 = 128x128x128 staged, 6/7/8 = 256x256 with 2x2 /
-     * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages, 12 = 64x256. */
+     * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages, 12 = 64x256,
+     * 13 = 64x128. */
     const char* e = getenv("BL_GEMM_TILE");
     const int m = (int)M, n = (int)N, k = (int)K;
     int tile = e && *e ? atoi(e) : -1;
     const bool direct_ok = layout == 1 && k % G3_BK == 0;
-    if (tile < 0) tile = direct_ok ? (m <= 64 ? 12 : 10) : (k % 128 == 0) ? 5 : 0;
-    if (tile >= 6 && tile <= 12 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
+    if (tile < 0) tile = direct_ok ? ((int64_t)((m + 127) / 128) * ((n + 127) / 128) <= 400 ? 13 : 10) : (k % 128 == 0) ? 5 : 0;
+    if (tile >= 6 && tile <= 13 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
     if (tile == 5 && k % 128) tile = 0;
-    if (tile >= 6 && tile <= 12)
+    if (tile >= 6 && tile <= 13)
         return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
     if (tile == 5)
         return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
