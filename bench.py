@@ -232,6 +232,34 @@ def main():
             t_alt, _ = time_graph_steps(torch, [(g, nl, reps)], nl * reps)
             alt[mode] = {"us_per_step": round(t_alt / (nl * reps) * 1e6, 3), "launches_per_step": launches,
                          "GBps": round(layer_bytes / (t_alt / (nl * reps)) / 1e9, 1)}
+        # independent steps on several streams inside one graph (each branch has its own output
+        # buffers): consecutive launches overlap, which hides the launch gap and the tail of each
+        # kernel.  Not the headline: a real decode chain is dependent (config 4).
+        for nb in (2, 4):
+            bufs_b = [buf] + [make_decode_buffers(bl, torch, synth, M, dev) for _ in range(nb - 1)]
+            descs_b = [descs] + [make_group_descs(bl, layers, b) for b in bufs_b[1:]]
+            branches = [torch.cuda.Stream() for _ in range(nb)]
+
+            def run_overlapped():
+                cur = torch.cuda.current_stream()
+                for b in range(nb):
+                    branches[b].wait_stream(cur)
+                    with torch.cuda.stream(branches[b]):
+                        sb = torch.cuda.current_stream().cuda_stream
+                        for i in range(b, nl, nb):
+                            rc = lib.bl_bitlinear_decode_group(descs_b[b][i], 4, layout, M, sb)
+                            assert rc == 0, rc
+                for b in range(nb):
+                    cur.wait_stream(branches[b])
+            run_overlapped()
+            torch.cuda.synchronize()
+            g = capture(torch, run_overlapped)
+            for _ in range(2):
+                g.replay()
+            t_alt, _ = time_graph_steps(torch, [(g, nl, reps)], nl * reps)
+            alt["overlap_%d_streams" % nb] = {"us_per_step": round(t_alt / (nl * reps) * 1e6, 3), "launches_per_step": 1,
+                                              "GBps": round(layer_bytes / (t_alt / (nl * reps)) / 1e9, 1)}
+            del bufs_b, descs_b
         # steady state of the same kernel: one product with a very large N (all 30 gate_up
         # matrices stacked would be this shape), 265 MB streamed per launch
         big_n = 30 * 13824
