@@ -30,9 +30,9 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
 # HBM bytes per launch, read + written, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # this same command (profiles/bench_decode_m1_prefill_m2048.md; counters scaled by what they read for
 # a plain 256 MiB copy: fetch x2.0, write x1.0).  Decode: the one grouped launch of a layer
-# (17.82 MB + 0.09 MB).  Prefill: the four launches of a layer at M = 2048 (252.9 MB + 186.7 MB).
+# (17.82 MB + 0.09 MB).  Prefill: the four launches of a layer at M = 2048 (253.7 MB + 186.7 MB).
 DECODE_TRAFFIC_BYTES = 17.91e6
-PREFILL_TRAFFIC_BYTES = 439.6e6
+PREFILL_TRAFFIC_BYTES = 440.4e6
 SHAPE_ORDER = ["qkv", "o", "gate_up", "down"]
 
 
