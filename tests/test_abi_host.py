@@ -76,6 +76,39 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.bl_pack_ternary(p, 0, 64, 64, 0, p, p, NULL, NULL) == 7
 
 
+def test_producer_and_group_descriptors_are_checked_on_the_host(lib):
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) & ~255   # never dereferenced on these error paths
+
+    class T:   # stands in for a tensor: only data_ptr() is used by the marshalling code
+        def __init__(self, a):
+            self.a = a
+
+        def data_ptr(self):
+            return self.a
+    t = T(p)
+
+    def quant_ex(prod, M=1, K=2560):
+        return lib.bl_quant_act_ex(ctypes.byref(prod), M, K, p, p, None, None)
+    assert quant_ex(bl.make_producer(9, t)) == 5                                  # unknown kind
+    assert quant_ex(bl.make_producer(bl.BL_PROD_RESIDUAL, t)) == 5                # no second operand
+    assert quant_ex(bl.make_producer(bl.BL_PROD_ATTN_V, t, n_q=20, n_kv=5, head_dim=64)) == 5   # geometry != K
+    assert quant_ex(bl.make_producer(bl.BL_PROD_F32, t, norm=True, eps=-1.0)) == 5             # negative eps
+    assert quant_ex(bl.make_producer(bl.BL_PROD_F32, t, norm=True, gain=T(p + 4))) == 5        # misaligned gains
+    assert quant_ex(bl.make_producer(bl.BL_PROD_F32, T(0))) == 1                  # no input
+    assert quant_ex(bl.make_producer(bl.BL_PROD_F32, t), K=100) == 2
+    # grouped decode: count, M limits per input kind, layout
+    beta = t
+    d_q = bl.make_decode_descs([dict(packed=t, beta=beta, N=64, K=64, y=t, q=t, scale=t)])
+    d_x = bl.make_decode_descs([dict(packed=t, beta=beta, N=64, K=64, y=t, X=t)])
+    assert lib.bl_bitlinear_decode_group(d_q, 0, 1, 1, None) == 2
+    assert lib.bl_bitlinear_decode_group(d_q, 5, 1, 1, None) == 2
+    assert lib.bl_bitlinear_decode_group(d_q, 1, 1, 65, None) == 2                # int8 inputs: M <= 64
+    assert lib.bl_bitlinear_decode_group(d_x, 1, 1, 17, None) == 2                # fused inputs: M <= 16
+    assert lib.bl_bitlinear_decode_group(d_q, 1, 7, 1, None) == 3
+    assert lib.bl_bitlinear_decode_group(None, 1, 1, 1, None) == 1
+
+
 def test_binding_raises_with_status():
     with pytest.raises(bl.BitLinearError) as e:
         bl._check(2, "bl_gemv_w158a8")
