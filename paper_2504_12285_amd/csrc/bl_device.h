@@ -83,6 +83,27 @@ typedef __attribute__((address_space(3))) void* bl_lptr;
  * vmcnt bits 3:0 in imm[3:0], bits 5:4 in imm[15:14]) */
 #define BL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
+/* Waits until at most r stages of LOADS direct loads each are still in flight (r <= J). */
+template <int J, int LOADS>
+__device__ __forceinline__ void bl_wait_stages(int r) {
+    if (r >= J) {
+        BL_WAIT_VM(J * LOADS);
+    } else {
+        if constexpr (J > 0) bl_wait_stages<J - 1, LOADS>(r);
+    }
+}
+
+/* Expand one packed word (16 weights, layout-1 digit order) into the sixteen
+ * int8 codes of 16 consecutive k: three shifts and four masks. */
+__device__ __forceinline__ bl_v4i bl_unpack16(uint32_t p) {
+    bl_v4i b;
+    b[0] = (int)(p & 0x03030303u);
+    b[1] = (int)((p >> 2) & 0x03030303u);
+    b[2] = (int)((p >> 4) & 0x03030303u);
+    b[3] = (int)((p >> 6) & 0x03030303u);
+    return b;
+}
+
 /* Wait for in-flight matrix-core results before ordinary vector instructions
  * read an accumulator.  The hardware has no interlock for that read, and the
  * compiler's wait-state count for the gfx950 16x16x64 int8 MFMA proved too

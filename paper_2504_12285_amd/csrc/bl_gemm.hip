@@ -13,16 +13,6 @@
 
 #define GEMM_THREADS 256
 
-/* Expand one packed word (16 weights, layout-1 digit order) into the sixteen
- * int8 codes of 16 consecutive k: three shifts and four masks. */
-__device__ __forceinline__ bl_v4i bl_unpack16(uint32_t p) {
-    bl_v4i b;
-    b[0] = (int)(p & 0x03030303u);
-    b[1] = (int)((p >> 2) & 0x03030303u);
-    b[2] = (int)((p >> 4) & 0x03030303u);
-    b[3] = (int)((p >> 6) & 0x03030303u);
-    return b;
-}
 #define GEMM_PAD 16   /* bytes of padding per activation row in LDS (bank spread) */
 
 /* Block tile BM x BN, k step BK (64 or 128), four waves arranged WGM x WGN.
@@ -231,16 +221,6 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * Requires layout 1, K % 128 == 0. */
 #define G3_BK 128
 
-
-/* Waits until at most r stages of LOADS direct loads each are still in flight (r <= J). */
-template <int J, int LOADS>
-__device__ __forceinline__ void bl_wait_stages(int r) {
-    if (r >= J) {
-        BL_WAIT_VM(J * LOADS);
-    } else {
-        if constexpr (J > 0) bl_wait_stages<J - 1, LOADS>(r);
-    }
-}
 
 template <int BM, int BN, int STAGES, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,

@@ -1,0 +1,319 @@
+/* Batched-decode W1.58A8 product for 17..64 tokens with int8 inputs (Section 5.1 of
+ * the BitNet b1.58 2B4T report: packed weights streamed from HBM once, unpacked on chip
+ * right before the int8 product).
+ *
+ * With this many tokens a workgroup can no longer keep every token row in LDS.  The kernel is
+ * a skinny GEMM: eight waves walk the k axis in steps of 256; both operands travel global ->
+ * LDS by direct loads (no registers) through a ring of S stages, S-1 of them in flight.
+ *
+ * What bounds it is LDS time, and that shaped the work split.  Measured on this kernel's loop
+ * skeleton: a CU takes direct-load data into LDS at ~48 B/clk and serves ds_read_b128 at ~138
+ * B/clk, and the two do NOT overlap (24 KB of direct loads + 80 KB of reads per step cost
+ * 506 + 570 clk).  So every staged byte should be read from LDS once: a wave owns one token
+ * block (32 tokens) and one k part of each step and multiplies it against ALL row blocks of
+ * the workgroup (NI = 1, 2 or 4 blocks of 32 rows, v_mfma_i32_32x32x32_i8, NI accumulators);
+ * the eight waves are TB token blocks (1: M <= 32, 2: M <= 64) x KH = 8/TB k parts, and the k
+ * parts meet through LDS once at the end, where all eight waves share the sums and the stores.
+ *
+ * LDS stage: TB*32 token rows of 256 bytes, then 32*NI weight rows of 64 packed bytes.
+ * 16-byte units are XOR-swizzled against the row index (applied to the global address a lane
+ * fetches, since a direct load writes 64 consecutive units), which spreads the reads of both
+ * operands over the banks.  Inside a k step lane half h and MFMA s use packed word 8h+s
+ * (k = 16*(8h+s) .. +15); k part kh takes s = kh*TB .. kh*TB+TB-1.
+ *
+ * Offset codes: the matrix cores multiply codes 0..2; sum_k q (given, or accumulated by one
+ * more chain against an all-ones operand) is subtracted once per output. */
+#include <stdlib.h>
+
+#include <type_traits>
+
+#include "bl_device.h"
+#include "bl_gemv_common.h"
+#include "bl_host.h"
+
+#ifdef BL_TRACE   /* development aid: per-workgroup time stamps (100 MHz clock) */
+__device__ unsigned long long* bl_ptrace_ptr;
+extern "C" int bl_trace_set_panel(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(bl_ptrace_ptr), &p, sizeof(p)); }
+#define BL_PSTAMP_DECL unsigned long long bl_ts[6] = {0, 0, 0, 0, 0, 0}
+#define BL_PSTAMP(i) bl_ts[i] = wall_clock64()
+#define BL_PSTAMP_FLUSH do { if (threadIdx.x == 0 && bl_ptrace_ptr) for (int i_ = 0; i_ < 6; ++i_) bl_ptrace_ptr[blockIdx.x * 8 + i_] = bl_ts[i_]; } while (0)
+#else
+#define BL_PSTAMP_DECL
+#define BL_PSTAMP(i)
+#define BL_PSTAMP_FLUSH
+#endif
+
+#define BL_PANEL_HEAD 128   /* ints in front of the ring: 64 token scales, 64 row sums */
+
+typedef int bl_v2i __attribute__((ext_vector_type(2)));
+
+template <int TB, int S, bool NEED_SUM, int NI>
+__device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M, int* lds) {
+    constexpr int SA = TB * 8192, SW = 8192, STG = SA + SW;
+    constexpr int LOADS = TB + 1;                          /* direct loads per wave and stage */
+    constexpr int KH = 8 / TB, NSUB = TB;                  /* k parts; MFMA sub-steps per wave and step */
+    static_assert((S - 2) * LOADS < 64, "vmcnt is a 6-bit count");
+    static_assert(S * STG >= 8 * 4 * 4096, "the ring must hold the partial sums of the epilogue");
+    BL_PSTAMP_DECL;
+    BL_PSTAMP(0);
+    const int N = P.N, K = P.K;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    const int tb = w % TB, kh = w / TB;
+    const int n_base = ((int)blockIdx.x - P.block0) * (NI * 32);
+    const int wunits = K / 64;                             /* 16-byte units per packed row */
+    const int nsteps = (K + 255) / 256;
+    float* fscale = (float*)lds;
+    int* frs = lds + 64;
+    uint8_t* ring = (uint8_t*)(lds + BL_PANEL_HEAD);
+
+    /* The token scales and row sums go to LDS by direct loads too (wave 0, one dword per lane,
+     * ahead of every stage load: loads return in order, so they have landed when the first
+     * stage has).  No register waits for them. */
+    const float bt = *P.beta;
+    if (w == 0) {
+        const int t = lane < M ? lane : M - 1;
+        if (P.scale) __builtin_amdgcn_global_load_lds((bl_gptr)(P.scale + t), (bl_lptr)fscale, 4, 0, 0);
+        if (!NEED_SUM) __builtin_amdgcn_global_load_lds((bl_gptr)(P.rowsum + t), (bl_lptr)frs, 4, 0, 0);
+    }
+
+    /* Per-lane sources of the direct loads, computed once: a k step only adds its offset.
+     * Exactly LOADS instructions per wave and stage whatever the shape, so that the vmcnt
+     * immediates below are right: tokens beyond M re-read row M-1, rows beyond N re-read row
+     * N-1 (never stored), and in a last, partial k step the units beyond K re-read the step's
+     * first unit (their weights are zeroed at the point of use). */
+    const int nl = NI * 16;                                /* lanes of the weight load in use */
+    const int8_t* asrc[TB];
+    int au[TB];
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        const int row = (w * TB + j) * 4 + (lane >> 4);    /* piece w*TB+j: 4 token rows = 1 KB */
+        const int tok = row < M ? row : M - 1;
+        au[j] = (lane & 15) ^ (row & 15);
+        asrc[j] = P.q + (int64_t)tok * K + au[j] * 16;
+    }
+    const bl_v4i* wsrc;
+    int wunit;
+    {
+        const int U = w * nl + lane;                       /* unit of the stage's weight region */
+        const int row = U >> 2;
+        wunit = (U & 3) ^ ((row >> 2) & 3);
+        int n = n_base + row;
+        if (n >= N) n = N - 1;
+        wsrc = P.packed + (int64_t)n * wunits + wunit;
+    }
+    auto issue = [&](int ks, int buf) {
+        uint8_t* base = ring + buf * STG;
+        const bool tail = ks * 256 + 256 > K;              /* wave-uniform: only the last step can be */
+#pragma unroll
+        for (int j = 0; j < TB; ++j) {
+            const int8_t* src = asrc[j] + ks * 256;
+            if (tail && ks * 256 + au[j] * 16 >= K) src -= au[j] * 16;
+            __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + (w * TB + j) * 1024), 16, 0, 0);
+        }
+        if (lane < nl) {
+            const bl_v4i* src = wsrc + ks * 4;
+            if (tail && ks * 4 + wunit >= wunits) src -= wunit;
+            __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + SA + w * nl * 16), 16, 0, 0);
+        }
+    };
+
+    bl_v16i C[NI], Cs;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) C[ni][v] = 0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Cs[v] = 0;
+
+    /* per-lane LDS read offsets inside a stage: this wave's MFMA sub-steps are s = kh*TB + j,
+     * packed word / activation unit 8h + s */
+    const int u0 = h * 8 + kh * NSUB;                      /* first word (and activation unit) of the wave */
+    const int ar = tb * 32 + l32;                          /* token row in the stage */
+    int a_off[NSUB];
+#pragma unroll
+    for (int j = 0; j < NSUB; ++j) a_off[j] = ar * 256 + (((u0 + j) ^ (ar & 15)) * 16);
+    /* weight row l32 of block ni sits at (ni*32 + l32) * 64; its unit u0/4 is swizzled with
+     * bits 2..3 of the row, which do not depend on ni */
+    const int w_off = SA + l32 * 64 + ((((u0 >> 2) ^ (l32 >> 2)) & 3) * 16) + (u0 & 3) * 4;
+
+    auto compute = [&](int ks, int buf, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;   /* a partial last step: mask the words beyond K */
+        const uint8_t* st = ring + buf * STG;
+        bl_v4i a[NSUB];
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) a[j] = *(const bl_v4i*)(st + a_off[j]);
+        uint32_t wds[NI][NSUB];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            {
+                if constexpr (NSUB == 2) {
+                    const bl_v2i q2 = *(const bl_v2i*)(st + w_off + ni * 2048);
+                    wds[ni][0] = (uint32_t)q2[0];
+                    wds[ni][1] = (uint32_t)q2[1];
+                } else {
+                    wds[ni][0] = (uint32_t)*(const int*)(st + w_off + ni * 2048);
+                }
+            }
+        }
+        const int k0 = ks * 256;
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) {
+            const bool cv = !TAIL || k0 + (u0 + j) * 16 < K;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                {
+                    const uint32_t wd = cv ? wds[ni][j] : 0u;
+                    uint32_t l0 = wd & 0x03030303u, l1 = (wd >> 2) & 0x03030303u, l2 = (wd >> 4) & 0x03030303u,
+                             l3 = (wd >> 6) & 0x03030303u;
+                    if (P.layout == 0) bl_transpose4x4(l0, l1, l2, l3);
+                    const bl_v4i b = {(int)l0, (int)l1, (int)l2, (int)l3};
+                    C[ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[j], b, C[ni], 0, 0, 0);
+                }
+            }
+            if (NEED_SUM) {
+                const int one = cv ? 0x01010101 : 0;
+                const bl_v4i ones = {one, one, one, one};
+                Cs = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[j], ones, Cs, 0, 0, 0);
+            }
+        }
+    };
+
+    for (int s0 = 0; s0 < S - 1 && s0 < nsteps; ++s0) issue(s0, s0);
+    BL_PSTAMP(1);
+    for (int it = 0; it < nsteps; ++it) {
+        /* stage `it` has landed; the stages issued after it may stay in flight */
+        const int later = nsteps - 1 - it;
+        bl_wait_stages<S - 2, LOADS>(later < S - 2 ? later : S - 2);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (it == 0) BL_PSTAMP(2);
+        if (it == 1) BL_PSTAMP(3);
+        const int nx = it + S - 1;
+        if (nx < nsteps) issue(nx, nx % S);
+        if (it * 256 + 256 > K) compute(it, it % S, std::true_type());
+        else compute(it, it % S, std::false_type());
+    }
+
+    bl_mfma_fence();
+    BL_PSTAMP(4);
+    asm volatile("" ::: "memory");
+    __syncthreads();                                       /* every wave is done with the ring */
+    /* The k parts meet in LDS: wave w leaves its partial sums (minus its part of sum_k q) for
+     * each row block, then wave wv = nib*TB + tbb adds the KH parts of block (tbb, nib),
+     * rescales and stores: all eight waves share the epilogue when NI*TB = 8. */
+    bl_v4i* red = (bl_v4i*)ring;                           /* [wave][ni][4][64] groups of four sums */
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        {
+            bl_v16i Dp = C[ni];
+            if (NEED_SUM) Dp -= Cs;
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq)
+                red[((w * NI + ni) * 4 + vq) * 64 + lane] = bl_v4i{Dp[4 * vq], Dp[4 * vq + 1], Dp[4 * vq + 2], Dp[4 * vq + 3]};
+        }
+    }
+    __syncthreads();
+    const int tbb = w % TB, nib = w / TB;
+    const int n = n_base + nib * 32 + l32;
+    if (nib < NI && n < N) {
+        bl_v16i D;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) D[v] = 0;
+#pragma unroll
+        for (int kp = 0; kp < KH; ++kp)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const bl_v4i t4 = red[(((kp * TB + tbb) * NI + nib) * 4 + vq) * 64 + lane];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) D[4 * vq + e] += t4[e];
+            }
+        /* residual values first, then the stores back to back: a load between two stores would
+         * make each store wait for the one before it (stores count on vmcnt too) */
+        auto emit = [&](auto add_tag) {
+            constexpr bool ADD = decltype(add_tag)::value;
+            float res[16];
+            if (ADD) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int tok = tbb * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+                    res[v] = P.residual[(int64_t)(tok < M ? tok : M - 1) * N + n];
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tok = tbb * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+                if (tok < M) {
+                    const int val = D[v] - (NEED_SUM ? 0 : frs[tok]);
+                    if (P.acc) P.acc[(int64_t)tok * N + n] = val;
+                    if (P.y) {
+                        const float r = (float)val * (bt * fscale[tok]);
+                        P.y[(int64_t)tok * N + n] = ADD ? res[v] + r : r;
+                    }
+                }
+            }
+        };
+        if (P.y && P.residual) emit(std::true_type());
+        else emit(std::false_type());
+    }
+    BL_PSTAMP(5);
+    BL_PSTAMP_FLUSH;
+}
+
+/* NI is a property of the workgroup's product: one specialised body per value, so that the
+ * accumulators are a fixed set of registers. */
+template <int TB, int S, bool NEED_SUM>
+__global__ __launch_bounds__(512) void bl_gemv_panel(const bl_gemv_group grp, const int M) {
+    extern __shared__ __attribute__((aligned(16))) int lds[];
+    const bl_gemv_prob P = bl_fetch_prob(grp);
+    if (P.ksplit == 4) bl_panel_body<TB, S, NEED_SUM, 4>(P, M, lds);
+    else if (P.ksplit == 2) bl_panel_body<TB, S, NEED_SUM, 2>(P, M, lds);
+    else bl_panel_body<TB, S, NEED_SUM, 1>(P, M, lds);
+}
+
+template <int TB, int S>
+static bl_status launch_panel(const bl_gemv_group& grp, int M, int blocks, bool have_sums, hipStream_t st) {
+    constexpr int lds = BL_PANEL_HEAD * 4 + S * (TB * 8192 + 8192);
+    static_assert(lds <= 160 * 1024, "LDS of one CU");
+    auto kern = have_sums ? bl_gemv_panel<TB, S, false> : bl_gemv_panel<TB, S, true>;
+    static bool done[2] = {false, false};
+    if (!done[have_sums]) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return BL_ERR_HIP;
+        done[have_sums] = true;
+    }
+    kern<<<blocks, 512, lds, st>>>(grp, M);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+/* 17 <= M <= 64, int8 inputs only.  Rows per workgroup: 32 * NI.  A long k gets NI = 1: its
+ * workgroups stream the most activation bytes and would otherwise finish last (measured on
+ * the four shapes of a layer at M = 64: 18.9 us against 22.4 with NI = 2); every NI is halved
+ * while the launch would leave most CUs without a workgroup.  BL_PANEL_NI forces one value. */
+bl_status bl_gemv_panel_launch(bl_gemv_group& grp, int M, hipStream_t st) {
+    if (M < 1 || M > 64) return BL_ERR_SHAPE;
+    const int TB = M <= 32 ? 1 : 2;
+    const char* e = getenv("BL_PANEL_NI");
+    const int force = e && *e ? atoi(e) : 0;
+    bool have_sums = true;
+    int blocks = 0;
+    for (int div = 1; div <= 4; div *= 2) {
+        blocks = 0;
+        bool floor_all = true;
+        for (int i = 0; i < grp.count; ++i) {
+            bl_gemv_prob& P = grp.p[i];
+            if (P.fused || !P.q) return BL_ERR_SHAPE;
+            if (!P.rowsum) have_sums = false;
+            int ni = (P.K > 4096 ? 1 : 4) / div;
+            if (ni <= 1) ni = 1;
+            else floor_all = false;
+            if (force == 1 || force == 2 || force == 4) ni = force;
+            P.ksplit = ni;
+            P.block0 = blocks;
+            blocks += (P.N + 32 * ni - 1) / (32 * ni);
+        }
+        if (blocks >= 128 || floor_all || force) break;
+    }
+    return TB == 1 ? launch_panel<1, 8>(grp, M, blocks, have_sums, st) : launch_panel<2, 6>(grp, M, blocks, have_sums, st);
+}

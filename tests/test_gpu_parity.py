@@ -136,12 +136,26 @@ def test_gemv_batched(bl, layout, M):
     assert_y_close(y, c.y)
 
 
-@pytest.mark.parametrize("M,N,K", [(9, 2564, 1024), (16, 52, 320), (33, 2560, 6912), (48, 200, 8192), (64, 20, 64)])
+@pytest.mark.parametrize("M,N,K", [(9, 2564, 1024), (16, 52, 320), (33, 2560, 6912), (48, 200, 8192), (64, 20, 64),
+                                   (40, 132, 320), (24, 100, 1088), (20, 36, 192), (57, 264, 2624)])
 def test_gemv_batched_phases_and_tails(bl, M, N, K):
     """Staging phases with a short last phase, ragged row groups, K at the limit."""
     c = Case(35, M, N, K)
     for layout in (0, 1):
         acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(layout == 1))
+        assert np.array_equal(acc, c.acc)
+        assert_y_close(y, c.y)
+
+
+@pytest.mark.parametrize("path", ["mma", "panel"])
+@pytest.mark.parametrize("M,N,K", [(17, 2560, 2560), (32, 264, 2624), (40, 100, 1088), (64, 2560, 6912), (64, 36, 192)])
+def test_both_batched_decode_kernels_at_every_m(bl, monkeypatch, path, M, N, K):
+    """The library picks one of two kernels for 17..64 tokens by measured speed; BL_GEMV_PATH
+    forces either, and both must give the oracle's numbers on every shape."""
+    monkeypatch.setenv("BL_GEMV_PATH", path)
+    c = Case(37, M, N, K)
+    for layout in (0, 1):
+        acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(layout == 0))
         assert np.array_equal(acc, c.acc)
         assert_y_close(y, c.y)
 
@@ -290,7 +304,7 @@ def test_fused_decode_zero_and_tiny_rows(bl):
 
 
 @pytest.mark.parametrize("M,fused", [(1, False), (1, True), (4, False), (4, True), (8, False), (8, True),
-                                     (8, "mixed"), (40, False), (64, False)])
+                                     (8, "mixed"), (24, False), (40, False), (64, False)])
 def test_grouped_decode_whole_layer(bl, M, fused):
     """The four shapes of one layer in ONE launch equal four oracle products."""
     cases, items, keep = [], [], []
@@ -315,6 +329,22 @@ def test_grouped_decode_whole_layer(bl, M, fused):
     for c, it in zip(cases, items):
         assert np.array_equal(it["acc"].cpu().numpy(), c.acc)
         assert_y_close(it["y"].cpu().numpy(), c.y)
+
+
+@pytest.mark.parametrize("M", [3, 12, 40, 64])
+def test_grouped_decode_residual_epilogue(bl, M):
+    """y = residual + float(acc) * (beta * scale): the fp32 add of the epilogue, every decode kernel."""
+    rng = np.random.default_rng(7)
+    c = Case(54, M, 264, 1088)
+    res = rng.standard_normal((M, c.N)).astype(np.float32)
+    it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=c.N, K=c.K,
+              q=to_dev(c.q), scale=to_dev(c.scale), rowsum=to_dev(c.rowsum), residual=to_dev(res),
+              y=torch.empty((M, c.N), dtype=torch.float32, device="cuda:0"))
+    bl.bl_bitlinear_decode_group(bl.make_decode_descs([it]), 1, M)
+    _sync()
+    want = res + c.y           # one fp32 add per element, as the kernels do
+    got = it["y"].cpu().numpy()
+    assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.abs(c.y) + 1.2e-7 * np.abs(want))
 
 
 def test_fused_fixed_scale(bl):
