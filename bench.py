@@ -30,9 +30,9 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
 # HBM bytes per launch, read + written, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # this same command (profiles/bench_decode_m1_prefill_m2048.md; counters scaled by what they read for
 # a plain 256 MiB copy: fetch x2.0, write x1.0).  Decode: the one grouped launch of a layer
-# (17.82 MB + 0.09 MB).  Prefill: the four launches of a layer at M = 2048 (253.7 MB + 186.7 MB).
+# (17.82 MB + 0.09 MB).  Prefill: the four launches of a layer at M = 2048 (135.2 MB + 186.7 MB).
 DECODE_TRAFFIC_BYTES = 17.91e6
-PREFILL_TRAFFIC_BYTES = 440.4e6
+PREFILL_TRAFFIC_BYTES = 321.8e6
 SHAPE_ORDER = ["qkv", "o", "gate_up", "down"]
 
 
@@ -362,7 +362,7 @@ def main():
                           "roofline": {"bound": "mfma", "achieved": round(tops, 2), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
                                        "traffic": PREFILL_TRAFFIC_BYTES if Mp == 2048 else None,
-                                       "kernel": "bl_gemm_mfma"}}
+                                       "kernel": "bl_gemm_tile256"}}
 
     # ------------------------------------------- config 2: batched decode, M in {8, 32, 64}
     if not args.no_batched:
