@@ -160,6 +160,22 @@ def test_both_batched_decode_kernels_at_every_m(bl, monkeypatch, path, M, N, K):
         assert_y_close(y, c.y)
 
 
+@pytest.mark.parametrize("M", [2, 12, 28, 48])
+def test_decode_single_outputs(bl, M):
+    """acc alone (no scales at all) and y alone, on each decode kernel."""
+    c = Case(38, M, 136, 832)
+    packed = to_dev(c.packed(1))
+    beta = to_dev(np.array([c.beta], dtype=np.float32))
+    q, scale, rowsum = to_dev(c.q), to_dev(c.scale), to_dev(c.rowsum)
+    acc, y = bl.bl_gemv_w158a8(packed, beta, 1, q, None, rowsum, c.N, want_acc=True, want_y=False)
+    _sync()
+    assert y is None and np.array_equal(acc.cpu().numpy(), c.acc)
+    acc, y = bl.bl_gemv_w158a8(packed, beta, 1, q, scale, None, c.N, want_acc=False, want_y=True)
+    _sync()
+    assert acc is None
+    assert_y_close(y.cpu().numpy(), c.y)
+
+
 @pytest.mark.parametrize("M", [1, 3, 40])
 def test_long_rows_beyond_the_decode_kernels(bl, M):
     """K above 8192: the decode entry point hands over to the prefill kernel; the int32 sums
