@@ -358,13 +358,16 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     uint4 xv[4];
     const bool pre_bf16 = fused && P.prod.kind == BL_PROD_BF16 && !(NORM && P.prod.norm);
     const bool first_block = blockIdx.x == (unsigned)P.block0;
-    if (pre_bf16) {
+    /* without normalisation every wave quantises tokens w, w+4, .. on its own: lane l holds
+     * groups l and l+64 of the wave's first token */
+    if (pre_bf16 && w < M) {
+        const uint4* xr = (const uint4*)((const uint16_t*)P.prod.in0 + (int64_t)w * K);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int u = tid + j * 256;
+            const int u = lane + j * 64;
             if (u < groups) {
-                xv[2 * j] = ((const uint4*)P.prod.in0)[2 * u];
-                xv[2 * j + 1] = ((const uint4*)P.prod.in0)[2 * u + 1];
+                xv[2 * j] = xr[2 * u];
+                xv[2 * j + 1] = xr[2 * u + 1];
             }
         }
     }
@@ -405,12 +408,65 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     }
 
     BL_STAMP(1);
-    /* 3. fused path: produce, quantise and stage every token */
-    if (fused) {
+    /* 3. fused path: produce, quantise and stage every token.  Without normalisation a token
+     * is one wave's work (absmax by a wave reduction, no workgroup barrier per token): the four
+     * waves run four tokens side by side.  A lane keeps its first two groups in registers
+     * between the absmax pass and the quantising pass and produces the others twice. */
+    if (fused && !(NORM && P.prod.norm)) {
+#pragma unroll 1
+        for (int m = w; m < M; m += 4) {
+            const bool have_xv = pre_bf16 && m == w;
+            float mx = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int u = lane + j * 64;
+                if (u < groups) {
+                    if (!have_xv) bl_produce16<NORM>(P.prod, m, u, K, first_block, 1.0f, xv[2 * j], xv[2 * j + 1]);
+                    mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
+                }
+            }
+            for (int u = lane + 128; u < groups; u += 64) {
+                uint4 lo, hi;
+                bl_produce16<NORM>(P.prod, m, u, K, false, 1.0f, lo, hi);
+                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+            }
+            const float gamma = bl_wave_max(mx);
+            const float gg = fmaxf(gamma, 1e-5f);
+            const float inv = bl_div_rn(127.0f, gg);
+            const bool emit = P.q_out && first_block;
+            uint8_t* Qm = Q + m * qstride;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int u = lane + j * 64;
+                if (u < groups) {
+                    uint32_t a0, a1, a2, a3;
+                    bl_quant8_words(xv[2 * j], inv, a0, a1);
+                    bl_quant8_words(xv[2 * j + 1], inv, a2, a3);
+                    if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
+                    *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
+                }
+            }
+            for (int u = lane + 128; u < groups; u += 64) {
+                uint32_t a0, a1, a2, a3;
+                uint4 lo, hi;
+                bl_produce16<NORM>(P.prod, m, u, K, first_block, 1.0f, lo, hi);
+                bl_quant8_words(lo, inv, a0, a1);
+                bl_quant8_words(hi, inv, a2, a3);
+                if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
+                *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
+            }
+            if (lane == 0) {
+                const float sc = bl_div_rn(gg, 127.0f);
+                fscale[m] = P.fixed_scale > 0.0f ? P.fixed_scale : sc;
+                if (P.scale_out && first_block) P.scale_out[m] = sc;
+            }
+        }
+        __syncthreads();
+    } else if (fused) {
 #pragma unroll 1
         for (int m = 0; m < M; ++m) {
             float rn = 1.0f;
-            bool have_xv = pre_bf16 && m == 0;
+            bool have_xv = false;
             if (NORM && P.prod.norm) {
                 rn = bl_norm_produce2(P.prod, m, K, first_block, (double*)frs, xv);
                 have_xv = true;
