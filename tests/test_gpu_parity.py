@@ -363,6 +363,32 @@ def test_grouped_decode_residual_epilogue(bl, M):
     assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.abs(c.y) + 1.2e-7 * np.abs(want))
 
 
+@pytest.mark.parametrize("M", [6, 24, 56])
+def test_grouped_decode_two_products_one_with_residual(bl, M):
+    """Two products of different shape in one launch, the second with a residual and without
+    row sums: the group then takes the variant that accumulates sum_k q itself."""
+    rng = np.random.default_rng(11)
+    ca, cb = Case(55, M, 200, 1088), Case(56, M, 132, 4160)
+    res = rng.standard_normal((M, cb.N)).astype(np.float32)
+    items = []
+    for c, extra in ((ca, {}), (cb, dict(residual=to_dev(res)))):
+        it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=c.N, K=c.K,
+                  q=to_dev(c.q), scale=to_dev(c.scale), acc=torch.empty((M, c.N), dtype=torch.int32, device="cuda:0"),
+                  y=torch.empty((M, c.N), dtype=torch.float32, device="cuda:0"))
+        if c is ca:
+            it["rowsum"] = to_dev(c.rowsum)
+        it.update(extra)
+        items.append(it)
+    bl.bl_bitlinear_decode_group(bl.make_decode_descs(items), 1, M)
+    _sync()
+    assert np.array_equal(items[0]["acc"].cpu().numpy(), ca.acc)
+    assert np.array_equal(items[1]["acc"].cpu().numpy(), cb.acc)
+    assert_y_close(items[0]["y"].cpu().numpy(), ca.y)
+    want = res + cb.y
+    got = items[1]["y"].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= 1e-6 * np.abs(cb.y) + 1.2e-7 * np.abs(want))
+
+
 def test_fused_fixed_scale(bl):
     c = Case(53, 2, 128, 256)
     it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=c.N, K=c.K,
