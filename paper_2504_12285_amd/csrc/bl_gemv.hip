@@ -774,7 +774,7 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
         /* more tokens than one MFMA tile: the streaming panel kernel, except for a product
          * alone with at most 32 tokens (measured per shape at M = 17 .. 64: the row-resident
          * kernel wins there, 6.1 .. 15.6 us against 7.8 .. 14.4, and loses above, 12.3 .. 23.5
-         * against 9.3 .. 17.2; a whole layer in one launch takes 15.6 / 18.9 us at M = 32 / 64
+         * against 9.3 .. 17.2; a whole layer in one launch takes 14.4 / 17.0 us at M = 32 / 64
          * against 26.1 / 41.5).  BL_GEMV_PATH=mma / panel force one of them. */
         const bool want_panel = path_env ? path_env[0] == 'p' : (grp.count > 1 || M > 32);
         if (want_panel) return bl_gemv_panel_launch(grp, M, st);

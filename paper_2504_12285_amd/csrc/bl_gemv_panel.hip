@@ -104,17 +104,28 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
     }
     auto issue = [&](int ks, int buf) {
         uint8_t* base = ring + buf * STG;
-        const bool tail = ks * 256 + 256 > K;              /* wave-uniform: only the last step can be */
+        /* wave-uniform: only the last step can be partial, and only then are sources clamped (the
+         * full steps pay one 64-bit add per load and nothing else) */
+        if (ks * 256 + 256 > K) {
 #pragma unroll
-        for (int j = 0; j < TB; ++j) {
-            const int8_t* src = asrc[j] + ks * 256;
-            if (tail && ks * 256 + au[j] * 16 >= K) src -= au[j] * 16;
-            __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + (w * TB + j) * 1024), 16, 0, 0);
-        }
-        if (lane < nl) {
-            const bl_v4i* src = wsrc + ks * 4;
-            if (tail && ks * 4 + wunit >= wunits) src -= wunit;
-            __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + SA + w * nl * 16), 16, 0, 0);
+            for (int j = 0; j < TB; ++j) {
+                const int8_t* src = asrc[j] + ks * 256;
+                if (ks * 256 + au[j] * 16 >= K) src -= au[j] * 16;
+                __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + (w * TB + j) * 1024), 16, 0, 0);
+            }
+            if (lane < nl) {
+                const bl_v4i* src = wsrc + ks * 4;
+                if (ks * 4 + wunit >= wunits) src -= wunit;
+                __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + SA + w * nl * 16), 16, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+                __builtin_amdgcn_global_load_lds((bl_gptr)(asrc[j] + ks * 256), (bl_lptr)(base + (w * TB + j) * 1024),
+                                                 16, 0, 0);
+            if (lane < nl)
+                __builtin_amdgcn_global_load_lds((bl_gptr)(wsrc + ks * 4), (bl_lptr)(base + SA + w * nl * 16), 16, 0,
+                                                 0);
         }
     };
 
