@@ -240,28 +240,54 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
 #pragma unroll
                 for (int e = 0; e < 4; ++e) D[4 * vq + e] += t4[e];
             }
-        /* residual values first, then the stores back to back: a load between two stores would
-         * make each store wait for the one before it (stores count on vmcnt too) */
+        /* The token terms come from LDS four at a time; residual values first, then the stores
+         * back to back (a load between two stores would make each store wait for the one before
+         * it: stores count on vmcnt too), through global-address-space pointers, y and acc in
+         * loops of their own so that the wave-uniform tests stay outside. */
+        typedef __attribute__((address_space(1))) float* gfloat_p;
+        typedef __attribute__((address_space(1))) int* gint_p;
+        typedef const __attribute__((address_space(1))) float* gcfloat_p;
         auto emit = [&](auto add_tag) {
             constexpr bool ADD = decltype(add_tag)::value;
-            float res[16];
-            if (ADD) {
+            int val[16];
+            float cf[16];
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int t0 = tbb * 32 + vq * 8 + h * 4;
+                const float4 sc4 = *(const float4*)(fscale + t0);
+                const float scv[4] = {sc4.x, sc4.y, sc4.z, sc4.w};
+                bl_v4i rs4 = {0, 0, 0, 0};
+                if (!NEED_SUM) rs4 = *(const bl_v4i*)(frs + t0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    val[4 * vq + e] = D[4 * vq + e] - rs4[e];
+                    cf[4 * vq + e] = bt * scv[e];
+                }
+            }
+            if (P.y) {
+                gfloat_p yp = (gfloat_p)P.y + n;
+                float res[16];
+                if (ADD) {
+                    gcfloat_p rp = (gcfloat_p)P.residual + n;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int tok = tbb * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+                        res[v] = rp[(int64_t)(tok < M ? tok : M - 1) * N];
+                    }
+                }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int tok = tbb * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-                    res[v] = P.residual[(int64_t)(tok < M ? tok : M - 1) * N + n];
+                    const float r = (float)val[v] * cf[v];
+                    if (tok < M) yp[(int64_t)tok * N] = ADD ? res[v] + r : r;
                 }
             }
+            if (P.acc) {
+                gint_p ap = (gint_p)P.acc + n;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tok = tbb * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-                if (tok < M) {
-                    const int val = D[v] - (NEED_SUM ? 0 : frs[tok]);
-                    if (P.acc) P.acc[(int64_t)tok * N + n] = val;
-                    if (P.y) {
-                        const float r = (float)val * (bt * fscale[tok]);
-                        P.y[(int64_t)tok * N + n] = ADD ? res[v] + r : r;
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int tok = tbb * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+                    if (tok < M) ap[(int64_t)tok * N] = val[v];
                 }
             }
         };
