@@ -727,14 +727,19 @@ static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks
 /* Lays the products of a group out over workgroups and launches them.  All
  * products of a group share M.  k is split over the waves of a workgroup when
  * a product alone would give fewer than about 150 workgroups.
- * Path: the VALU dot4 + DPP kernel for M <= 4 (measured faster there), the
- * matrix-core kernel above that; BL_GEMV_PATH=mma forces the latter.  Returns BL_ERR_SHAPE if a K is too long for the
- * register-resident row scheme (the caller then uses the prefill kernel). */
+ * Path: the VALU dot4 + DPP kernel for M <= 2, the matrix-core kernel above that (measured on
+ * the four shapes of a layer in one launch, fused inputs: 7.4 / 14.0 / 18.6 / 23.0 us at M = 1..4
+ * against 15.0 / 15.4 / 15.8 / 16.1; int8 inputs: 6.6 / 11.2 / 13.2 / 15.2 against 10.2 / 10.4 /
+ * 10.6 / 10.8); normalising producers stay on the dot4 kernel up to M = 4.  BL_GEMV_PATH=rows / mma
+ * forces one of them.  Returns BL_ERR_SHAPE if a K is too long for the register-resident row
+ * scheme (the caller then uses the prefill kernel). */
 bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
     const char* path_env = getenv("BL_GEMV_PATH");
-    const bool dot4 = M <= 4 && !(path_env && path_env[0] == 'm');
     bool any_norm = false;
     for (int i = 0; i < grp.count; ++i) any_norm = any_norm || (grp.p[i].fused && grp.p[i].prod.norm);
+    const bool dot4 = path_env && path_env[0] == 'm'   ? false
+                      : path_env && path_env[0] == 'r' ? M <= 4
+                                                       : (M <= 2 || (M <= 4 && any_norm));
     int G = dot4 ? bl_env_int("BL_GEMV_G", 8) : 4;
     if ((G != 4 && G != 8) || (dot4 && any_norm)) G = 8;
     const int force_split = bl_env_int("BL_GEMV_KSPLIT", 0);

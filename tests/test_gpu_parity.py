@@ -147,6 +147,25 @@ def test_gemv_batched_phases_and_tails(bl, M, N, K):
         assert_y_close(y, c.y)
 
 
+@pytest.mark.parametrize("path", ["rows", "mma"])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+def test_both_small_m_decode_kernels(bl, monkeypatch, path, M):
+    """1..4 tokens: the dot4 kernel and the matrix-core kernel, int8 and fused inputs."""
+    monkeypatch.setenv("BL_GEMV_PATH", path)
+    c = Case(39, M, 264, 1088)
+    for layout in (0, 1):
+        acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(layout == 0))
+        assert np.array_equal(acc, c.acc)
+        assert_y_close(y, c.y)
+    packed = to_dev(c.packed(1))
+    beta = to_dev(np.array([c.beta], dtype=np.float32))
+    acc, y, q, scale = bl.bl_bitlinear_decode(packed, beta, 1, to_dev(c.X), c.N, want_acc=True, want_q=True)
+    _sync()
+    assert np.array_equal(q.cpu().numpy(), c.q) and np.array_equal(scale.cpu().numpy(), c.scale)
+    assert np.array_equal(acc.cpu().numpy(), c.acc)
+    assert_y_close(y.cpu().numpy(), c.y)
+
+
 @pytest.mark.parametrize("path", ["mma", "panel"])
 @pytest.mark.parametrize("M,N,K", [(17, 2560, 2560), (32, 264, 2624), (40, 100, 1088), (64, 2560, 6912), (64, 36, 192)])
 def test_both_batched_decode_kernels_at_every_m(bl, monkeypatch, path, M, N, K):
