@@ -425,10 +425,29 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                     mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
                 }
             }
-            for (int u = lane + 128; u < groups; u += 64) {
-                uint4 lo, hi;
-                bl_produce16<NORM>(P.prod, m, u, K, false, 1.0f, lo, hi);
-                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+            if (pre_bf16) {
+                /* plain bf16 rows: the lane's other groups four at a time, so that their loads
+                 * are in flight together (one round trip instead of four) */
+                const uint4* xr = (const uint4*)((const uint16_t*)P.prod.in0 + (int64_t)m * K);
+                for (int u0 = lane + 128; u0 < groups; u0 += 256) {
+                    uint4 t[8];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (u0 + 64 * j < groups) {
+                            t[2 * j] = xr[2 * (u0 + 64 * j)];
+                            t[2 * j + 1] = xr[2 * (u0 + 64 * j) + 1];
+                        }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (u0 + 64 * j < groups)
+                            mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(t[2 * j]), bl_absmax8_bf16(t[2 * j + 1])));
+                }
+            } else {
+                for (int u = lane + 128; u < groups; u += 64) {
+                    uint4 lo, hi;
+                    bl_produce16<NORM>(P.prod, m, u, K, false, 1.0f, lo, hi);
+                    mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+                }
             }
             const float gamma = bl_wave_max(mx);
             const float gg = fmaxf(gamma, 1e-5f);
@@ -446,14 +465,38 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                     *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
                 }
             }
-            for (int u = lane + 128; u < groups; u += 64) {
-                uint32_t a0, a1, a2, a3;
-                uint4 lo, hi;
-                bl_produce16<NORM>(P.prod, m, u, K, first_block, 1.0f, lo, hi);
-                bl_quant8_words(lo, inv, a0, a1);
-                bl_quant8_words(hi, inv, a2, a3);
-                if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
-                *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
+            if (pre_bf16) {
+                const uint4* xr = (const uint4*)((const uint16_t*)P.prod.in0 + (int64_t)m * K);
+                for (int u0 = lane + 128; u0 < groups; u0 += 256) {
+                    uint4 t[8];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (u0 + 64 * j < groups) {
+                            t[2 * j] = xr[2 * (u0 + 64 * j)];
+                            t[2 * j + 1] = xr[2 * (u0 + 64 * j) + 1];
+                        }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int u = u0 + 64 * j;
+                        if (u < groups) {
+                            uint32_t a0, a1, a2, a3;
+                            bl_quant8_words(t[2 * j], inv, a0, a1);
+                            bl_quant8_words(t[2 * j + 1], inv, a2, a3);
+                            if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
+                            *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
+                        }
+                    }
+                }
+            } else {
+                for (int u = lane + 128; u < groups; u += 64) {
+                    uint32_t a0, a1, a2, a3;
+                    uint4 lo, hi;
+                    bl_produce16<NORM>(P.prod, m, u, K, first_block, 1.0f, lo, hi);
+                    bl_quant8_words(lo, inv, a0, a1);
+                    bl_quant8_words(hi, inv, a2, a3);
+                    if (emit) *(uint4*)(P.q_out + (int64_t)m * K + u * 16) = make_uint4(a0, a1, a2, a3);
+                    *(uint4*)(Qm + u * 16) = make_uint4(a0, a1, a2, a3);
+                }
             }
             if (lane == 0) {
                 const float sc = bl_div_rn(gg, 127.0f);
