@@ -818,14 +818,18 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
         }
     }
     if (!dot4) {
-        if (M <= 16) return launch_mma_l<1>(L, grp, M, blocks, st);
-        /* more tokens than one MFMA tile: the streaming panel kernel, except for a product
-         * alone with at most 32 tokens (measured per shape at M = 17 .. 64: the row-resident
-         * kernel wins there, 6.1 .. 15.6 us against 7.8 .. 14.4, and loses above, 12.3 .. 23.5
-         * against 9.3 .. 17.2; a whole layer in one launch takes 14.4 / 17.0 us at M = 32 / 64
-         * against 26.1 / 41.5).  BL_GEMV_PATH=mma / panel force one of them. */
-        const bool want_panel = path_env ? path_env[0] == 'p' : (grp.count > 1 || M > 32);
+        /* Matrix-core kernels.  The streaming panel kernel takes int8 inputs only; measured on
+         * the four shapes of a layer (us per layer, row-resident kernel / panel kernel):
+         *   one launch:  M = 3: 10.5 / 9.9, 8: 11.7 / 10.0, 16: 17.1 / 10.2, 32: 26.8 / 10.7, 48: 38.2 / 14.0
+         *   four calls:  M = 8: 23.4 / 28.9, 16: 26.7 / 29.3, 24: 37.1 / 29.7, 48: 54.1 / 38.1
+         * so a group goes to the panel kernel whenever it can, a product alone from 20 tokens.
+         * BL_GEMV_PATH=mma / panel force one of them. */
+        bool any_fused = false;
+        for (int i = 0; i < grp.count; ++i) any_fused = any_fused || grp.p[i].fused;
+        const bool want_panel =
+            !any_fused && (path_env ? path_env[0] == 'p' : (grp.count > 1 || M >= 20));
         if (want_panel) return bl_gemv_panel_launch(grp, M, st);
+        if (M <= 16) return launch_mma_l<1>(L, grp, M, blocks, st);
         if (M <= 32) return launch_mma_l<2>(L, grp, M, blocks, st);
         return launch_mma_l<4>(L, grp, M, blocks, st);
     }

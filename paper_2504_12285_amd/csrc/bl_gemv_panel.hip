@@ -1,10 +1,12 @@
-/* Batched-decode W1.58A8 product for 17..64 tokens with int8 inputs (Section 5.1 of
+/* Batched-decode W1.58A8 product for 3..64 tokens with int8 inputs (Section 5.1 of
  * the BitNet b1.58 2B4T report: packed weights streamed from HBM once, unpacked on chip
  * right before the int8 product).
  *
  * With this many tokens a workgroup can no longer keep every token row in LDS.  The kernel is
- * a skinny GEMM: eight waves walk the k axis in steps of 256; both operands travel global ->
- * LDS by direct loads (no registers) through a ring of S stages, S-1 of them in flight.
+ * a skinny GEMM: eight waves walk the k axis in steps of KS = 512 (256 is kept for comparisons:
+ * 13.1 / 15.3 us per layer at M = 32 / 64 against 10.5 / 13.9; half the barriers, waits and
+ * address arithmetic per k); both operands travel global -> LDS by direct loads (no registers)
+ * through a ring of S stages, S-1 of them in flight.
  *
  * What bounds it is LDS time, and that shaped the work split.  Measured on this kernel's loop
  * skeleton: a CU takes direct-load data into LDS at ~48 B/clk and serves ds_read_b128 at ~138
@@ -15,11 +17,11 @@
  * the eight waves are TB token blocks (1: M <= 32, 2: M <= 64) x KH = 8/TB k parts, and the k
  * parts meet through LDS once at the end, where all eight waves share the sums and the stores.
  *
- * LDS stage: TB*32 token rows of 256 bytes, then 32*NI weight rows of 64 packed bytes.
+ * LDS stage: TB*32 token rows of KS bytes, then 32*NI weight rows of KS/4 packed bytes.
  * 16-byte units are XOR-swizzled against the row index (applied to the global address a lane
  * fetches, since a direct load writes 64 consecutive units), which spreads the reads of both
- * operands over the banks.  Inside a k step lane half h and MFMA s use packed word 8h+s
- * (k = 16*(8h+s) .. +15); k part kh takes s = kh*TB .. kh*TB+TB-1.
+ * operands over the banks.  Inside a k step lane half h and MFMA s use packed word (KS/32)*h+s
+ * (16 consecutive k); k part kh takes NSUB = KS/32/KH consecutive s.
  *
  * Offset codes: the matrix cores multiply codes 0..2; sum_k q (given, or accumulated by one
  * more chain against an all-ones operand) is subtracted once per output. */
@@ -47,11 +49,17 @@ extern "C" int bl_trace_set_panel(void* p) { return (int)hipMemcpyToSymbol(HIP_S
 
 typedef int bl_v2i __attribute__((ext_vector_type(2)));
 
-template <int TB, int S, bool NEED_SUM, int NI>
+template <int TB, int S, bool NEED_SUM, int NI, int KS>
 __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M, int* lds) {
-    constexpr int SA = TB * 8192, SW = 8192, STG = SA + SW;
-    constexpr int LOADS = TB + 1;                          /* direct loads per wave and stage */
-    constexpr int KH = 8 / TB, NSUB = TB;                  /* k parts; MFMA sub-steps per wave and step */
+    static_assert(KS == 256 || KS == 512, "k step");
+    constexpr int UA = KS / 16;                            /* 16-byte units of a token row per step */
+    constexpr int UW = KS / 64;                            /* 16-byte units of a packed row per step */
+    constexpr int RPP = 1024 / KS;                         /* token rows per 1 KB piece */
+    constexpr int SA = TB * 32 * KS, SW = 128 * (KS / 4), STG = SA + SW;
+    constexpr int NA = TB * (KS / 256);                    /* activation loads per wave and stage */
+    constexpr int NWL = (NI * UW * 4 + 63) / 64;           /* weight loads per wave and stage */
+    constexpr int LOADS = NA + NWL;                        /* direct loads per wave and stage */
+    constexpr int KH = 8 / TB, NSUB = (KS / 32) / KH;      /* k parts; MFMA sub-steps per wave and step */
     static_assert((S - 2) * LOADS < 64, "vmcnt is a 6-bit count");
     static_assert(S * STG >= 8 * 4 * 4096, "the ring must hold the partial sums of the epilogue");
     BL_PSTAMP_DECL;
@@ -62,7 +70,7 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
     const int tb = w % TB, kh = w / TB;
     const int n_base = ((int)blockIdx.x - P.block0) * (NI * 32);
     const int wunits = K / 64;                             /* 16-byte units per packed row */
-    const int nsteps = (K + 255) / 256;
+    const int nsteps = (K + KS - 1) / KS;
     float* fscale = (float*)lds;
     int* frs = lds + 64;
     uint8_t* ring = (uint8_t*)(lds + BL_PANEL_HEAD);
@@ -82,50 +90,59 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
      * immediates below are right: tokens beyond M re-read row M-1, rows beyond N re-read row
      * N-1 (never stored), and in a last, partial k step the units beyond K re-read the step's
      * first unit (their weights are zeroed at the point of use). */
-    const int nl = NI * 16;                                /* lanes of the weight load in use */
-    const int8_t* asrc[TB];
-    int au[TB];
+    constexpr int WPW = NI * UW * 4;                       /* weight units per wave and stage */
+    const int nl = WPW < 64 ? WPW : 64;                    /* lanes of a weight load in use */
+    const int8_t* asrc[NA];
+    int au[NA];
 #pragma unroll
-    for (int j = 0; j < TB; ++j) {
-        const int row = (w * TB + j) * 4 + (lane >> 4);    /* piece w*TB+j: 4 token rows = 1 KB */
+    for (int j = 0; j < NA; ++j) {
+        const int row = (w * NA + j) * RPP + lane / UA;    /* piece w*NA+j: RPP token rows = 1 KB */
         const int tok = row < M ? row : M - 1;
-        au[j] = (lane & 15) ^ (row & 15);
+        au[j] = (lane % UA) ^ (row & 15);
         asrc[j] = P.q + (int64_t)tok * K + au[j] * 16;
     }
-    const bl_v4i* wsrc;
-    int wunit;
-    {
-        const int U = w * nl + lane;                       /* unit of the stage's weight region */
-        const int row = U >> 2;
-        wunit = (U & 3) ^ ((row >> 2) & 3);
+    const bl_v4i* wsrc[NWL];
+    int wunit[NWL];
+#pragma unroll
+    for (int jj = 0; jj < NWL; ++jj) {
+        const int U = w * WPW + jj * 64 + lane;            /* unit of the stage's weight region */
+        const int row = U / UW;
+        wunit[jj] = (U % UW) ^ (UW == 4 ? (row >> 2) & 3 : (row >> 1) & 7);
         int n = n_base + row;
         if (n >= N) n = N - 1;
-        wsrc = P.packed + (int64_t)n * wunits + wunit;
+        wsrc[jj] = P.packed + (int64_t)n * wunits + wunit[jj];
     }
     auto issue = [&](int ks, int buf) {
         uint8_t* base = ring + buf * STG;
         /* wave-uniform: only the last step can be partial, and only then are sources clamped (the
          * full steps pay one 64-bit add per load and nothing else) */
-        if (ks * 256 + 256 > K) {
+        if (ks * KS + KS > K) {
 #pragma unroll
-            for (int j = 0; j < TB; ++j) {
-                const int8_t* src = asrc[j] + ks * 256;
-                if (ks * 256 + au[j] * 16 >= K) src -= au[j] * 16;
-                __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + (w * TB + j) * 1024), 16, 0, 0);
+            for (int j = 0; j < NA; ++j) {
+                const int8_t* src = asrc[j] + ks * KS;
+                if (ks * KS + au[j] * 16 >= K) src -= au[j] * 16;
+                __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + (w * NA + j) * 1024), 16, 0, 0);
             }
             if (lane < nl) {
-                const bl_v4i* src = wsrc + ks * 4;
-                if (ks * 4 + wunit >= wunits) src -= wunit;
-                __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + SA + w * nl * 16), 16, 0, 0);
+#pragma unroll
+                for (int jj = 0; jj < NWL; ++jj) {
+                    const bl_v4i* src = wsrc[jj] + ks * UW;
+                    if (ks * UW + wunit[jj] >= wunits) src -= wunit[jj];
+                    __builtin_amdgcn_global_load_lds((bl_gptr)src, (bl_lptr)(base + SA + (w * WPW + jj * 64) * 16), 16,
+                                                     0, 0);
+                }
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < TB; ++j)
-                __builtin_amdgcn_global_load_lds((bl_gptr)(asrc[j] + ks * 256), (bl_lptr)(base + (w * TB + j) * 1024),
-                                                 16, 0, 0);
-            if (lane < nl)
-                __builtin_amdgcn_global_load_lds((bl_gptr)(wsrc + ks * 4), (bl_lptr)(base + SA + w * nl * 16), 16, 0,
-                                                 0);
+            for (int j = 0; j < NA; ++j)
+                __builtin_amdgcn_global_load_lds((bl_gptr)(asrc[j] + ks * KS), (bl_lptr)(base + (w * NA + j) * 1024), 16,
+                                                 0, 0);
+            if (lane < nl) {
+#pragma unroll
+                for (int jj = 0; jj < NWL; ++jj)
+                    __builtin_amdgcn_global_load_lds((bl_gptr)(wsrc[jj] + ks * UW),
+                                                     (bl_lptr)(base + SA + (w * WPW + jj * 64) * 16), 16, 0, 0);
+            }
         }
     };
 
@@ -139,14 +156,15 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
 
     /* per-lane LDS read offsets inside a stage: this wave's MFMA sub-steps are s = kh*TB + j,
      * packed word / activation unit 8h + s */
-    const int u0 = h * 8 + kh * NSUB;                      /* first word (and activation unit) of the wave */
+    const int u0 = h * (KS / 32) + kh * NSUB;              /* first word (and activation unit) of the wave */
     const int ar = tb * 32 + l32;                          /* token row in the stage */
     int a_off[NSUB];
 #pragma unroll
-    for (int j = 0; j < NSUB; ++j) a_off[j] = ar * 256 + (((u0 + j) ^ (ar & 15)) * 16);
-    /* weight row l32 of block ni sits at (ni*32 + l32) * 64; its unit u0/4 is swizzled with
-     * bits 2..3 of the row, which do not depend on ni */
-    const int w_off = SA + l32 * 64 + ((((u0 >> 2) ^ (l32 >> 2)) & 3) * 16) + (u0 & 3) * 4;
+    for (int j = 0; j < NSUB; ++j) a_off[j] = ar * KS + (((u0 + j) ^ (ar & 15)) * 16);
+    /* weight row l32 of block ni sits at (ni*32 + l32) * KS/4; its unit u0/4 is swizzled with
+     * row bits that do not depend on ni */
+    const int w_off = SA + l32 * (KS / 4) +
+                      (((u0 >> 2) ^ (UW == 4 ? (l32 >> 2) & 3 : (l32 >> 1) & 7)) * 16) + (u0 & 3) * 4;
 
     auto compute = [&](int ks, int buf, auto tail_tag) {
         constexpr bool TAIL = decltype(tail_tag)::value;   /* a partial last step: mask the words beyond K */
@@ -158,16 +176,20 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
             {
-                if constexpr (NSUB == 2) {
-                    const bl_v2i q2 = *(const bl_v2i*)(st + w_off + ni * 2048);
+                if constexpr (NSUB == 4) {
+                    const bl_v4i q4 = *(const bl_v4i*)(st + w_off + ni * 32 * (KS / 4));
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) wds[ni][j] = (uint32_t)q4[j];
+                } else if constexpr (NSUB == 2) {
+                    const bl_v2i q2 = *(const bl_v2i*)(st + w_off + ni * 32 * (KS / 4));
                     wds[ni][0] = (uint32_t)q2[0];
                     wds[ni][1] = (uint32_t)q2[1];
                 } else {
-                    wds[ni][0] = (uint32_t)*(const int*)(st + w_off + ni * 2048);
+                    wds[ni][0] = (uint32_t)*(const int*)(st + w_off + ni * 32 * (KS / 4));
                 }
             }
         }
-        const int k0 = ks * 256;
+        const int k0 = ks * KS;
 #pragma unroll
         for (int j = 0; j < NSUB; ++j) {
             const bool cv = !TAIL || k0 + (u0 + j) * 16 < K;
@@ -203,7 +225,7 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
         if (it == 1) BL_PSTAMP(3);
         const int nx = it + S - 1;
         if (nx < nsteps) issue(nx, nx % S);
-        if (it * 256 + 256 > K) compute(it, it % S, std::true_type());
+        if (it * KS + KS > K) compute(it, it % S, std::true_type());
         else compute(it, it % S, std::false_type());
     }
 
@@ -300,20 +322,20 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
 
 /* NI is a property of the workgroup's product: one specialised body per value, so that the
  * accumulators are a fixed set of registers. */
-template <int TB, int S, bool NEED_SUM>
+template <int TB, int S, bool NEED_SUM, int KS>
 __global__ __launch_bounds__(512) void bl_gemv_panel(const bl_gemv_group grp, const int M) {
     extern __shared__ __attribute__((aligned(16))) int lds[];
     const bl_gemv_prob P = bl_fetch_prob(grp);
-    if (P.ksplit == 4) bl_panel_body<TB, S, NEED_SUM, 4>(P, M, lds);
-    else if (P.ksplit == 2) bl_panel_body<TB, S, NEED_SUM, 2>(P, M, lds);
-    else bl_panel_body<TB, S, NEED_SUM, 1>(P, M, lds);
+    if (P.ksplit == 4) bl_panel_body<TB, S, NEED_SUM, 4, KS>(P, M, lds);
+    else if (P.ksplit == 2) bl_panel_body<TB, S, NEED_SUM, 2, KS>(P, M, lds);
+    else bl_panel_body<TB, S, NEED_SUM, 1, KS>(P, M, lds);
 }
 
-template <int TB, int S>
+template <int TB, int S, int KS>
 static bl_status launch_panel(const bl_gemv_group& grp, int M, int blocks, bool have_sums, hipStream_t st) {
-    constexpr int lds = BL_PANEL_HEAD * 4 + S * (TB * 8192 + 8192);
+    constexpr int lds = BL_PANEL_HEAD * 4 + S * (TB * 32 * KS + 128 * (KS / 4));
     static_assert(lds <= 160 * 1024, "LDS of one CU");
-    auto kern = have_sums ? bl_gemv_panel<TB, S, false> : bl_gemv_panel<TB, S, true>;
+    auto kern = have_sums ? bl_gemv_panel<TB, S, false, KS> : bl_gemv_panel<TB, S, true, KS>;
     static bool done[2] = {false, false};
     if (!done[have_sums]) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
@@ -324,7 +346,7 @@ static bl_status launch_panel(const bl_gemv_group& grp, int M, int blocks, bool 
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
-/* 17 <= M <= 64, int8 inputs only.  Rows per workgroup: 32 * NI.  A long k gets NI = 1: its
+/* M <= 64, int8 inputs only.  Rows per workgroup: 32 * NI.  A long k gets NI = 1: its
  * workgroups stream the most activation bytes and would otherwise finish last (measured on
  * the four shapes of a layer at M = 64: 18.9 us against 22.4 with NI = 2); every NI is halved
  * while the launch would leave most CUs without a workgroup.  BL_PANEL_NI forces one value. */
@@ -352,5 +374,10 @@ bl_status bl_gemv_panel_launch(bl_gemv_group& grp, int M, hipStream_t st) {
         }
         if (blocks >= 128 || floor_all || force) break;
     }
-    return TB == 1 ? launch_panel<1, 8>(grp, M, blocks, have_sums, st) : launch_panel<2, 6>(grp, M, blocks, have_sums, st);
+    const char* eks = getenv("BL_PANEL_KS");
+    if (eks && atoi(eks) == 256)
+        return TB == 1 ? launch_panel<1, 8, 256>(grp, M, blocks, have_sums, st)
+                       : launch_panel<2, 6, 256>(grp, M, blocks, have_sums, st);
+    return TB == 1 ? launch_panel<1, 4, 512>(grp, M, blocks, have_sums, st)
+                   : launch_panel<2, 3, 512>(grp, M, blocks, have_sums, st);
 }

@@ -167,10 +167,11 @@ def test_both_small_m_decode_kernels(bl, monkeypatch, path, M):
 
 
 @pytest.mark.parametrize("path", ["mma", "panel"])
-@pytest.mark.parametrize("M,N,K", [(17, 2560, 2560), (32, 264, 2624), (40, 100, 1088), (64, 2560, 6912), (64, 36, 192)])
+@pytest.mark.parametrize("M,N,K", [(5, 264, 1088), (12, 2560, 2560), (17, 2560, 2560), (32, 264, 2624),
+                                   (40, 100, 1088), (64, 2560, 6912), (64, 36, 192), (9, 20, 64)])
 def test_both_batched_decode_kernels_at_every_m(bl, monkeypatch, path, M, N, K):
-    """The library picks one of two kernels for 17..64 tokens by measured speed; BL_GEMV_PATH
-    forces either, and both must give the oracle's numbers on every shape."""
+    """The library picks one of two matrix-core kernels by measured speed; BL_GEMV_PATH forces
+    either, and both must give the oracle's numbers on every shape."""
     monkeypatch.setenv("BL_GEMV_PATH", path)
     c = Case(37, M, N, K)
     for layout in (0, 1):
