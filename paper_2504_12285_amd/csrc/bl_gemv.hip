@@ -778,11 +778,17 @@ static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks
  * scheme (the caller then uses the prefill kernel). */
 bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
     const char* path_env = getenv("BL_GEMV_PATH");
-    bool any_norm = false;
-    for (int i = 0; i < grp.count; ++i) any_norm = any_norm || (grp.p[i].fused && grp.p[i].prod.norm);
+    bool any_norm = false, any_fused = false;
+    for (int i = 0; i < grp.count; ++i) {
+        any_norm = any_norm || (grp.p[i].fused && grp.p[i].prod.norm);
+        any_fused = any_fused || grp.p[i].fused;
+    }
+    /* (a group of int8 products at M = 2 already does better on the panel kernel: 9.9 against 11.2) */
     const bool dot4 = path_env && path_env[0] == 'm'   ? false
                       : path_env && path_env[0] == 'r' ? M <= 4
-                                                       : (M <= 2 || (M <= 4 && any_norm));
+                      : path_env && path_env[0] == 'p' ? M <= 2 && any_fused
+                                                       : (M == 1 || (M == 2 && (any_fused || grp.count == 1)) ||
+                                                          (M <= 4 && any_norm));
     int G = dot4 ? bl_env_int("BL_GEMV_G", 8) : 4;
     if ((G != 4 && G != 8) || (dot4 && any_norm)) G = 8;
     const int force_split = bl_env_int("BL_GEMV_KSPLIT", 0);
@@ -824,8 +830,6 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
          *   four calls:  M = 8: 23.4 / 28.9, 16: 26.7 / 29.3, 24: 37.1 / 29.7, 48: 54.1 / 38.1
          * so a group goes to the panel kernel whenever it can, a product alone from 20 tokens.
          * BL_GEMV_PATH=mma / panel force one of them. */
-        bool any_fused = false;
-        for (int i = 0; i < grp.count; ++i) any_fused = any_fused || grp.p[i].fused;
         const bool want_panel =
             !any_fused && (path_env ? path_env[0] == 'p' : (grp.count > 1 || M >= 20));
         if (want_panel) return bl_gemv_panel_launch(grp, M, st);

@@ -339,7 +339,7 @@ def test_fused_decode_zero_and_tiny_rows(bl):
     assert_y_close(y.cpu().numpy(), ref["y"])
 
 
-@pytest.mark.parametrize("M,fused", [(1, False), (1, True), (4, False), (4, True), (8, False), (8, True),
+@pytest.mark.parametrize("M,fused", [(1, False), (1, True), (2, False), (2, True), (4, False), (4, True), (8, False), (8, True),
                                      (8, "mixed"), (24, False), (40, False), (64, False)])
 def test_grouped_decode_whole_layer(bl, M, fused):
     """The four shapes of one layer in ONE launch equal four oracle products."""
