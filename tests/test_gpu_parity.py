@@ -409,6 +409,45 @@ def test_grouped_decode_two_products_one_with_residual(bl, M):
     assert np.all(np.abs(got - want) <= 1e-6 * np.abs(cb.y) + 1.2e-7 * np.abs(want))
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_grouped_decode_seeded_shape_mix(bl, seed):
+    """Seeded mixes of valid shapes through the grouped entry point: 1..4 int8 products with
+    ragged N, K not a multiple of the kernels' k steps, either layout, optional row sums,
+    residuals and int32 outputs; every token count from 2 to 64 comes up over the seeds."""
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.integers(2, 65))
+    layout = int(rng.integers(0, 2))
+    count = int(rng.integers(1, 5))
+    items, cases, residuals = [], [], []
+    for i in range(count):
+        N = 4 * int(rng.integers(1, 150))
+        K = 64 * int(rng.integers(1, 70))
+        c = Case(2000 + 10 * seed + i, M, N, K)
+        it = dict(packed=to_dev(c.packed(layout)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=N, K=K,
+                  q=to_dev(c.q), scale=to_dev(c.scale),
+                  y=torch.empty((M, N), dtype=torch.float32, device="cuda:0"))
+        if rng.integers(0, 2):
+            it["rowsum"] = to_dev(c.rowsum)
+        if rng.integers(0, 2):
+            it["acc"] = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
+        res = None
+        if rng.integers(0, 3) == 0:
+            res = rng.standard_normal((M, N)).astype(np.float32)
+            it["residual"] = to_dev(res)
+        items.append(it); cases.append(c); residuals.append(res)
+    bl.bl_bitlinear_decode_group(bl.make_decode_descs(items), layout, M)
+    _sync()
+    for it, c, res in zip(items, cases, residuals):
+        if "acc" in it:
+            assert np.array_equal(it["acc"].cpu().numpy(), c.acc)
+        got = it["y"].cpu().numpy()
+        if res is None:
+            assert_y_close(got, c.y)
+        else:
+            want = res + c.y
+            assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.abs(c.y) + 1.2e-7 * np.abs(want))
+
+
 def test_fused_fixed_scale(bl):
     c = Case(53, 2, 128, 256)
     it = dict(packed=to_dev(c.packed(1)), beta=to_dev(np.array([c.beta], dtype=np.float32)), N=c.N, K=c.K,
