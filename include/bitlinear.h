@@ -229,6 +229,19 @@ bl_status bl_gemm_w158a8_res(const uint8_t* packed, const float* beta, int layou
                              int64_t M, int64_t N, int64_t K, const float* residual,
                              int32_t* acc, float* y, void* workspace, bl_stream s);
 
+/* bl_gemm_w158a8 for callers that cannot allocate device memory or bring a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same product and same results as bl_gemm_w158a8 called with rowsum = NULL;
+ * the scratch for the row sums sum_k q[m][k] is a static device array inside the library
+ * (64 KiB per GPU, held until the process ends), so the call allocates and frees nothing.
+ * Limit: 1 <= M <= 16384, else BL_ERR_SHAPE.  All calls on one GPU share that array:
+ * calls that overlap on the same GPU (different streams or threads) race; calls on one
+ * stream, or otherwise ordered, are safe.  Nothing needs clearing between calls. */
+bl_status bl_gemm_w158a8_noalloc(const uint8_t* packed, const float* beta, int layout,
+                                 const int8_t* q, const float* scale,
+                                 int64_t M, int64_t N, int64_t K,
+                                 int32_t* acc, float* y, bl_stream s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ SIGNATURES = {
     "bl_bitlinear_decode_group": (_ci, [_vp, _ci, _ci, _i64, _vp]),
     "bl_quant_act_ex": (_ci, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_gemm_w158a8_res": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "bl_gemm_w158a8_noalloc": (_ci, [_vp, _vp, _ci, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
 }
 
 BL_PROD_BF16, BL_PROD_F32, BL_PROD_ATTN_V, BL_PROD_RESIDUAL, BL_PROD_RELU2_GATE = 0, 1, 2, 3, 4
@@ -261,4 +262,13 @@ def bl_gemm_w158a8_res(packed, beta, layout, q, scale, rowsum, N, residual, want
     _check(load().bl_gemm_w158a8_res(_ptr(packed), _ptr(beta), layout, _ptr(q), _ptr(scale), _ptr(rowsum), M, N, K,
                                      _ptr(residual), _ptr(acc), _ptr(y), _ptr(workspace), _stream()),
            "bl_gemm_w158a8_res")
+    return acc, y
+
+
+def bl_gemm_w158a8_noalloc(packed, beta, layout, q, scale, N, acc=None, y=None):
+    """Prefill product through the entry point that allocates nothing (row sums in the
+    library's static device scratch).  The caller passes the outputs; returns (acc, y)."""
+    M, K = q.shape
+    _check(load().bl_gemm_w158a8_noalloc(_ptr(packed), _ptr(beta), layout, _ptr(q), _ptr(scale), M, N, K,
+                                         _ptr(acc), _ptr(y), _stream()), "bl_gemm_w158a8_noalloc")
     return acc, y

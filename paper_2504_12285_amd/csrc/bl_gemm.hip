@@ -11,6 +11,8 @@
 
 #include <stdlib.h>
 
+#include <atomic>
+
 #define GEMM_THREADS 256
 
 #define GEMM_PAD 16   /* bytes of padding per activation row in LDS (bank spread) */
@@ -567,4 +569,48 @@ extern "C" bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, in
                                     const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
                                     int32_t* acc, float* y, void* workspace, bl_stream s) {
     return bl_gemm_w158a8_res(packed, beta, layout, q, scale, rowsum, M, N, K, nullptr, acc, y, workspace, s);
+}
+
+/* ---- entry point that allocates nothing ---------------------------------------------------
+ * bl_gemm_w158a8 needs device scratch for the row sums sum_k q[m][k] when the caller brings
+ * none.  Here that scratch is a static device array: every GPU the library runs on holds its
+ * own copy, at its own address, until the process ends.  In host code the array's name is only
+ * a stand-in: the device address comes from hipGetSymbolAddress, once per device, and that
+ * pointer is what the kernels receive. */
+#define BL_NOALLOC_MAX_DEVICES 64
+static __device__ __align__(256) int32_t scratch[BL_NOALLOC_MAX_M];
+static std::atomic<int32_t*> bl_scratch_ptr[BL_NOALLOC_MAX_DEVICES];
+
+static bl_status bl_scratch_for_current_device(int32_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= BL_NOALLOC_MAX_DEVICES) return BL_ERR_HIP;
+    int32_t* p = bl_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        /* two threads racing here both obtain the same address: the symbol has one copy per device */
+        void* sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return BL_ERR_HIP;
+        p = (int32_t*)sym;
+        bl_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return BL_OK;
+}
+
+extern "C" bl_status bl_gemm_w158a8_noalloc(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
+                                            const float* scale, int64_t M, int64_t N, int64_t K, int32_t* acc,
+                                            float* y, bl_stream s) {
+    if (!packed || !beta || !q) return BL_ERR_NULL;
+    if (!acc && !y) return BL_ERR_NULL;
+    if (y && !scale) return BL_ERR_NULL;
+    if (M < 1 || M > BL_NOALLOC_MAX_M || !bl_shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (!bl_aligned(packed, 16) || !bl_aligned(q, 16) || !bl_aligned(acc, 4) || !bl_aligned(y, 4) ||
+        !bl_aligned(scale, 4) || !bl_aligned(beta, 4))
+        return BL_ERR_ALIGN;
+    int32_t* rs = nullptr;
+    const bl_status st = bl_scratch_for_current_device(&rs);
+    if (st != BL_OK) return st;
+    /* the row-sum kernel overwrites entries 0..M-1 and nothing reads beyond them, so what an
+     * earlier (larger) call left behind needs no clearing */
+    return bl_gemm_dispatch(packed, beta, layout, q, scale, nullptr, M, N, K, nullptr, acc, y, rs, (hipStream_t)s);
 }

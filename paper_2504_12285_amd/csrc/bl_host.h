@@ -5,6 +5,7 @@
 #include "bitlinear.h"
 
 #define BL_PACK_PARTIALS 1024          /* fp64 partial sums used by bl_pack_ternary */
+#define BL_NOALLOC_MAX_M 16384          /* rows bl_gemm_w158a8_noalloc accepts        */
 #define BL_MAX_DIM ((int64_t)1 << 24)  /* upper bound on M, N and K                 */
 
 static inline bool bl_shape_ok(int64_t N, int64_t K) {

@@ -113,3 +113,13 @@ def test_binding_raises_with_status():
     with pytest.raises(bl.BitLinearError) as e:
         bl._check(2, "bl_gemv_w158a8")
     assert e.value.status == 2 and "BL_ERR_SHAPE" in str(e.value)
+
+
+def test_noalloc_entry_point_checks_arguments_before_any_gpu_work(lib):
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) & ~255
+    assert lib.bl_gemm_w158a8_noalloc(None, p, 1, p, p, 1, 64, 64, p, p, None) == 1      # NULL packed
+    assert lib.bl_gemm_w158a8_noalloc(p, p, 1, p, p, 16385, 64, 64, p, p, None) == 2     # beyond the scratch
+    assert lib.bl_gemm_w158a8_noalloc(p, p, 1, p, p, 0, 64, 64, p, p, None) == 2
+    assert lib.bl_gemm_w158a8_noalloc(p, p, 9, p, p, 1, 64, 64, p, p, None) == 3         # layout
+    assert lib.bl_gemm_w158a8_noalloc(p + 4, p, 1, p, p, 1, 64, 64, p, p, None) == 4     # alignment
