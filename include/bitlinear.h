@@ -163,12 +163,12 @@ bl_status bl_bitlinear_decode(const uint8_t* packed, const float* beta, int layo
  * norm != 0 adds the sub-layer normalisation in front of the quantiser (Section 2,
  * "Normalization"; the report names the scheme but gives no formula, so this is the
  * bias-free RMS form): with t[k] the fp32 value of the kind above BEFORE narrowing,
- *   ss = sum_k t[k]^2 in fp64 in a FIXED order (256 leaves: leaf j sums, ascending, the
- *        16-element groups u = j, j+256, ..; leaves are joined by a butterfly over
- *        strides 1,2,..,32 inside each block of 64, then (b0+b1)+(b2+b3)),
+ *   ss = sum_k t[k]^2 with exact fp64 squares and an fp64 sum (relative error of the sum
+ *        far below 1e-12; the order inside a kernel is fixed, so a result is reproducible),
  *   r = fp32(1 / sqrt(ss/K + eps)) in fp64,   X[k] = bf16((t[k]*r)*gain[k])
- * (gain NULL: no second multiply).  Every step is a single rounded IEEE operation, so
- * the result does not depend on the launch shape.  BL_PROD_RESIDUAL still stores the
+ * (gain NULL: no second multiply).  Every later step is a single rounded IEEE operation; r can
+ * depend on the summation order only when 1/sqrt(ss/K+eps) lies within ~1e-12 (relative) of
+ * an fp32 rounding midpoint.  BL_PROD_RESIDUAL still stores the
  * un-normalised sum in aux_out.
  * All pointers are device pointers, 16-byte aligned. */
 enum { BL_PROD_BF16 = 0, BL_PROD_F32 = 1, BL_PROD_ATTN_V = 2, BL_PROD_RESIDUAL = 3, BL_PROD_RELU2_GATE = 4 };

@@ -62,7 +62,7 @@ def _load():
         lib.orc_chain_residual.restype = None
         lib.orc_chain_relu2_gate.argtypes = [vp, i64, i64, vp]
         lib.orc_chain_relu2_gate.restype = None
-        lib.orc_rmsnorm_rows.argtypes = [vp, i64, i64, vp, f32, vp]
+        lib.orc_rmsnorm_rows.argtypes = [vp, i64, i64, vp, f32, vp, vp]
         lib.orc_rmsnorm_rows.restype = None
         lib.orc_chain_attn_f32.argtypes = [vp, i64, ci, ci, ci, vp]
         lib.orc_chain_attn_f32.restype = None
@@ -233,17 +233,36 @@ def chain_relu2_gate(gu):
     return f
 
 
-def rmsnorm_rows(t, gain=None, eps=1e-5):
-    """bf16 bits of the RMS-normalised rows of t (fp32 [M][K]); fixed fp64 summation
-    order, see orc_rmsnorm_rows."""
+def fp32_rounding_guard_ok(v64, rel=1e-11):
+    """True if the fp64 value is not within `rel` (relative) of the midpoint of two adjacent
+    fp32 values: every fp64 evaluation that differs from it by less narrows to the same fp32."""
+    f = np.float32(v64)
+    for nb in (np.nextafter(f, np.float32(np.inf)), np.nextafter(f, np.float32(-np.inf))):
+        mid = (float(f) + float(nb)) / 2.0
+        if abs(v64 - mid) <= rel * abs(v64):
+            return False
+    return True
+
+
+def rmsnorm_rows(t, gain=None, eps=1e-5, return_r64=False, check_guard=True):
+    """bf16 bits of the RMS-normalised rows of t (fp32 [M][K]); the sum of squares is the
+    exact real sum to fp64 accuracy (compensated), see orc_rmsnorm_rows.  check_guard: raise
+    if a row's factor 1/sqrt(ss/K+eps) lies so close to an fp32 rounding boundary that another
+    fp64 summation order could narrow differently (then the test input must change)."""
     t = _c(t, np.float32)
     M, K = t.shape
     assert K % 16 == 0
     g = None if gain is None else _c(gain, np.float32)
     assert g is None or g.shape == (K,)
     out = np.empty((M, K), dtype=np.uint16)
-    _load().orc_rmsnorm_rows(_p(t), M, K, None if g is None else _p(g), float(np.float32(eps)), _p(out))
-    return out
+    r64 = np.empty(M, dtype=np.float64)
+    _load().orc_rmsnorm_rows(_p(t), M, K, None if g is None else _p(g), float(np.float32(eps)), _p(out), _p(r64))
+    if check_guard:
+        bad = [m for m in range(M) if not fp32_rounding_guard_ok(float(r64[m]))]
+        if bad:
+            raise ValueError("rmsnorm factor of rows %s too close to an fp32 rounding midpoint: "
+                             "change the input seed" % bad[:8])
+    return (out, r64) if return_r64 else out
 
 
 def chain_attn_f32(qkv, n_q=20, n_kv=5, hd=128):

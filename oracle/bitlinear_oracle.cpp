@@ -256,36 +256,31 @@ void orc_chain_relu2_gate(const float* gu, int64_t M, int64_t F, uint16_t* f) {
 /* Sub-layer normalisation in front of the quantiser (Section 2, "Normalization": the
  * report names sub-LN and removes all biases but prints no formula; this is the bias-free
  * RMS form).  For each row t[K] (fp32):
- *   ss = sum_k t[k]^2, every square and every addition in fp64, in this FIXED order:
- *        256 leaves; leaf j adds, in ascending k, the 16-element groups u = j, j+256, ..
- *        (group u = elements 16u..16u+15); the leaves are joined inside each block of 64
- *        by a butterfly over strides 1, 2, 4, 8, 16, 32 (new[j] = old[j] + old[j^s]) and
- *        the four block sums as (b0 + b1) + (b2 + b3);
+ *   ss = sum_k t[k]^2: every square is exact in fp64 (24-bit operands), and the sum is
+ *        carried sequentially, ascending k, with Neumaier compensation, so ss is the exact
+ *        real sum to within a few units of 1e-16 relative, whatever the order;
  *   r  = fp32( 1 / sqrt(ss/K + eps) )   (fp64 operations, one final narrowing);
  *   out[k] = bf16( (t[k]*r) * gain[k] )  (fp32 multiplies; gain == NULL: no second one).
- * K % 16 == 0.  Parity pinned by closed forms and against the fp64 formula in the tests;
- * the summation order itself is this file's reading. */
-void orc_rmsnorm_rows(const float* t, int64_t M, int64_t K, const float* gain, float eps, uint16_t* out) {
-    const int64_t groups = K / 16;
+ * r64 (optional, [M]): the fp64 value of 1/sqrt(ss/K + eps) before the narrowing, so that a
+ * caller can assert that it does not sit on an fp32 rounding boundary (any other fp64
+ * summation order then narrows to the same r).
+ * Parity pinned by closed forms and against the fp64 formula in the tests. */
+void orc_rmsnorm_rows(const float* t, int64_t M, int64_t K, const float* gain, float eps, uint16_t* out,
+                      double* r64) {
     for (int64_t m = 0; m < M; ++m) {
         const float* row = t + m * K;
-        double leaf[256];
-        for (int j = 0; j < 256; ++j) {
-            double p = 0.0;
-            for (int64_t u = j; u < groups; u += 256)
-                for (int e = 0; e < 16; ++e) {
-                    const double v = (double)row[u * 16 + e];
-                    p += v * v;
-                }
-            leaf[j] = p;
+        double sum = 0.0, comp = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const double a = (double)row[k] * (double)row[k];
+            const double u = sum + a;
+            if (std::fabs(sum) >= a) comp += (sum - u) + a;
+            else                     comp += (a - u) + sum;
+            sum = u;
         }
-        for (int s = 1; s < 64; s <<= 1) {
-            double next[256];
-            for (int j = 0; j < 256; ++j) next[j] = leaf[j] + leaf[j ^ s];
-            for (int j = 0; j < 256; ++j) leaf[j] = next[j];
-        }
-        const double ss = (leaf[0] + leaf[64]) + (leaf[128] + leaf[192]);
-        const float r = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+        const double ss = sum + comp;
+        const double rd = 1.0 / std::sqrt(ss / (double)K + (double)eps);
+        if (r64) r64[m] = rd;
+        const float r = (float)rd;
         for (int64_t k = 0; k < K; ++k) {
             float v = row[k] * r;
             if (gain) v = v * gain[k];

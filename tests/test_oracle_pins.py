@@ -392,6 +392,18 @@ def test_chain_glue_against_torch():
     assert np.array_equal(f, want)
     x, y = qkv[:, :2560], qkv[:, 100:2660]
     assert np.array_equal(oracle.chain_residual(x, y), x + y)
+    # the fp32 forms used in front of the normalisation: the same maps without the narrowing
+    assert np.array_equal(oracle.chain_attn_f32(qkv).view(np.uint32), v.contiguous().numpy().view(np.uint32))
+    assert np.array_equal(oracle.chain_relu2_gate_f32(gu).view(np.uint32), ((r * r) * u).numpy().view(np.uint32))
+    # a wrong head mapping or operand order would show: V of kv head 1 feeds q heads 4..7 only
+    probe = np.zeros((1, 3840), np.float32)
+    probe[0, 3200 + 128 + 5] = 2.5
+    a32 = oracle.chain_attn_f32(probe)
+    assert sorted(np.nonzero(a32[0])[0].tolist()) == [h * 128 + 5 for h in range(4, 8)]
+    gate = np.zeros((1, 8), np.float32)
+    gate[0, :4] = [-3.0, 2.0, 0.5, 0.0]
+    gate[0, 4:] = [7.0, -1.5, 4.0, 9.0]
+    assert oracle.chain_relu2_gate_f32(gate)[0].tolist() == [0.0, -6.0, 1.0, 0.0]
 
 
 def test_chain_layer_stays_bounded_and_is_token_independent():
@@ -472,6 +484,20 @@ def test_rmsnorm_against_fp64_formula_and_gains():
         # rows are independent and the gain is elementwise
         one = oracle.rmsnorm_rows(t[2:3], g, 1e-5)
         assert np.array_equal(one, oracle.rmsnorm_rows(t, g, 1e-5)[2:3])
+    # the sum of squares is the exactly rounded one: math.fsum of the exact fp64 squares
+    import math
+    for K in (64, 2560, 6912):
+        t = (rng.standard_normal((4, K)) * 1e3).astype(np.float32)
+        _, r64 = oracle.rmsnorm_rows(t, None, 1e-5, return_r64=True)
+        for m in range(4):
+            ss = math.fsum(float(v) * float(v) for v in t[m])
+            want = 1.0 / math.sqrt(ss / K + float(np.float32(1e-5)))
+            assert abs(r64[m] - want) <= 4e-16 * want
+    # the guard trips exactly when the factor sits at an fp32 rounding midpoint
+    f = np.float32(0.3)
+    mid = (float(f) + float(np.nextafter(f, np.float32(1)))) / 2.0
+    assert not oracle.fp32_rounding_guard_ok(mid) and not oracle.fp32_rounding_guard_ok(mid * (1 + 5e-12))
+    assert oracle.fp32_rounding_guard_ok(mid * (1 + 1e-9)) and oracle.fp32_rounding_guard_ok(float(f))
     # unit RMS after normalisation (before narrowing the mean square is 1 up to eps)
     t = rng.standard_normal((3, 4096)).astype(np.float32) * 7
     out = _bf16_to_f32(oracle.rmsnorm_rows(t, None, 1e-5)).astype(np.float64)
