@@ -229,6 +229,41 @@ bl_status bl_gemm_w158a8_res(const uint8_t* packed, const float* beta, int layou
                              int64_t M, int64_t N, int64_t K, const float* residual,
                              int32_t* acc, float* y, void* workspace, bl_stream s);
 
+/* Persistent streaming decode over a TABLE of products (Section 5.1: the decode kernel is
+ * there to use as little memory bandwidth as possible, which on this GPU means the weight
+ * stream of a whole stack of BitLinears must never stop).  One launch walks every product
+ * of the table with as many workgroups as stay resident; each product is the same
+ * arithmetic, bit for bit, as one entry of bl_bitlinear_decode_group.  Entries with a fused
+ * input are quantised (Section 2) without a pass of their own: a plain bf16 input (X) inside
+ * the stream launch, by each workgroup that meets the product (about five hundred workgroups
+ * over the table, each meeting one or two products; no data crosses workgroups); a
+ * producer or a normalised input (prod) by a small preparation launch in front of it (one
+ * workgroup per such entry, into scratch inside `table`; the same launch computes a missing
+ * rowsum of an int8 entry); int8 entries are streamed as they are.
+ * The products of one table are INDEPENDENT: none may read what another writes.
+ *   bl_stack_table_bytes  device bytes `table` needs for these descriptors (HOST array): the
+ *                         table itself plus the scratch for quantised rows.  0: bad count or K.
+ *   bl_stack_build        setup call: checks the descriptors (HOST array), lays the work out
+ *                         over the grid, copies the table to `table` (device, 256-byte
+ *                         aligned, caller-owned) and fills *plan (HOST, caller-owned).  It
+ *                         waits for that copy on `s` (the only call here that synchronises).
+ *                         Limits: M = 1, 1 <= count <= 1024, K <= 20480 per product.
+ *   bl_stack_run          at most two kernel launches on `s` (preparation, stream); no
+ *                         allocation, no synchronisation; may be captured in a HIP graph and
+ *                         replayed.  The table and every tensor it names must stay alive and
+ *                         in place; runs on one table must not overlap (they share the scratch). */
+enum { BL_STACK_MAX_COUNT = 1024 };
+typedef struct {
+    int32_t count, blocks, prep_count, inline_count, norm, lds_bytes;
+    int64_t wg_offset, prep_offset;   /* byte offsets inside `table`                            */
+    int64_t packed_bytes;             /* sum of N*K/4 over the products: bytes one run streams */
+    int64_t table_bytes;
+} bl_stack_plan;
+size_t    bl_stack_table_bytes(const bl_decode_desc* descs, int count);
+bl_status bl_stack_build(const bl_decode_desc* descs, int count, int layout, int64_t M,
+                         void* table, bl_stack_plan* plan, bl_stream s);
+bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_stream s);
+
 /* bl_gemm_w158a8 for callers that cannot allocate device memory or bring a workspace:
  * code running under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same product and same results as bl_gemm_w158a8 called with rowsum = NULL;
@@ -241,6 +276,18 @@ bl_status bl_gemm_w158a8_noalloc(const uint8_t* packed, const float* beta, int l
                                  const int8_t* q, const float* scale,
                                  int64_t M, int64_t N, int64_t K,
                                  int32_t* acc, float* y, bl_stream s);
+
+/* Measurement aids (not part of the product path): the achievable roofs the kernels are
+ * priced against beside the datasheet peaks.
+ *   bl_probe_stream_read  one launch that reads `bytes` (a multiple of 16) of device memory
+ *                         at `buf` with 128-bit loads and does nothing else; time it over a
+ *                         buffer much larger than the caches to get the streaming-read rate.
+ *   bl_probe_mfma_i8      one launch of `iters` x 4 back-to-back v_mfma_i32_32x32x32_i8 per
+ *                         wave, operands in registers; *ops (HOST, optional) receives the
+ *                         integer operations of the launch (2 per multiply-accumulate).
+ * sink: device, 64 int32, never written in practice (it keeps the work observable). */
+bl_status bl_probe_stream_read(const void* buf, size_t bytes, int32_t* sink, bl_stream s);
+bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s);
 
 #ifdef __cplusplus
 }

@@ -31,6 +31,11 @@ SIGNATURES = {
     "bl_bitlinear_decode_group": (_ci, [_vp, _ci, _ci, _i64, _vp]),
     "bl_quant_act_ex": (_ci, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_gemm_w158a8_res": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "bl_stack_table_bytes": (_sz, [_vp, _ci]),
+    "bl_stack_build": (_ci, [_vp, _ci, _ci, _i64, _vp, _vp, _vp]),
+    "bl_stack_run": (_ci, [_vp, _vp, _vp]),
+    "bl_probe_stream_read": (_ci, [_vp, _sz, _vp, _vp]),
+    "bl_probe_mfma_i8": (_ci, [_ci, _vp, _vp, _vp]),
     "bl_gemm_w158a8_noalloc": (_ci, [_vp, _vp, _ci, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
 }
 
@@ -58,6 +63,14 @@ class DecodeDesc(ctypes.Structure):
     _fields_ = [("packed", _vp), ("beta", _vp), ("X", _vp), ("q", _vp), ("scale", _vp), ("rowsum", _vp),
                 ("N", _i64), ("K", _i64), ("acc", _vp), ("y", _vp), ("q_out", _vp), ("scale_out", _vp),
                 ("fixed_scale", ctypes.c_float), ("prod", Producer), ("residual", _vp)]
+
+
+class StackPlan(ctypes.Structure):
+    """Mirror of bl_stack_plan."""
+    _fields_ = [("count", ctypes.c_int32), ("blocks", ctypes.c_int32), ("prep_count", ctypes.c_int32),
+                ("inline_count", ctypes.c_int32), ("norm", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
+                ("wg_offset", _i64), ("prep_offset", _i64),
+                ("packed_bytes", _i64), ("table_bytes", _i64)]
 
 
 class BitLinearError(RuntimeError):
@@ -272,3 +285,23 @@ def bl_gemm_w158a8_noalloc(packed, beta, layout, q, scale, N, acc=None, y=None):
     _check(load().bl_gemm_w158a8_noalloc(_ptr(packed), _ptr(beta), layout, _ptr(q), _ptr(scale), M, N, K,
                                          _ptr(acc), _ptr(y), _stream()), "bl_gemm_w158a8_noalloc")
     return acc, y
+
+
+class Stack:
+    """A product table of the persistent streaming decode kernel: bl_stack_build once,
+    bl_stack_run per step.  Holds the device table and keeps the descriptors' tensors alive."""
+
+    def __init__(self, items, layout, M, device):
+        import torch
+        self.items = items                      # keeps every tensor of the table alive
+        self.descs = make_decode_descs(items)
+        nbytes = load().bl_stack_table_bytes(self.descs, len(items))
+        if nbytes == 0:
+            raise BitLinearError(2, "bl_stack_table_bytes")
+        self.table = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.plan = StackPlan()
+        _check(load().bl_stack_build(self.descs, len(items), layout, M, _ptr(self.table), ctypes.byref(self.plan),
+                                     _stream()), "bl_stack_build")
+
+    def run(self):
+        _check(load().bl_stack_run(_ptr(self.table), ctypes.byref(self.plan), _stream()), "bl_stack_run")

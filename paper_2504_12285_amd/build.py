@@ -6,7 +6,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libbitlinear_hip.so")
-SOURCES = ["bl_api.cpp", "bl_pack.hip", "bl_quant.hip", "bl_gemv.hip", "bl_gemv_panel.hip", "bl_gemm.hip"]
+SOURCES = ["bl_api.cpp", "bl_pack.hip", "bl_quant.hip", "bl_gemv.hip", "bl_gemv_panel.hip", "bl_gemm.hip", "bl_stream.hip", "bl_probe.hip"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

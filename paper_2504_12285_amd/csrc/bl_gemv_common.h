@@ -36,17 +36,20 @@ template <typename T>
 __device__ __forceinline__ void bl_pin(T& v) {
     asm volatile("" : "+s"(v));
 }
+__device__ __forceinline__ void bl_pin_prob(bl_gemv_prob& P) {
+    bl_pin(P.packed); bl_pin(P.q); bl_pin(P.prod.kind); bl_pin(P.prod.in0); bl_pin(P.prod.in1);
+    bl_pin(P.prod.aux_out); bl_pin(P.prod.voff); bl_pin(P.prod.group); bl_pin(P.prod.hd);
+    bl_pin(P.prod.in_stride); bl_pin(P.fused); bl_pin(P.residual); bl_pin(P.beta); bl_pin(P.scale);
+    bl_pin(P.rowsum); bl_pin(P.acc); bl_pin(P.y); bl_pin(P.q_out); bl_pin(P.scale_out); bl_pin(P.N);
+    bl_pin(P.K); bl_pin(P.layout); bl_pin(P.block0); bl_pin(P.ksplit); bl_pin(P.fixed_scale);
+}
 __device__ __forceinline__ bl_gemv_prob bl_fetch_prob(const bl_gemv_group& grp) {
     int pi = 0;
 #pragma unroll
     for (int i = 1; i < BL_GEMV_MAX_GROUP; ++i)
         if (i < grp.count && (int)blockIdx.x >= grp.p[i].block0) pi = i;
     bl_gemv_prob P = grp.p[pi];
-    bl_pin(P.packed); bl_pin(P.q); bl_pin(P.prod.kind); bl_pin(P.prod.in0); bl_pin(P.prod.in1);
-    bl_pin(P.prod.aux_out); bl_pin(P.prod.voff); bl_pin(P.prod.group); bl_pin(P.prod.hd);
-    bl_pin(P.prod.in_stride); bl_pin(P.fused); bl_pin(P.residual); bl_pin(P.beta); bl_pin(P.scale);
-    bl_pin(P.rowsum); bl_pin(P.acc); bl_pin(P.y); bl_pin(P.q_out); bl_pin(P.scale_out); bl_pin(P.N);
-    bl_pin(P.K); bl_pin(P.layout); bl_pin(P.block0); bl_pin(P.ksplit); bl_pin(P.fixed_scale);
+    bl_pin_prob(P);
     return P;
 }
 

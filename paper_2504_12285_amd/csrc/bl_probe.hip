@@ -1,0 +1,78 @@
+/* Measurement aids: the two achievable roofs the BitLinear kernels are priced against beside
+ * the datasheet peaks.  bl_probe_stream_read is a plain 16-byte-per-lane streaming read of a
+ * large buffer (what the memory system delivers to a kernel that does nothing else);
+ * bl_probe_mfma_i8 is a register-resident loop of v_mfma_i32_32x32x32_i8 (what the matrix
+ * cores deliver with no operand traffic at all).  Neither is part of the product path. */
+#include "bl_device.h"
+#include "bl_host.h"
+
+typedef bl_v4i __attribute__((address_space(1))) bl_pgv4i;
+
+/* Each thread reads units tid, tid + T, tid + 2T, .. (T = all threads of the grid), eight loads
+ * in flight; the XOR of everything read goes to sink[thread] only if it equals a value that
+ * random data never produces in practice, so the loads cannot be removed. */
+__global__ __launch_bounds__(256) void bl_probe_read_kernel(const bl_v4i* __restrict__ buf, int64_t n16,
+                                                             int32_t* __restrict__ sink) {
+    const bl_pgv4i* p = (const bl_pgv4i*)buf;
+    const int64_t T = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    bl_v4i x = {0, 0, 0, 0};
+    for (; i + 7 * T < n16; i += 8 * T) {
+        bl_v4i v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + i + j * T);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x ^= v[j];
+    }
+    for (; i < n16; i += T) x ^= __builtin_nontemporal_load(p + i);
+    const int r = x[0] ^ x[1] ^ x[2] ^ x[3];
+    if (r == 0x5EEDF00D) sink[threadIdx.x & 63] = r;
+}
+
+/* Four independent accumulator chains per wave, operands in registers. */
+__global__ __launch_bounds__(256) void bl_probe_mfma_kernel(int iters, int32_t* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    bl_v4i a = {lane * 0x01010101, (lane + 3) * 0x01010101, (lane ^ 21) * 0x01010101, (lane + 9) * 0x01010101};
+    bl_v4i b = {0x01020001, 0x00010201, 0x02000102, 0x01010200};
+    bl_v16i c0 = {}, c1 = {}, c2 = {}, c3 = {};
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, a, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, b, c3, 0, 0, 0);
+    }
+    bl_mfma_fence();
+    int r = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) r ^= c0[j] ^ c1[j] ^ c2[j] ^ c3[j];
+    if (r == 0x5EEDF00D) sink[lane] = r;
+}
+
+static int probe_grid(int per_cu) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return 0;
+    return cus * per_cu;
+}
+
+extern "C" bl_status bl_probe_stream_read(const void* buf, size_t bytes, int32_t* sink, bl_stream s) {
+    if (!buf || !sink) return BL_ERR_NULL;
+    if (bytes < 16 || bytes % 16) return BL_ERR_SHAPE;
+    if (!bl_aligned(buf, 16) || !bl_aligned(sink, 4)) return BL_ERR_ALIGN;
+    const int blocks = probe_grid(8);
+    if (blocks < 1) return BL_ERR_HIP;
+    bl_probe_read_kernel<<<blocks, 256, 0, (hipStream_t)s>>>((const bl_v4i*)buf, (int64_t)(bytes / 16), sink);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+extern "C" bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s) {
+    if (!sink) return BL_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24)) return BL_ERR_SHAPE;
+    if (!bl_aligned(sink, 4)) return BL_ERR_ALIGN;
+    const int blocks = probe_grid(2);
+    if (blocks < 1) return BL_ERR_HIP;
+    bl_probe_mfma_kernel<<<blocks, 256, 0, (hipStream_t)s>>>(iters, sink);
+    if (ops) *ops = (double)blocks * 4.0 * iters * 4.0 * 2.0 * 32.0 * 32.0 * 32.0;
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}

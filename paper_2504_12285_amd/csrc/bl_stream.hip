@@ -1,0 +1,576 @@
+/* Persistent streaming decode (Section 5.1 of the BitNet b1.58 2B4T report: the decode
+ * kernel exists to minimise memory-bandwidth use, so the packed weights of a whole stack of
+ * BitLinear products are streamed from HBM in ONE launch whose loads never stop).
+ *
+ * A table of products lives in device memory.  The grid is as many workgroups as stay
+ * resident; each owns one contiguous slice of the table's weight bytes, cut at row-group
+ * boundaries, so a workgroup meets one or two products and quantises / stages the activation
+ * row of a product once.  Inside a product the four waves of a workgroup take row groups
+ * round-robin; a wave keeps the int8 activations of its lanes' k chunks in REGISTERS for
+ * the whole product (they do not depend on the row), and double-buffers the 128-bit weight
+ * loads: the loads of row group i+1 are issued before the dot products of row group i.
+ *
+ * Arithmetic as in bl_gemv.hip: offset codes c = Wt + 1, bit-pair levels isolated by masks,
+ * v_dot4_i32_i8 into four accumulators carrying 1, 4, 16, 16, DPP sums over the G lanes of
+ * a row, rowsum subtracted once per output.  One token per product (M = 1).
+ */
+#include <string.h>
+
+#include <vector>
+
+#include "bl_device.h"
+#include "bl_gemv_common.h"
+#include "bl_host.h"
+#include "bl_producer.h"
+
+/* ---- device side -------------------------------------------------------------------------- */
+
+/* Pointers read from the product table are generic to the compiler; they are cast to the
+ * global address space so that their loads and stores are global_* instructions with exact
+ * counter waits (a generic access forces a full wait at every use). */
+#define BL_G __attribute__((address_space(1)))
+typedef bl_v4i BL_G bl_gv4i;
+
+/* What the streaming kernel needs to know about one product (device memory). */
+struct bl_stream_item {
+    const bl_v4i* packed;
+    const int8_t* q;          /* [K] int8: the caller's, or the preparation kernel's output */
+    const float* scale;       /* [1] token part of the rescale factor (NULL: y is not wanted) */
+    const int32_t* rowsum;    /* [1] sum_k q */
+    const float* beta;
+    const float* residual;    /* [N] or NULL */
+    int32_t* acc;             /* [N] or NULL */
+    float* y;                 /* [N] or NULL */
+    const uint16_t* xbf16;    /* [K] bf16, or NULL: quantised by every workgroup that meets the product */
+    int8_t* q_out;            /* xbf16 only: the caller's optional copies of q and absmax/127 */
+    float* scale_out;
+    float fixed_scale;        /* xbf16 only: > 0 replaces absmax/127 in the rescale */
+    int N, nchunks, lgG, lp, layout, units, pad0;
+};
+
+/* What the preparation kernel needs: the fused producer + quantiser of one product. */
+struct bl_stream_prep_item {
+    bl_prod_dev prod;
+    int fused;                /* 1: produce + quantise; 0: only the row sum of a given q is missing */
+    const int8_t* q_in;       /* fused == 0 */
+    int8_t* q_ws;             /* [K] quantised row (fused) */
+    float* scale_ws;          /* [1] rescale factor's token part (fused) */
+    int32_t* rowsum_ws;       /* [1] */
+    int8_t* q_out;            /* caller's optional copies */
+    float* scale_out;
+    float fixed_scale;
+    int K;
+};
+
+/* Sum over aligned groups of 1 << lgG lanes (8, 16, 32 or 64), result in every lane. */
+__device__ __forceinline__ int bl_group_sum_rt(int v, int lgG) {
+    v = bl_group_sum<8>(v);
+    if (lgG >= 4) v += bl_dpp<BL_DPP_ROW_MIRROR>(v);
+    if (lgG >= 5) v += __shfl_xor(v, 16);
+    if (lgG >= 6) v += __shfl_xor(v, 32);
+    return v;
+}
+
+/* The four bit-pair levels of four packed words against the sixteen activation dwords
+ * a[s][d] of one chunk. */
+__device__ __forceinline__ void bl_stream_dot(const bl_v4i p, const bl_v4i* a, int* A) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t w = (uint32_t)p[d];
+            const uint32_t lv = s == 0 ? (w & 0x03030303u)
+                              : s == 1 ? (w & 0x0C0C0C0Cu)
+                              : s == 2 ? (w & 0x30303030u)
+                                       : ((w >> 2) & 0x30303030u);
+            A[s] = __builtin_amdgcn_sdot4((int)lv, a[s][d], A[s], false);
+        }
+    }
+}
+
+/* Per-token absmax int8 quantiser (Section 2) of a plain bf16 row by the whole workgroup, into
+ * LDS: Qs[K/4] the int8 row in natural order, misc[0] = sum_k q, misc[1] = rescale factor's token
+ * part (float bits).  Every workgroup that meets the product does this for itself: nothing
+ * crosses workgroups inside the launch (a hand-over through flags was measured and dropped:
+ * fresh data needs either an L2 write-back + invalidate per wave, +40 us per launch, or
+ * uncached loads of the row by every wave, +26 us).  Two passes over the row (the second
+ * hits the cache); `owner` also writes the caller's copies.  Ends with a barrier. */
+__device__ __forceinline__ void bl_stream_quant_bf16(const bl_stream_item& P, int* __restrict__ Qs,
+                                                     int* __restrict__ misc, bool owner) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int groups = P.nchunks * 4;
+    const bl_gv4i* x = (const bl_gv4i*)P.xbf16;
+    float* fs = (float*)(misc + 2);
+    int* ssum = misc + 6;
+    auto ld = [&](int i) {
+        const bl_v4i v = x[i];
+        return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+    };
+    float mx = 0.0f;
+    for (int u = tid; u < groups; u += 256)
+        mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(ld(2 * u)), bl_absmax8_bf16(ld(2 * u + 1))));
+    mx = bl_wave_max(mx);
+    if (lane == 0) fs[w] = mx;
+    __syncthreads();
+    const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
+    const float gg = fmaxf(gamma, 1e-5f);
+    const float inv = bl_div_rn(127.0f, gg);
+    int part = 0;
+    for (int u = tid; u < groups; u += 256) {
+        uint32_t a0, a1, a2, a3;
+        bl_quant8_words(ld(2 * u), inv, a0, a1);
+        bl_quant8_words(ld(2 * u + 1), inv, a2, a3);
+        part += bl_sum16(a0, a1, a2, a3);
+        const bl_v4i qv = {(int)a0, (int)a1, (int)a2, (int)a3};
+        if (owner && P.q_out) *(bl_gv4i*)(P.q_out + u * 16) = qv;
+        *(bl_v4i*)(Qs + u * 4) = qv;
+    }
+    part = bl_wave_sum(part);
+    if (lane == 0) ssum[w] = part;
+    __syncthreads();
+    if (tid == 0) {
+        const float sc = bl_div_rn(gg, 127.0f);
+        misc[1] = __float_as_int(P.fixed_scale > 0.0f ? P.fixed_scale : sc);
+        if (owner && P.scale_out) *(float BL_G*)P.scale_out = sc;
+        misc[0] = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+    }
+    __syncthreads();
+}
+
+/* Preparation: one workgroup per table entry that needs it.  Fused entries: producer, RMS
+ * normalisation (NORM), per-token absmax, int8 quantisation (Section 2) into the workspace,
+ * with the caller's optional copies; int8 entries without a row sum: the row sum. */
+template <bool NORM>
+__global__ __launch_bounds__(256) void bl_stream_prep(const bl_stream_prep_item* __restrict__ items) {
+    __shared__ float fs[4];
+    __shared__ int ssum[4];
+    __shared__ double s4[4];
+    const bl_stream_prep_item& it = items[blockIdx.x];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int K = it.K, groups = K / 16;
+    int part = 0;
+    if (it.fused) {
+        const bl_prod_dev pd = it.prod;
+        uint4 xv[4];
+        float rn = 1.0f;
+        bool have_xv = false;
+        if (NORM && pd.norm) {
+            rn = bl_norm_produce2(pd, 0, K, true, s4, xv);
+            have_xv = true;
+        }
+        float mx = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int u = tid + j * 256;
+            if (u < groups) {
+                if (!have_xv) bl_produce16<NORM>(pd, 0, u, K, true, rn, xv[2 * j], xv[2 * j + 1]);
+                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(xv[2 * j]), bl_absmax8_bf16(xv[2 * j + 1])));
+            }
+        }
+        for (int u = tid + 512; u < groups; u += 256) {
+            uint4 lo, hi;
+            bl_produce16<NORM>(pd, 0, u, K, false, rn, lo, hi);
+            mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(lo), bl_absmax8_bf16(hi)));
+        }
+        mx = bl_wave_max(mx);
+        if (lane == 0) fs[w] = mx;
+        __syncthreads();
+        const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
+        const float gg = fmaxf(gamma, 1e-5f);
+        const float inv = bl_div_rn(127.0f, gg);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int u = tid + j * 256;
+            if (u < groups) {
+                uint32_t a0, a1, a2, a3;
+                bl_quant8_words(xv[2 * j], inv, a0, a1);
+                bl_quant8_words(xv[2 * j + 1], inv, a2, a3);
+                part += bl_sum16(a0, a1, a2, a3);
+                if (it.q_out) *(uint4*)(it.q_out + u * 16) = make_uint4(a0, a1, a2, a3);
+                *(uint4*)(it.q_ws + u * 16) = make_uint4(a0, a1, a2, a3);
+            }
+        }
+        for (int u = tid + 512; u < groups; u += 256) {
+            uint32_t a0, a1, a2, a3;
+            uint4 lo, hi;
+            bl_produce16<NORM>(pd, 0, u, K, true, rn, lo, hi);
+            bl_quant8_words(lo, inv, a0, a1);
+            bl_quant8_words(hi, inv, a2, a3);
+            part += bl_sum16(a0, a1, a2, a3);
+            if (it.q_out) *(uint4*)(it.q_out + u * 16) = make_uint4(a0, a1, a2, a3);
+            *(uint4*)(it.q_ws + u * 16) = make_uint4(a0, a1, a2, a3);
+        }
+        if (tid == 0) {
+            const float sc = bl_div_rn(gg, 127.0f);
+            *it.scale_ws = it.fixed_scale > 0.0f ? it.fixed_scale : sc;
+            if (it.scale_out) *it.scale_out = sc;
+        }
+    } else {
+        for (int u = tid; u < groups; u += 256) {
+            const uint4 v = *(const uint4*)(it.q_in + (int64_t)u * 16);
+            part += bl_sum16(v.x, v.y, v.z, v.w);
+        }
+    }
+    part = bl_wave_sum(part);
+    if (lane == 0) ssum[w] = part;
+    __syncthreads();
+    if (tid == 0) *it.rowsum_ws = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+}
+
+/* One product slice [ub, ue) of row groups, for a product whose lanes hold LP 16-byte weight
+ * loads per row (k chunks g, g+G, .. of the row; G = 1 << lgG lanes per row, R = 64 / G rows
+ * per wave-wide load).  A "unit" is S consecutive row groups: S*LP loads per lane per register
+ * set.  The four waves of the workgroup take units round-robin.  Every load of the steady loop
+ * is unconditional (out-of-range lanes read a clamped, valid address and meet zeroed
+ * activation registers or are never stored), so the hardware counter waits are exact and the
+ * loads of unit i+1 stay in flight during the dot products of unit i.  No LDS, no barrier. */
+template <int LP, int S>
+__device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const int ub, const int ue, int* Qs,
+                                                int* misc, const bool restage) {
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = P.N, nchunks = P.nchunks, lgG = P.lgG;
+    const int R = 64 >> lgG;
+    const int r = lane >> lgG, g = lane & ((1 << lgG) - 1);
+    const int nunits = (ue - ub + S - 1) / S;            /* the last unit may be partial */
+    const bl_gv4i* const wbase = (const bl_gv4i*)P.packed;
+    int32_t BL_G* const acc_g = (int32_t BL_G*)P.acc;
+    float BL_G* const y_g = (float BL_G*)P.y;
+    const float BL_G* const res_g = (const float BL_G*)P.residual;
+    int coff[LP];                                        /* clamped k chunk of each load */
+#pragma unroll
+    for (int i = 0; i < LP; ++i) {
+        const int chunk = g + (i << lgG);
+        coff[i] = chunk < nchunks ? chunk : nchunks - 1;
+    }
+    /* the residual value of a row travels with the row's weights: a load issued later, in the
+     * epilogue, could only be waited for together with every weight load issued before it.  With
+     * no residual every lane reads beta instead (a valid address) and the value is not used. */
+    const float BL_G* const res_base = res_g ? res_g : (const float BL_G*)P.beta;
+    auto issue = [&](bl_v4i* p, float* rv, int unit) {
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            int n = (ub + unit * S + j) * R + r;
+            n = n < N ? n : N - 1;
+            const bl_gv4i* wrow = wbase + (int64_t)n * nchunks;
+#pragma unroll
+            for (int i = 0; i < LP; ++i) p[j * LP + i] = __builtin_nontemporal_load(wrow + coff[i]);
+            rv[j] = res_base[res_g ? n : 0];
+        }
+    };
+    bl_v4i pa[S * LP], pb[S * LP];
+    float ra[S], rb[S];
+    int u = w;                                           /* this wave's unit */
+    if (u < nunits) issue(pa, ra, u);                    /* in flight while the activations arrive */
+    if (P.xbf16) {                                       /* workgroup-uniform: barriers inside */
+        if (restage) __syncthreads();                    /* every wave is done with the previous image */
+        bl_stream_quant_bf16(P, Qs, misc, ub == 0);
+    }
+    if (u >= nunits) return;
+
+    /* this lane's activation dwords: chunk g + i*G as sixteen dwords a[s][d] = the bytes that pair
+     * with bit-pair level s of packed word d (layout 1: dword s of the 16-byte group d; layout 0:
+     * after a 4x4 byte transpose of the group); zero where the lane's load was clamped */
+    bl_v4i a[LP][4];
+    {
+        const bl_gv4i* qg = (const bl_gv4i*)P.q;
+#pragma unroll
+        for (int i = 0; i < LP; ++i) {
+            const bool live = g + (i << lgG) < nchunks;
+            bl_v4i grp[4];
+            if (P.xbf16) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) grp[d] = *(const bl_v4i*)(Qs + coff[i] * 16 + d * 4);
+            } else {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) grp[d] = qg[coff[i] * 4 + d];
+            }
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t t0 = (uint32_t)grp[d][0], t1 = (uint32_t)grp[d][1], t2 = (uint32_t)grp[d][2],
+                         t3 = (uint32_t)grp[d][3];
+                if (P.layout == 0) bl_transpose4x4(t0, t1, t2, t3);
+                a[i][0][d] = live ? (int)t0 : 0;
+                a[i][1][d] = live ? (int)t1 : 0;
+                a[i][2][d] = live ? (int)t2 : 0;
+                a[i][3][d] = live ? (int)t3 : 0;
+            }
+        }
+    }
+    int rs;
+    float cf = 0.0f;
+    if (P.xbf16) {
+        rs = misc[0];
+        if (y_g) cf = *(const float BL_G*)P.beta * __int_as_float(misc[1]);
+    } else {
+        rs = *(const int32_t BL_G*)P.rowsum;
+        if (y_g) cf = *(const float BL_G*)P.beta * *(const float BL_G*)P.scale;
+    }
+
+    auto finish = [&](const bl_v4i* p, const float* rv, int unit) {
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            int A[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < LP; ++i) bl_stream_dot(p[j * LP + i], a[i], A);
+            int v = A[0] + (A[1] >> 2) + ((A[2] + A[3]) >> 4);
+            v = bl_group_sum_rt(v, lgG);
+            const int rg = ub + unit * S + j;
+            const int n = rg * R + r;
+            if (g == 0 && rg < ue && n < N) {
+                const int val = v - rs;
+                if (acc_g) acc_g[n] = val;
+                if (y_g) {
+                    const float t = (float)val * cf;
+                    y_g[n] = res_g ? rv[j] + t : t;
+                }
+            }
+        }
+    };
+    /* two register sets alternate; the loop body always issues, the tails never do */
+    for (;;) {
+        if (u + 4 >= nunits) { finish(pa, ra, u); break; }
+        issue(pb, rb, u + 4);
+        finish(pa, ra, u);
+        u += 4;
+        if (u + 4 >= nunits) { finish(pb, rb, u); break; }
+        issue(pa, ra, u + 4);
+        finish(pb, rb, u);
+        u += 4;
+    }
+}
+
+/* Persistent grid: workgroup b walks the table slice wgstart[b] .. wgstart[b+1], each entry
+ * (product, row group).  Two register shapes cover every product: five loads per lane and row
+ * (one row group per register set), and up to four (two row groups per set; a product with
+ * fewer loads per row leaves slots idle: clamped loads that hit the cache, zeroed
+ * activations).  Two waves per SIMD: more variants or a higher occupancy target make the
+ * compiler spill, and a kernel that touches scratch memory loses a third of the stream rate
+ * (measured: 6.0 TB/s without, 3.9 - 5.1 with). */
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void bl_stream_m1(const bl_stream_item* __restrict__ items, const int2* __restrict__ wgstart, const int q_ints) {
+    extern __shared__ int lds[];                         /* q_ints ints of quantised row + 16 */
+    int* Qs = lds;
+    int* misc = lds + q_ints;
+    const int2 s0 = wgstart[blockIdx.x], s1 = wgstart[blockIdx.x + 1];
+    const int p_first = __builtin_amdgcn_readfirstlane(s0.x), u_first = __builtin_amdgcn_readfirstlane(s0.y);
+    const int p_last = __builtin_amdgcn_readfirstlane(s1.x), u_last = __builtin_amdgcn_readfirstlane(s1.y);
+    bool staged = false;
+    for (int pi = p_first; pi <= p_last; ++pi) {
+        if (pi == p_last && u_last == 0) break;          /* the slice ends exactly at a product boundary */
+        const bl_stream_item P = items[pi];
+        const int ub = pi == p_first ? u_first : 0;
+        const int ue = pi == p_last ? u_last : P.units;
+        if (ub >= ue) continue;
+        if (P.lp == 5) bl_stream_slice<5, 1>(P, ub, ue, Qs, misc, staged);
+        else bl_stream_slice<4, 2>(P, ub, ue, Qs, misc, staged);
+        staged = staged || P.xbf16 != nullptr;
+    }
+}
+
+/* ---- host side ---------------------------------------------------------------------------- */
+
+#define BL_STREAM_LMAX 5
+#define BL_STREAM_MAX_BLOCKS 4096
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+/* Device buffer layout: [items][slice table][preparation items][rowsum_ws][scale_ws][q_ws]. */
+struct bl_stream_layout {
+    size_t wg_off, prep_off, rowsum_off, scale_off, q_off, total;
+};
+static bl_stream_layout stream_layout(int count, size_t q_bytes) {
+    bl_stream_layout L;
+    L.wg_off = align_up((size_t)count * sizeof(bl_stream_item), 256);
+    L.prep_off = L.wg_off + align_up((size_t)(BL_STREAM_MAX_BLOCKS + 1) * sizeof(int2), 256);
+    L.rowsum_off = L.prep_off + align_up((size_t)count * sizeof(bl_stream_prep_item), 256);
+    L.scale_off = L.rowsum_off + align_up((size_t)count * 4, 256);
+    L.q_off = L.scale_off + align_up((size_t)count * 4, 256);
+    L.total = L.q_off + align_up(q_bytes, 256);
+    return L;
+}
+
+static bool desc_is_fused(const bl_decode_desc& d) { return d.X || d.prod.in0; }
+
+static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
+    if (!d.packed || !d.beta) return BL_ERR_NULL;
+    const bool fused = desc_is_fused(d);
+    if (!fused && !d.q) return BL_ERR_NULL;
+    if (!d.acc && !d.y) return BL_ERR_NULL;
+    if (!fused && d.y && !d.scale) return BL_ERR_NULL;
+    if (!bl_shape_ok(d.N, d.K) || d.K > 64 * 64 * BL_STREAM_LMAX || d.N > (1 << 28)) return BL_ERR_SHAPE;
+    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
+        !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||
+        !bl_aligned(d.rowsum, 4) || !bl_aligned(d.scale_out, 4) || !bl_aligned(d.residual, 4))
+        return BL_ERR_ALIGN;
+    return BL_OK;
+}
+
+extern "C" size_t bl_stack_table_bytes(const bl_decode_desc* descs, int count) {
+    if (!descs || count < 1 || count > BL_STACK_MAX_COUNT) return 0;
+    size_t q_bytes = 0;
+    for (int i = 0; i < count; ++i) {
+        if (descs[i].K < 64 || descs[i].K > 64 * 64 * BL_STREAM_LMAX) return 0;
+        if (desc_is_fused(descs[i])) q_bytes += align_up((size_t)descs[i].K, 256);
+    }
+    return stream_layout(count, q_bytes).total;
+}
+
+extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int layout, int64_t M, void* table,
+                                    bl_stack_plan* plan, bl_stream s) {
+    if (!descs || !table || !plan) return BL_ERR_NULL;
+    if (count < 1 || count > BL_STACK_MAX_COUNT || M != 1) return BL_ERR_SHAPE;
+    if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
+    size_t q_bytes = 0;
+    for (int i = 0; i < count; ++i) {
+        const bl_status st = check_stack_desc(descs[i], layout);
+        if (st != BL_OK) return st;
+        if (desc_is_fused(descs[i])) q_bytes += align_up((size_t)descs[i].K, 256);
+    }
+    const bl_stream_layout L = stream_layout(count, q_bytes);
+    uint8_t* const dev_base = (uint8_t*)table;
+    std::vector<bl_stream_item> items((size_t)count);
+    std::vector<bl_stream_prep_item> preps;
+    int max_inline_k = 0, inline_count = 0;
+    std::vector<int64_t> unit_bytes((size_t)count);
+    bool any_norm = false;
+    int64_t total = 0, packed_bytes = 0, total_units = 0;
+    size_t q_used = 0;
+    for (int i = 0; i < count; ++i) {
+        const bl_decode_desc& d = descs[i];
+        const bool fused = desc_is_fused(d);
+        bl_stream_item it;
+        memset(&it, 0, sizeof(it));
+        it.packed = (const bl_v4i*)d.packed;
+        it.beta = d.beta;
+        it.residual = d.residual;
+        it.acc = d.acc;
+        it.y = d.y;
+        it.N = (int)d.N;
+        it.nchunks = (int)(d.K / 64);
+        it.layout = layout;
+        int lgG = 3;
+        while (((it.nchunks + (1 << lgG) - 1) >> lgG) > BL_STREAM_LMAX) ++lgG;   /* K bound checked: lgG <= 6 */
+        const int R = 64 >> lgG;
+        it.lgG = lgG;
+        it.lp = (it.nchunks + (1 << lgG) - 1) >> lgG;
+        it.units = (it.N + R - 1) / R;
+        if (fused && d.prod.in0 == nullptr) {
+            /* a plain bf16 row: quantised inside the stream launch by each workgroup that meets it */
+            it.xbf16 = d.X;
+            it.q_out = d.q_out;
+            it.scale_out = d.scale_out;
+            it.fixed_scale = d.fixed_scale;
+            if ((int)d.K > max_inline_k) max_inline_k = (int)d.K;
+            ++inline_count;
+        } else if (fused || !d.rowsum) {
+            bl_stream_prep_item pp;
+            memset(&pp, 0, sizeof(pp));
+            pp.K = (int)d.K;
+            pp.rowsum_ws = (int32_t*)(dev_base + L.rowsum_off) + i;
+            it.rowsum = pp.rowsum_ws;
+            if (fused) {
+                pp.fused = 1;
+                if (!bl_make_prod(d.prod, d.X, d.K, &pp.prod)) return BL_ERR_VALUE;
+                any_norm = any_norm || pp.prod.norm;
+                pp.q_ws = (int8_t*)(dev_base + L.q_off + q_used);
+                q_used += align_up((size_t)d.K, 256);
+                pp.scale_ws = (float*)(dev_base + L.scale_off) + i;
+                pp.q_out = d.q_out;
+                pp.scale_out = d.scale_out;
+                pp.fixed_scale = d.fixed_scale;
+                it.q = pp.q_ws;
+                it.scale = pp.scale_ws;
+            } else {
+                pp.q_in = d.q;
+                it.q = d.q;
+                it.scale = d.scale;
+            }
+            preps.push_back(pp);
+        } else {
+            it.q = d.q;
+            it.scale = d.scale;
+            it.rowsum = d.rowsum;
+        }
+        unit_bytes[(size_t)i] = (int64_t)R * (d.K / 4);
+        total += (int64_t)it.units * unit_bytes[(size_t)i];
+        total_units += it.units;
+        packed_bytes += d.N * d.K / 4;
+        items[(size_t)i] = it;
+    }
+    /* persistent grid: the workgroups that are resident at once, but no more than one per four
+     * row groups' worth of work (a workgroup has four waves) */
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)bl_stream_m1, 256,
+                                                     (size_t)max_inline_k + 64) != hipSuccess ||
+        cus < 1 || per_cu < 1)
+        return BL_ERR_HIP;
+    int64_t blocks64 = (int64_t)cus * per_cu;
+    if (blocks64 > (total_units + 3) / 4) blocks64 = (total_units + 3) / 4;
+    if (blocks64 > BL_STREAM_MAX_BLOCKS) blocks64 = BL_STREAM_MAX_BLOCKS;
+    if (blocks64 < 1) blocks64 = 1;
+    const int blocks = (int)blocks64;
+
+    /* slice boundaries: workgroup b starts at byte b*total/blocks, rounded down to a row group */
+    std::vector<int2> wg((size_t)blocks + 1);
+    {
+        int pi = 0;
+        int64_t start = 0;                               /* first byte of product pi */
+        for (int b = 0; b < blocks; ++b) {
+            const int64_t c = total / blocks * b + total % blocks * b / blocks;
+            while (pi < count - 1 && c >= start + (int64_t)items[(size_t)pi].units * unit_bytes[(size_t)pi]) {
+                start += (int64_t)items[(size_t)pi].units * unit_bytes[(size_t)pi];
+                ++pi;
+            }
+            int64_t unit = (c - start) / unit_bytes[(size_t)pi];
+            if (unit > items[(size_t)pi].units) unit = items[(size_t)pi].units;
+            wg[(size_t)b] = make_int2(pi, (int)unit);
+        }
+        wg[(size_t)blocks] = make_int2(count - 1, items[(size_t)count - 1].units);
+    }
+    std::vector<uint8_t> blob(L.rowsum_off, 0);
+    memcpy(blob.data(), items.data(), items.size() * sizeof(bl_stream_item));
+    memcpy(blob.data() + L.wg_off, wg.data(), wg.size() * sizeof(int2));
+    if (!preps.empty()) memcpy(blob.data() + L.prep_off, preps.data(), preps.size() * sizeof(bl_stream_prep_item));
+    hipStream_t st = (hipStream_t)s;
+    if (hipMemcpyAsync(table, blob.data(), blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return BL_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return BL_ERR_HIP;   /* the host copy of the table dies here */
+
+    memset(plan, 0, sizeof(*plan));
+    plan->count = count;
+    plan->blocks = blocks;
+    plan->prep_count = (int32_t)preps.size();
+    plan->inline_count = inline_count;
+    plan->norm = any_norm ? 1 : 0;
+    plan->lds_bytes = max_inline_k + 64;
+    plan->wg_offset = (int64_t)L.wg_off;
+    plan->prep_offset = (int64_t)L.prep_off;
+    plan->packed_bytes = packed_bytes;
+    plan->table_bytes = (int64_t)L.total;
+    return BL_OK;
+}
+
+extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_stream s) {
+    if (!table || !plan) return BL_ERR_NULL;
+    if (plan->count < 1 || plan->count > BL_STACK_MAX_COUNT || plan->blocks < 1 ||
+        plan->blocks > BL_STREAM_MAX_BLOCKS || plan->prep_count < 0 || plan->inline_count < 0 ||
+        plan->prep_count + plan->inline_count > plan->count || plan->lds_bytes < 64 ||
+        plan->lds_bytes > 64 + 64 * 64 * BL_STREAM_LMAX || plan->lds_bytes % 64)
+        return BL_ERR_VALUE;
+    const bl_stream_layout L = stream_layout(plan->count, 0);
+    if (plan->wg_offset != (int64_t)L.wg_off || plan->prep_offset != (int64_t)L.prep_off) return BL_ERR_VALUE;
+    if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
+    uint8_t* base = (uint8_t*)table;
+    hipStream_t st = (hipStream_t)s;
+    if (plan->prep_count > 0) {
+        const bl_stream_prep_item* pp = (const bl_stream_prep_item*)(base + L.prep_off);
+        if (plan->norm) bl_stream_prep<true><<<plan->prep_count, 256, 0, st>>>(pp);
+        else bl_stream_prep<false><<<plan->prep_count, 256, 0, st>>>(pp);
+        if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
+    }
+    bl_stream_m1<<<plan->blocks, 256, (size_t)plan->lds_bytes, st>>>(
+        (const bl_stream_item*)base, (const int2*)(base + L.wg_off), (plan->lds_bytes - 64) / 4);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
