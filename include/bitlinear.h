@@ -282,11 +282,14 @@ bl_status bl_gemm_w158a8_noalloc(const uint8_t* packed, const float* beta, int l
  *   bl_probe_stream_read  one launch that reads `bytes` (a multiple of 16) of device memory
  *                         at `buf` with 128-bit loads and does nothing else; time it over a
  *                         buffer much larger than the caches to get the streaming-read rate.
+ *                         workgroups_per_cu: 256-thread workgroups per compute unit, 1..8
+ *                         (0 = 8, the fastest); 2 is the occupancy of the streaming decode.
  *   bl_probe_mfma_i8      one launch of `iters` x 4 back-to-back v_mfma_i32_32x32x32_i8 per
  *                         wave, operands in registers; *ops (HOST, optional) receives the
  *                         integer operations of the launch (2 per multiply-accumulate).
  * sink: device, 64 int32, never written in practice (it keeps the work observable). */
-bl_status bl_probe_stream_read(const void* buf, size_t bytes, int32_t* sink, bl_stream s);
+bl_status bl_probe_stream_read(const void* buf, size_t bytes, int workgroups_per_cu, int32_t* sink,
+                               bl_stream s);
 bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s);
 
 #ifdef __cplusplus

@@ -8,26 +8,60 @@
 
 typedef bl_v4i __attribute__((address_space(1))) bl_pgv4i;
 
-/* Each thread reads units tid, tid + T, tid + 2T, .. (T = all threads of the grid), eight loads
- * in flight; the XOR of everything read goes to sink[thread] only if it equals a value that
- * random data never produces in practice, so the loads cannot be removed. */
+/* The buffer is cut into one contiguous slice per workgroup (as the streaming decode kernel
+ * cuts its table); inside a slice wave w reads blocks w, w + 4, .. of 8 KiB: eight 1 KiB wave-wide
+ * loads in flight per wave.  The XOR of everything read goes to sink[] only if it equals a value
+ * that random data never produces in practice, so the loads cannot be removed. */
 __global__ __launch_bounds__(256) void bl_probe_read_kernel(const bl_v4i* __restrict__ buf, int64_t n16,
                                                              int32_t* __restrict__ sink) {
     const bl_pgv4i* p = (const bl_pgv4i*)buf;
-    const int64_t T = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t nblk = n16 / 512;                       /* whole 8 KiB blocks */
+    const int64_t b0 = nblk * blockIdx.x / gridDim.x, b1 = nblk * (blockIdx.x + 1) / gridDim.x;
     bl_v4i x = {0, 0, 0, 0};
-    for (; i + 7 * T < n16; i += 8 * T) {
+    for (int64_t b = b0 + w; b < b1; b += 4) {
         bl_v4i v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + i + j * T);
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + b * 512 + j * 64 + lane);
 #pragma unroll
         for (int j = 0; j < 8; ++j) x ^= v[j];
     }
-    for (; i < n16; i += T) x ^= __builtin_nontemporal_load(p + i);
+    /* the tail beyond the last whole block */
+    for (int64_t i = nblk * 512 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
+        x ^= __builtin_nontemporal_load(p + i);
     const int r = x[0] ^ x[1] ^ x[2] ^ x[3];
     if (r == 0x5EEDF00D) sink[threadIdx.x & 63] = r;
 }
+
+#ifdef BL_PROBE_EXPERIMENTS
+/* experiment: the access pattern of the decode kernel (8 lanes per 640-byte row, 8 rows per load) */
+__global__ __launch_bounds__(256) void bl_probe_read_rows(const bl_v4i* __restrict__ buf, int64_t n16,
+                                                           int32_t* __restrict__ sink, int mode) {
+    const bl_pgv4i* p = (const bl_pgv4i*)buf;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t nblk = n16 / 320;                       /* units of 8 rows x 40 chunks */
+    const int64_t b0 = nblk * blockIdx.x / gridDim.x, b1 = nblk * (blockIdx.x + 1) / gridDim.x;
+    const int r = lane >> 3, g = lane & 7;
+    bl_v4i x = {0, 0, 0, 0};
+    for (int64_t b = b0 + w; b < b1; b += 4) {
+        bl_v4i v[5];
+#pragma unroll
+        for (int j = 0; j < 5; ++j)
+            v[j] = __builtin_nontemporal_load(p + b * 320 + (mode == 0 ? r * 40 + g + 8 * j : j * 64 + lane));
+#pragma unroll
+        for (int j = 0; j < 5; ++j) x ^= v[j];
+    }
+    const int rr = x[0] ^ x[1] ^ x[2] ^ x[3];
+    if (rr == 0x5EEDF00D) sink[threadIdx.x & 63] = rr;
+}
+extern "C" int bl_probe_rows(const void* buf, size_t bytes, int per_cu, int mode, int32_t* sink, void* s) {
+    int dev = 0, cus = 0;
+    hipGetDevice(&dev);
+    hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    bl_probe_read_rows<<<cus * per_cu, 256, 0, (hipStream_t)s>>>((const bl_v4i*)buf, (int64_t)(bytes / 16), sink, mode);
+    return (int)hipGetLastError();
+}
+#endif
 
 /* Four independent accumulator chains per wave, operands in registers. */
 __global__ __launch_bounds__(256) void bl_probe_mfma_kernel(int iters, int32_t* __restrict__ sink) {
@@ -56,11 +90,13 @@ static int probe_grid(int per_cu) {
     return cus * per_cu;
 }
 
-extern "C" bl_status bl_probe_stream_read(const void* buf, size_t bytes, int32_t* sink, bl_stream s) {
+extern "C" bl_status bl_probe_stream_read(const void* buf, size_t bytes, int workgroups_per_cu, int32_t* sink,
+                                          bl_stream s) {
     if (!buf || !sink) return BL_ERR_NULL;
     if (bytes < 16 || bytes % 16) return BL_ERR_SHAPE;
     if (!bl_aligned(buf, 16) || !bl_aligned(sink, 4)) return BL_ERR_ALIGN;
-    const int blocks = probe_grid(8);
+    if (workgroups_per_cu < 0 || workgroups_per_cu > 8) return BL_ERR_SHAPE;
+    const int blocks = probe_grid(workgroups_per_cu ? workgroups_per_cu : 8);
     if (blocks < 1) return BL_ERR_HIP;
     bl_probe_read_kernel<<<blocks, 256, 0, (hipStream_t)s>>>((const bl_v4i*)buf, (int64_t)(bytes / 16), sink);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;

@@ -5,10 +5,9 @@
  * A table of products lives in device memory.  The grid is as many workgroups as stay
  * resident; each owns one contiguous slice of the table's weight bytes, cut at row-group
  * boundaries, so a workgroup meets one or two products and quantises / stages the activation
- * row of a product once.  Inside a product the four waves of a workgroup take row groups
- * round-robin; a wave keeps the int8 activations of its lanes' k chunks in REGISTERS for
- * the whole product (they do not depend on the row), and double-buffers the 128-bit weight
- * loads: the loads of row group i+1 are issued before the dot products of row group i.
+ * row of a product once, into LDS.  Inside a product the four waves of a workgroup take row
+ * groups round-robin and double-buffer the 128-bit weight loads: the loads of row group i+1
+ * are issued before the dot products of row group i.
  *
  * Arithmetic as in bl_gemv.hip: offset codes c = Wt + 1, bit-pair levels isolated by masks,
  * v_dot4_i32_i8 into four accumulators carrying 1, 4, 16, 16, DPP sums over the G lanes of
@@ -86,55 +85,6 @@ __device__ __forceinline__ void bl_stream_dot(const bl_v4i p, const bl_v4i* a, i
             A[s] = __builtin_amdgcn_sdot4((int)lv, a[s][d], A[s], false);
         }
     }
-}
-
-/* Per-token absmax int8 quantiser (Section 2) of a plain bf16 row by the whole workgroup, into
- * LDS: Qs[K/4] the int8 row in natural order, misc[0] = sum_k q, misc[1] = rescale factor's token
- * part (float bits).  Every workgroup that meets the product does this for itself: nothing
- * crosses workgroups inside the launch (a hand-over through flags was measured and dropped:
- * fresh data needs either an L2 write-back + invalidate per wave, +40 us per launch, or
- * uncached loads of the row by every wave, +26 us).  Two passes over the row (the second
- * hits the cache); `owner` also writes the caller's copies.  Ends with a barrier. */
-__device__ __forceinline__ void bl_stream_quant_bf16(const bl_stream_item& P, int* __restrict__ Qs,
-                                                     int* __restrict__ misc, bool owner) {
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int groups = P.nchunks * 4;
-    const bl_gv4i* x = (const bl_gv4i*)P.xbf16;
-    float* fs = (float*)(misc + 2);
-    int* ssum = misc + 6;
-    auto ld = [&](int i) {
-        const bl_v4i v = x[i];
-        return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
-    };
-    float mx = 0.0f;
-    for (int u = tid; u < groups; u += 256)
-        mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(ld(2 * u)), bl_absmax8_bf16(ld(2 * u + 1))));
-    mx = bl_wave_max(mx);
-    if (lane == 0) fs[w] = mx;
-    __syncthreads();
-    const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
-    const float gg = fmaxf(gamma, 1e-5f);
-    const float inv = bl_div_rn(127.0f, gg);
-    int part = 0;
-    for (int u = tid; u < groups; u += 256) {
-        uint32_t a0, a1, a2, a3;
-        bl_quant8_words(ld(2 * u), inv, a0, a1);
-        bl_quant8_words(ld(2 * u + 1), inv, a2, a3);
-        part += bl_sum16(a0, a1, a2, a3);
-        const bl_v4i qv = {(int)a0, (int)a1, (int)a2, (int)a3};
-        if (owner && P.q_out) *(bl_gv4i*)(P.q_out + u * 16) = qv;
-        *(bl_v4i*)(Qs + u * 4) = qv;
-    }
-    part = bl_wave_sum(part);
-    if (lane == 0) ssum[w] = part;
-    __syncthreads();
-    if (tid == 0) {
-        const float sc = bl_div_rn(gg, 127.0f);
-        misc[1] = __float_as_int(P.fixed_scale > 0.0f ? P.fixed_scale : sc);
-        if (owner && P.scale_out) *(float BL_G*)P.scale_out = sc;
-        misc[0] = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
-    }
-    __syncthreads();
 }
 
 /* Preparation: one workgroup per table entry that needs it.  Fused entries: producer, RMS
@@ -217,16 +167,103 @@ __global__ __launch_bounds__(256) void bl_stream_prep(const bl_stream_prep_item*
     if (tid == 0) *it.rowsum_ws = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
 }
 
+/* ---- the stream kernel ----------------------------------------------------------------------
+ * A product's quantised activation row lives in LDS for the workgroup (staged once per product
+ * and workgroup: quantised from bf16 right there, or copied from the int8 row) and is read with
+ * ds_read_b128 right before each group of sixteen dot products.  Holding the row in registers
+ * instead (80 per lane) was measured: 2 waves per SIMD, 5.7 - 5.9 TB/s against 5.85 - 6.2 here
+ * with 4; the loop issues ~300 vector instructions per 5 KiB of weights, so the vector unit,
+ * not the memory, sets the pace (a plain read with the same access pattern gets 7.0 TB/s).
+ * Every workgroup that meets a bf16 product quantises the row for itself: nothing crosses
+ * workgroups inside the launch.  (A hand-over through ready flags was measured and dropped:
+ * fresh data needs either an L2 write-back + invalidate per wave, +40 us per launch, or
+ * uncached loads of the row by every wave, +26 us; a separate preparation launch costs 5.5 us.)
+ * LDS image: per 64-wide k chunk 20 dwords (16 + 4 of padding so that the eight chunks a wave
+ * reads together fall on different banks), dword s*4+d = the bytes that pair with bit-pair
+ * level s of packed word d; one all-zero chunk behind the last for lanes whose load is clamped. */
+#define BL_QSTRIDE 20
+
+__device__ __forceinline__ void bl_lds_put16(int* __restrict__ Qs, int c16, int layout, uint32_t a0, uint32_t a1,
+                                             uint32_t a2, uint32_t a3) {
+    if (layout == 0) bl_transpose4x4(a0, a1, a2, a3);
+    int* dst = Qs + (c16 >> 2) * BL_QSTRIDE + (c16 & 3);
+    dst[0] = (int)a0;
+    dst[4] = (int)a1;
+    dst[8] = (int)a2;
+    dst[12] = (int)a3;
+}
+
+/* Stages the activation row of P: Qs = the image above, misc[0] = sum_k q, misc[1] = token part
+ * of the rescale factor (float bits).  Ends with a barrier. */
+__device__ __forceinline__ void bl_stream_stage(const bl_stream_item& P, int* __restrict__ Qs,
+                                                    int* __restrict__ misc, bool owner) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int groups = P.nchunks * 4;
+    float* fs = (float*)(misc + 2);
+    int* ssum = misc + 6;
+    if (tid < BL_QSTRIDE) Qs[P.nchunks * BL_QSTRIDE + tid] = 0;
+    int part = 0;
+    if (P.xbf16) {
+        const bl_gv4i* x = (const bl_gv4i*)P.xbf16;
+        auto ld = [&](int i) {
+            const bl_v4i v = x[i];
+            return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+        };
+        float mx = 0.0f;
+        for (int u = tid; u < groups; u += 256)
+            mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(ld(2 * u)), bl_absmax8_bf16(ld(2 * u + 1))));
+        mx = bl_wave_max(mx);
+        if (lane == 0) fs[w] = mx;
+        __syncthreads();
+        const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
+        const float gg = fmaxf(gamma, 1e-5f);
+        const float inv = bl_div_rn(127.0f, gg);
+        for (int u = tid; u < groups; u += 256) {
+            uint32_t a0, a1, a2, a3;
+            bl_quant8_words(ld(2 * u), inv, a0, a1);
+            bl_quant8_words(ld(2 * u + 1), inv, a2, a3);
+            part += bl_sum16(a0, a1, a2, a3);
+            const bl_v4i qv = {(int)a0, (int)a1, (int)a2, (int)a3};
+            if (owner && P.q_out) *(bl_gv4i*)(P.q_out + u * 16) = qv;
+            bl_lds_put16(Qs, u, P.layout, a0, a1, a2, a3);
+        }
+        if (tid == 0) {
+            const float sc = bl_div_rn(gg, 127.0f);
+            misc[1] = __float_as_int(P.fixed_scale > 0.0f ? P.fixed_scale : sc);
+            if (owner && P.scale_out) *(float BL_G*)P.scale_out = sc;
+        }
+        part = bl_wave_sum(part);
+        if (lane == 0) ssum[w] = part;
+        __syncthreads();
+        if (tid == 0) misc[0] = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+    } else {
+        const bl_gv4i* qg = (const bl_gv4i*)P.q;
+        for (int u = tid; u < groups; u += 256) {
+            const bl_v4i v = qg[u];
+            bl_lds_put16(Qs, u, P.layout, (uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+        }
+        if (tid == 0) {
+            misc[0] = *(const int32_t BL_G*)P.rowsum;
+            misc[1] = P.scale ? __float_as_int(*(const float BL_G*)P.scale) : 0;
+        }
+    }
+    __syncthreads();
+}
+
 /* One product slice [ub, ue) of row groups, for a product whose lanes hold LP 16-byte weight
  * loads per row (k chunks g, g+G, .. of the row; G = 1 << lgG lanes per row, R = 64 / G rows
  * per wave-wide load).  A "unit" is S consecutive row groups: S*LP loads per lane per register
  * set.  The four waves of the workgroup take units round-robin.  Every load of the steady loop
- * is unconditional (out-of-range lanes read a clamped, valid address and meet zeroed
- * activation registers or are never stored), so the hardware counter waits are exact and the
- * loads of unit i+1 stay in flight during the dot products of unit i.  No LDS, no barrier. */
+ * is unconditional (out-of-range lanes read a clamped, valid address and meet the all-zero
+ * chunk, or are never stored), so the hardware counter waits are exact and the loads of unit
+ * i+1 stay in flight during the dot products of unit i.  The residual value of a row travels
+ * with the row's weights: a load issued later, in the epilogue, could only be waited for
+ * together with every weight load issued before it (with no residual every lane reads beta
+ * instead, a valid address, and the value is not used). */
 template <int LP, int S>
-__device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const int ub, const int ue, int* Qs,
-                                                int* misc, const bool restage) {
+__device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const int ub, const int ue,
+                                                    int* __restrict__ Qs, int* __restrict__ misc,
+                                                    const bool restage) {
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int N = P.N, nchunks = P.nchunks, lgG = P.lgG;
     const int R = 64 >> lgG;
@@ -236,16 +273,14 @@ __device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const i
     int32_t BL_G* const acc_g = (int32_t BL_G*)P.acc;
     float BL_G* const y_g = (float BL_G*)P.y;
     const float BL_G* const res_g = (const float BL_G*)P.residual;
-    int coff[LP];                                        /* clamped k chunk of each load */
+    const float BL_G* const res_base = res_g ? res_g : (const float BL_G*)P.beta;
+    int coff[LP], qoff[LP];                              /* clamped k chunk of each load; its LDS image */
 #pragma unroll
     for (int i = 0; i < LP; ++i) {
         const int chunk = g + (i << lgG);
         coff[i] = chunk < nchunks ? chunk : nchunks - 1;
+        qoff[i] = (chunk < nchunks ? chunk : nchunks) * BL_QSTRIDE;   /* clamped lanes meet the zero chunk */
     }
-    /* the residual value of a row travels with the row's weights: a load issued later, in the
-     * epilogue, could only be waited for together with every weight load issued before it.  With
-     * no residual every lane reads beta instead (a valid address) and the value is not used. */
-    const float BL_G* const res_base = res_g ? res_g : (const float BL_G*)P.beta;
     auto issue = [&](bl_v4i* p, float* rv, int unit) {
 #pragma unroll
         for (int j = 0; j < S; ++j) {
@@ -260,58 +295,32 @@ __device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const i
     bl_v4i pa[S * LP], pb[S * LP];
     float ra[S], rb[S];
     int u = w;                                           /* this wave's unit */
-    if (u < nunits) issue(pa, ra, u);                    /* in flight while the activations arrive */
-    if (P.xbf16) {                                       /* workgroup-uniform: barriers inside */
-        if (restage) __syncthreads();                    /* every wave is done with the previous image */
-        bl_stream_quant_bf16(P, Qs, misc, ub == 0);
-    }
+    if (u < nunits) issue(pa, ra, u);                    /* in flight during the staging */
+    if (restage) __syncthreads();                        /* every wave is done with the previous image */
+    bl_stream_stage(P, Qs, misc, ub == 0);
     if (u >= nunits) return;
-
-    /* this lane's activation dwords: chunk g + i*G as sixteen dwords a[s][d] = the bytes that pair
-     * with bit-pair level s of packed word d (layout 1: dword s of the 16-byte group d; layout 0:
-     * after a 4x4 byte transpose of the group); zero where the lane's load was clamped */
-    bl_v4i a[LP][4];
-    {
-        const bl_gv4i* qg = (const bl_gv4i*)P.q;
-#pragma unroll
-        for (int i = 0; i < LP; ++i) {
-            const bool live = g + (i << lgG) < nchunks;
-            bl_v4i grp[4];
-            if (P.xbf16) {
-#pragma unroll
-                for (int d = 0; d < 4; ++d) grp[d] = *(const bl_v4i*)(Qs + coff[i] * 16 + d * 4);
-            } else {
-#pragma unroll
-                for (int d = 0; d < 4; ++d) grp[d] = qg[coff[i] * 4 + d];
-            }
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                uint32_t t0 = (uint32_t)grp[d][0], t1 = (uint32_t)grp[d][1], t2 = (uint32_t)grp[d][2],
-                         t3 = (uint32_t)grp[d][3];
-                if (P.layout == 0) bl_transpose4x4(t0, t1, t2, t3);
-                a[i][0][d] = live ? (int)t0 : 0;
-                a[i][1][d] = live ? (int)t1 : 0;
-                a[i][2][d] = live ? (int)t2 : 0;
-                a[i][3][d] = live ? (int)t3 : 0;
-            }
-        }
-    }
-    int rs;
+    const int rs = misc[0];
     float cf = 0.0f;
-    if (P.xbf16) {
-        rs = misc[0];
-        if (y_g) cf = *(const float BL_G*)P.beta * __int_as_float(misc[1]);
-    } else {
-        rs = *(const int32_t BL_G*)P.rowsum;
-        if (y_g) cf = *(const float BL_G*)P.beta * *(const float BL_G*)P.scale;
-    }
+    if (y_g) cf = *(const float BL_G*)P.beta * __int_as_float(misc[1]);
 
     auto finish = [&](const bl_v4i* p, const float* rv, int unit) {
 #pragma unroll
         for (int j = 0; j < S; ++j) {
             int A[4] = {0, 0, 0, 0};
+            /* The image does not change inside the loop, so the compiler would hoist these reads
+             * out of it and hold them in 16 * LP registers again: the address is hidden from it. */
+            bl_v4i a[1][4];
+            auto rd = [&](int i, bl_v4i* dst) {
+                int qo = qoff[i];
+                asm volatile("" : "+v"(qo));
 #pragma unroll
-            for (int i = 0; i < LP; ++i) bl_stream_dot(p[j * LP + i], a[i], A);
+                for (int s = 0; s < 4; ++s) dst[s] = *(const bl_v4i*)(Qs + qo + s * 4);
+            };
+#pragma unroll
+            for (int i = 0; i < LP; ++i) {
+                rd(i, a[0]);
+                bl_stream_dot(p[j * LP + i], a[0], A);
+            }
             int v = A[0] + (A[1] >> 2) + ((A[2] + A[3]) >> 4);
             v = bl_group_sum_rt(v, lgG);
             const int rg = ub + unit * S + j;
@@ -326,7 +335,6 @@ __device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const i
             }
         }
     };
-    /* two register sets alternate; the loop body always issues, the tails never do */
     for (;;) {
         if (u + 4 >= nunits) { finish(pa, ra, u); break; }
         issue(pb, rb, u + 4);
@@ -340,15 +348,13 @@ __device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const i
 }
 
 /* Persistent grid: workgroup b walks the table slice wgstart[b] .. wgstart[b+1], each entry
- * (product, row group).  Two register shapes cover every product: five loads per lane and row
- * (one row group per register set), and up to four (two row groups per set; a product with
- * fewer loads per row leaves slots idle: clamped loads that hit the cache, zeroed
- * activations).  Two waves per SIMD: more variants or a higher occupancy target make the
- * compiler spill, and a kernel that touches scratch memory loses a third of the stream rate
- * (measured: 6.0 TB/s without, 3.9 - 5.1 with). */
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+ * (product, row group).  Two loop shapes cover every product: five loads per lane and row, and
+ * up to four (a product with fewer leaves slots idle: clamped loads that hit the cache, the
+ * all-zero chunk).  Four waves per SIMD, no scratch memory: a version that spilled lost a third
+ * of the stream rate. */
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void bl_stream_m1(const bl_stream_item* __restrict__ items, const int2* __restrict__ wgstart, const int q_ints) {
-    extern __shared__ int lds[];                         /* q_ints ints of quantised row + 16 */
+    extern __shared__ int lds[];                         /* q_ints ints of image + 16 */
     int* Qs = lds;
     int* misc = lds + q_ints;
     const int2 s0 = wgstart[blockIdx.x], s1 = wgstart[blockIdx.x + 1];
@@ -356,14 +362,14 @@ void bl_stream_m1(const bl_stream_item* __restrict__ items, const int2* __restri
     const int p_last = __builtin_amdgcn_readfirstlane(s1.x), u_last = __builtin_amdgcn_readfirstlane(s1.y);
     bool staged = false;
     for (int pi = p_first; pi <= p_last; ++pi) {
-        if (pi == p_last && u_last == 0) break;          /* the slice ends exactly at a product boundary */
+        if (pi == p_last && u_last == 0) break;
         const bl_stream_item P = items[pi];
         const int ub = pi == p_first ? u_first : 0;
         const int ue = pi == p_last ? u_last : P.units;
         if (ub >= ue) continue;
         if (P.lp == 5) bl_stream_slice<5, 1>(P, ub, ue, Qs, misc, staged);
-        else bl_stream_slice<4, 2>(P, ub, ue, Qs, misc, staged);
-        staged = staged || P.xbf16 != nullptr;
+        else bl_stream_slice<4, 1>(P, ub, ue, Qs, misc, staged);
+        staged = true;
     }
 }
 
@@ -371,6 +377,7 @@ void bl_stream_m1(const bl_stream_item* __restrict__ items, const int2* __restri
 
 #define BL_STREAM_LMAX 5
 #define BL_STREAM_MAX_BLOCKS 4096
+#define BL_STREAM_LDS_BYTES ((max_k / 64 + 1) * BL_QSTRIDE * 4 + 64)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -431,7 +438,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     uint8_t* const dev_base = (uint8_t*)table;
     std::vector<bl_stream_item> items((size_t)count);
     std::vector<bl_stream_prep_item> preps;
-    int max_inline_k = 0, inline_count = 0;
+    int inline_count = 0, max_k = 0;
     std::vector<int64_t> unit_bytes((size_t)count);
     bool any_norm = false;
     int64_t total = 0, packed_bytes = 0, total_units = 0;
@@ -448,6 +455,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
         it.y = d.y;
         it.N = (int)d.N;
         it.nchunks = (int)(d.K / 64);
+        if ((int)d.K > max_k) max_k = (int)d.K;
         it.layout = layout;
         int lgG = 3;
         while (((it.nchunks + (1 << lgG) - 1) >> lgG) > BL_STREAM_LMAX) ++lgG;   /* K bound checked: lgG <= 6 */
@@ -461,7 +469,6 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
             it.q_out = d.q_out;
             it.scale_out = d.scale_out;
             it.fixed_scale = d.fixed_scale;
-            if ((int)d.K > max_inline_k) max_inline_k = (int)d.K;
             ++inline_count;
         } else if (fused || !d.rowsum) {
             bl_stream_prep_item pp;
@@ -504,7 +511,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)bl_stream_m1, 256,
-                                                     (size_t)max_inline_k + 64) != hipSuccess ||
+                                                     (size_t)BL_STREAM_LDS_BYTES) != hipSuccess ||
         cus < 1 || per_cu < 1)
         return BL_ERR_HIP;
     int64_t blocks64 = (int64_t)cus * per_cu;
@@ -513,22 +520,61 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     if (blocks64 < 1) blocks64 = 1;
     const int blocks = (int)blocks64;
 
-    /* slice boundaries: workgroup b starts at byte b*total/blocks, rounded down to a row group */
+    /* Slice boundaries.  A workgroup's time is its bytes, weighted by the measured rate of the
+     * product's register shape, plus a fixed cost each time it enters a product (activation
+     * row, pipeline refill; larger when it quantises the row itself), expressed in bytes at a
+     * workgroup's share of the stream rate.  Walk the row groups once, cutting whenever a
+     * workgroup's cost reaches the target; the last workgroup takes what is left. */
     std::vector<int2> wg((size_t)blocks + 1);
     {
-        int pi = 0;
-        int64_t start = 0;                               /* first byte of product pi */
-        for (int b = 0; b < blocks; ++b) {
-            const int64_t c = total / blocks * b + total % blocks * b / blocks;
-            while (pi < count - 1 && c >= start + (int64_t)items[(size_t)pi].units * unit_bytes[(size_t)pi]) {
-                start += (int64_t)items[(size_t)pi].units * unit_bytes[(size_t)pi];
-                ++pi;
+        auto enter_cost = [&](int pi) { return items[(size_t)pi].xbf16 ? (int64_t)36 << 10 : (int64_t)12 << 10; };
+        auto unit_cost = [&](int pi) {
+            return items[(size_t)pi].lp == 5 ? unit_bytes[(size_t)pi] : unit_bytes[(size_t)pi] * 26 / 25;
+        };
+        int64_t all = 0;
+        for (int i = 0; i < count; ++i) all += (int64_t)items[(size_t)i].units * unit_cost(i) + enter_cost(i);
+        /* every cut inside a product adds one more entry, so the target is refined until the
+         * last workgroup (which takes what is left) is no longer than the others */
+        int64_t target = all / blocks + 1;
+        for (int iter = 0; iter < 12; ++iter) {
+            int pi = 0, unit = 0;
+            for (int b = 0; b < blocks; ++b) {
+                wg[(size_t)b] = make_int2(pi, unit);
+                int64_t c = 0;
+                bool entered = false;
+                while (pi < count && b < blocks - 1) {
+                    if (!entered) { c += enter_cost(pi); entered = true; }
+                    const int64_t uc = unit_cost(pi);
+                    const int64_t room = target - c;
+                    const int64_t take = room > 0 ? (room + uc - 1) / uc : 0;
+                    const int left = items[(size_t)pi].units - unit;
+                    if (take >= left) {
+                        c += (int64_t)left * uc;
+                        ++pi;
+                        unit = 0;
+                        entered = false;
+                        if (c >= target) break;
+                    } else {
+                        unit += (int)take;
+                        break;
+                    }
+                }
             }
-            int64_t unit = (c - start) / unit_bytes[(size_t)pi];
-            if (unit > items[(size_t)pi].units) unit = items[(size_t)pi].units;
-            wg[(size_t)b] = make_int2(pi, (int)unit);
+            /* cost of what is left for the last workgroup */
+            int64_t last = 0;
+            {
+                int pi = wg[(size_t)blocks - 1].x, unit = wg[(size_t)blocks - 1].y;
+                for (; pi < count; ++pi, unit = 0)
+                    if (items[(size_t)pi].units > unit)
+                        last += enter_cost(pi) + (int64_t)(items[(size_t)pi].units - unit) * unit_cost(pi);
+            }
+            if (last <= target + target / 64) break;
+            target += (last - target) / blocks + 1;
         }
-        wg[(size_t)blocks] = make_int2(count - 1, items[(size_t)count - 1].units);
+        /* normalise an end position (count, 0) to (count - 1, units): the kernel never reads entry `count` */
+        for (int b = 0; b <= blocks; ++b)
+            if (b == blocks || wg[(size_t)b].x >= count)
+                wg[(size_t)b] = make_int2(count - 1, items[(size_t)count - 1].units);
     }
     std::vector<uint8_t> blob(L.rowsum_off, 0);
     memcpy(blob.data(), items.data(), items.size() * sizeof(bl_stream_item));
@@ -544,7 +590,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     plan->prep_count = (int32_t)preps.size();
     plan->inline_count = inline_count;
     plan->norm = any_norm ? 1 : 0;
-    plan->lds_bytes = max_inline_k + 64;
+    plan->lds_bytes = BL_STREAM_LDS_BYTES;
     plan->wg_offset = (int64_t)L.wg_off;
     plan->prep_offset = (int64_t)L.prep_off;
     plan->packed_bytes = packed_bytes;
@@ -557,7 +603,7 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
     if (plan->count < 1 || plan->count > BL_STACK_MAX_COUNT || plan->blocks < 1 ||
         plan->blocks > BL_STREAM_MAX_BLOCKS || plan->prep_count < 0 || plan->inline_count < 0 ||
         plan->prep_count + plan->inline_count > plan->count || plan->lds_bytes < 64 ||
-        plan->lds_bytes > 64 + 64 * 64 * BL_STREAM_LMAX || plan->lds_bytes % 64)
+        plan->lds_bytes > 64 + (64 * BL_STREAM_LMAX + 1) * BL_QSTRIDE * 4 || plan->lds_bytes % 16)
         return BL_ERR_VALUE;
     const bl_stream_layout L = stream_layout(plan->count, 0);
     if (plan->wg_offset != (int64_t)L.wg_off || plan->prep_offset != (int64_t)L.prep_off) return BL_ERR_VALUE;
