@@ -2,18 +2,21 @@
 """Benchmark of the BitLinear W1.58A8 hot path on one MI355X.
 
 Headline workload (config 1 of the benchmark spec): decode at M=1 over the four
-BitLinear shapes of one 2B-style layer.  A "step" is one pass of the hot path
-over one layer: for each shape, per-token absmax int8 quantisation of the bf16
-activations, then the packed-ternary product with int32 accumulation and fp32
-rescale.  Steps rotate over 30 distinct layers (521 MB of packed weights, more
-than L2 + Infinity Cache) so every step streams its weights from HBM.  The
-launches are replayed from a HIP graph; inputs are resident in HBM.
+BitLinear shapes of a 2B-style layer, for 30 distinct layers (521 MB of packed
+weights, more than L2 + Infinity Cache, so everything streams from HBM).  A
+"step" is one pass of the hot path over those 30 layers = 120 BitLinears: for
+each, per-token absmax int8 quantisation of its bf16 activations, the
+packed-ternary product with int32 accumulation, and the fp32 rescale - all in
+ONE launch of the persistent streaming kernel (bl_stack_run).  Launches are
+replayed from a HIP graph; inputs are resident in HBM.
 
     value = packed weight bytes per step / time per step   [GB/s]
 
-Also reported in the same JSON line: the roofline of the decode kernel, the
-prefill product (config 3: M=2048, int8 matrix-core TOPS) and the CPU oracle
-timed on the host cores (baseline only).
+Also reported in the same JSON line: the same work as one launch per layer
+(the previous headline), the measured achievable roofs (plain streaming read,
+register-resident int8 MFMA loop), the prefill product (config 3: M=2048, int8
+matrix-core TOPS), batched decode (config 2), the chained stack (config 4) and
+the CPU oracle timed on the host cores (baseline only).
 """
 import argparse
 import json
@@ -27,17 +30,27 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
-# HBM bytes per launch, read + written, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
-# this same command (profiles/bench_decode_m1_prefill_m2048.md; counters scaled by what they read for
-# a plain 256 MiB copy: fetch x2.0, write x1.0).  Decode: the one grouped launch of a layer
-# (17.82 MB + 0.09 MB).  Prefill: the four launches of a layer at M = 2048 (135.2 MB + 186.7 MB).
-DECODE_TRAFFIC_BYTES = 17.91e6
-PREFILL_TRAFFIC_BYTES = 321.8e6
 SHAPE_ORDER = ["qkv", "o", "gate_up", "down"]
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def profiled_traffic(key):
+    """HBM bytes per launch (read + written) of a kernel/workload, from the rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE summary committed in profiles/hbm_traffic.txt (lines
+    `key read_bytes write_bytes`, counters already scaled by the plain-copy calibration).
+    None if the file or the key is missing: the bench line then says so instead of guessing."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == key:
+                return float(f[1]) + float(f[2])
+    except OSError:
+        pass
+    return None
 
 
 class Layer:
@@ -184,12 +197,43 @@ def main():
     buf = make_decode_buffers(bl, torch, synth, M, dev)
     side = torch.cuda.Stream()
     K_steps, W_steps = args.steps, args.warmup
+    stack_bytes = nl * layer_bytes
+    sink = torch.zeros(64, dtype=torch.int32, device=dev)
     with torch.cuda.stream(side):
         st = torch.cuda.current_stream().cuda_stream
         for l in range(min(nl, 4)):
             decode_step(lib, st, layers[l], buf, layout)
         torch.cuda.synchronize()
 
+        # headline: the 120 BitLinears of the 30 layers in one streamed launch, quantiser inside
+        items = []
+        ys = []
+        for L in layers:
+            for n in SHAPE_ORDER:
+                y = torch.empty((1, buf[n].N), dtype=torch.float32, device=dev)
+                ys.append(y)
+                items.append(dict(packed=L.packed[n], beta=L.beta[n], N=buf[n].N, K=buf[n].K, X=buf[n].X, y=y))
+        stack = bl.Stack(items, layout, 1, dev)
+        assert stack.plan.packed_bytes == stack_bytes and stack.plan.prep_count == 0
+        stack.run()
+        torch.cuda.synchronize()
+        per_graph = 10
+        g_stack = capture(torch, lambda: [stack.run() for _ in range(per_graph)])
+        plan = [(g_stack, per_graph, K_steps // per_graph)] if K_steps >= per_graph else []
+        if K_steps % per_graph:
+            g_rem = capture(torch, lambda: [stack.run() for _ in range(K_steps % per_graph)])
+            plan.append((g_rem, K_steps % per_graph, 1))
+        for _ in range(max(1, W_steps // per_graph)):
+            g_stack.replay()
+        torch.cuda.synchronize()
+        t_gpu, t_wall = time_graph_steps(torch, plan, K_steps)
+        ms_per_step = t_gpu * 1e3 / K_steps
+        value = stack_bytes / (t_gpu / K_steps) / 1e9
+        # the timed region consists of launches of the streaming kernel only (the quantiser runs
+        # inside it), so the same HIP-event interval gives that kernel's average launch duration
+        stream_avg_s = t_gpu / K_steps
+
+        # the same work as one launch per layer (bl_bitlinear_decode_group: four shapes, fused quantiser)
         descs = make_group_descs(bl, layers, buf)
 
         def run_steps(first, count, mode="group"):
@@ -206,95 +250,83 @@ def main():
                 else:                        # products only, activations already quantised
                     decode_step(lib, s, L, buf, layout, False)
 
-        g_full = capture(torch, lambda: run_steps(0, nl))
-        plan = [(g_full, nl, K_steps // nl)]
-        if K_steps % nl:
-            g_rem = capture(torch, lambda: run_steps(0, K_steps % nl))
-            plan.append((g_rem, K_steps % nl, 1))
-        for _ in range(max(1, W_steps // nl)):
-            g_full.replay()
-        torch.cuda.synchronize()
-        t_gpu, t_wall = time_graph_steps(torch, plan, K_steps)
-        ms_per_step = t_gpu * 1e3 / K_steps
-        value = layer_bytes / (t_gpu / K_steps) / 1e9
-        # the timed region consists of launches of the decode kernel only, so the
-        # same HIP-event interval gives that kernel's average launch duration
-        achieved = value
-        bytes_per_launch = float(layer_bytes)
-        gemv_avg_s = t_gpu / K_steps
-
-        reps = max(1, min(K_steps // nl, 20))
+        reps = max(1, min(K_steps, 20))
         alt = {}
-        for mode, launches in (("fused", 4), ("calls", 8), ("gemv_only", 4)):
+        for mode, launches in (("group", 1), ("fused", 4), ("calls", 8), ("gemv_only", 4)):
             g = capture(torch, lambda: run_steps(0, nl, mode))
             for _ in range(2):
                 g.replay()
             t_alt, _ = time_graph_steps(torch, [(g, nl, reps)], nl * reps)
-            alt[mode] = {"us_per_step": round(t_alt / (nl * reps) * 1e6, 3), "launches_per_step": launches,
+            alt[mode] = {"us_per_layer": round(t_alt / (nl * reps) * 1e6, 3), "launches_per_layer": launches,
                          "GBps": round(layer_bytes / (t_alt / (nl * reps)) / 1e9, 1)}
-        # independent steps on several streams inside one graph (each branch has its own output
-        # buffers): consecutive launches overlap, which hides the launch gap and the tail of each
-        # kernel.  Not the headline: a real decode chain is dependent (config 4).
-        for nb in (2, 4):
-            bufs_b = [buf] + [make_decode_buffers(bl, torch, synth, M, dev) for _ in range(nb - 1)]
-            descs_b = [descs] + [make_group_descs(bl, layers, b) for b in bufs_b[1:]]
-            branches = [torch.cuda.Stream() for _ in range(nb)]
-
-            def run_overlapped():
-                cur = torch.cuda.current_stream()
-                for b in range(nb):
-                    branches[b].wait_stream(cur)
-                    with torch.cuda.stream(branches[b]):
-                        sb = torch.cuda.current_stream().cuda_stream
-                        for i in range(b, nl, nb):
-                            rc = lib.bl_bitlinear_decode_group(descs_b[b][i], 4, layout, M, sb)
-                            assert rc == 0, rc
-                for b in range(nb):
-                    cur.wait_stream(branches[b])
-            run_overlapped()
-            torch.cuda.synchronize()
-            g = capture(torch, run_overlapped)
-            for _ in range(2):
-                g.replay()
-            t_alt, _ = time_graph_steps(torch, [(g, nl, reps)], nl * reps)
-            alt["overlap_%d_streams" % nb] = {"us_per_step": round(t_alt / (nl * reps) * 1e6, 3), "launches_per_step": 1,
+        one_layer_s = alt["group"]["us_per_layer"] * 1e-6
+        # the streaming kernel on one layer per launch and on one very large product
+        st1 = [bl.Stack(items[4 * l:4 * l + 4], layout, 1, dev) for l in range(nl)]
+        g = capture(torch, lambda: [s_.run() for s_ in st1])
+        g.replay()
+        t_alt, _ = time_graph_steps(torch, [(g, nl, reps)], nl * reps)
+        alt["stream_one_layer_per_launch"] = {"us_per_layer": round(t_alt / (nl * reps) * 1e6, 3), "launches_per_layer": 1,
                                               "GBps": round(layer_bytes / (t_alt / (nl * reps)) / 1e9, 1)}
-            del bufs_b, descs_b
-        # steady state of the same kernel: one product with a very large N (all 30 gate_up
-        # matrices stacked would be this shape), 265 MB streamed per launch
+        del st1
         big_n = 30 * 13824
         big = torch.randint(0, 256, (big_n * 2560 // 4,), dtype=torch.uint8, device=dev)
         yb = torch.empty((1, big_n), dtype=torch.float32, device=dev)
-        bg = buf["gate_up"]
-
-        def run_big():
-            rc = lib.bl_bitlinear_decode(big.data_ptr(), layers[0].beta["gate_up"].data_ptr(), layout,
-                                         bg.X.data_ptr(), 1, big_n, 2560, None, yb.data_ptr(), None, None,
-                                         torch.cuda.current_stream().cuda_stream)
-            assert rc == 0, rc
-        g = capture(torch, run_big)
+        stb = bl.Stack([dict(packed=big, beta=layers[0].beta["gate_up"], N=big_n, K=2560, X=buf["gate_up"].X, y=yb)],
+                       layout, 1, dev)
+        g = capture(torch, stb.run)
         g.replay()
         t_big, _ = time_graph_steps(torch, [(g, 1, 10)], 10)
-        alt["large_n"] = {"shape": "N=%d K=2560 M=1, one launch" % big_n, "us": round(t_big / 10 * 1e6, 2),
+        alt["large_n"] = {"shape": "N=%d K=2560 M=1, one streamed launch" % big_n, "us": round(t_big / 10 * 1e6, 2),
                           "GBps": round(big_n * 2560 / 4 / (t_big / 10) / 1e9, 1)}
-        del big, yb
-    log("[bench] decode (one grouped fused launch per layer): %.3f us/step, %.1f GB/s; alternatives %s"
-        % (ms_per_step * 1e3, value, alt))
+        del big, yb, stb
+
+        # achievable roof: a plain 128-bit streaming read (same slicing, no arithmetic) of 2 GiB, and
+        # of as many bytes as one step streams, at the stream kernel's occupancy and at the best one
+        probe = torch.randint(0, 256, (2 << 30,), dtype=torch.uint8, device=dev)
+
+        def probe_rate(nbytes, per_cu):
+            def fn():
+                rc = lib.bl_probe_stream_read(probe.data_ptr(), nbytes, per_cu, sink.data_ptr(),
+                                              torch.cuda.current_stream().cuda_stream)
+                assert rc == 0, rc
+            fn()
+            g_ = capture(torch, fn)
+            g_.replay()
+            t_, _ = time_graph_steps(torch, [(g_, 1, 10)], 10)
+            return nbytes / (t_ / 10) / 1e9
+        read_roof = {"bytes_2GiB_8wg_per_cu": round(probe_rate(2 << 30, 8), 1),
+                     "bytes_2GiB_4wg_per_cu": round(probe_rate(2 << 30, 4), 1),
+                     "bytes_of_one_step_4wg_per_cu": round(probe_rate(stack_bytes, 4), 1)}
+        del probe
+        achievable = max(read_roof.values())
+    log("[bench] decode M=1, 120 BitLinears per streamed launch: %.2f us/step, %.1f GB/s (%.3f of %.0f); "
+        "one launch per layer: %s; read roof %s"
+        % (ms_per_step * 1e3, value, value / HBM_PEAK_GBS, HBM_PEAK_GBS, alt, read_roof))
 
     out = {
         "metric": "W1.58A8 GEMV HBM GB/s at M=1 (decode) + int8 TOPS at M=2048 (prefill)",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "config 1: decode M=1, one 2B-style layer per step (qkv 3840x2560, o 2560x2560, "
-                               "gate_up 13824x2560, down 2560x6912), quantise+product+rescale of all four shapes per step, "
-                               "rotating over %d distinct layers" % nl,
-                   "packed_bytes_per_step": layer_bytes, "layout": layout, "launch": "hip graph; one bl_bitlinear_decode_group launch per step "
-                                                      "(four shapes, absmax int8 quantiser fused)"},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": DECODE_TRAFFIC_BYTES,
-                     "kernel": "bl_gemv_rows", "bytes_per_launch": bytes_per_launch,
-                     "avg_launch_us": round(gemv_avg_s * 1e6, 3)},
+        "config": {"workload": "config 1: decode M=1 over the four BitLinear shapes of a 2B-style layer (qkv 3840x2560, "
+                               "o 2560x2560, gate_up 13824x2560, down 2560x6912), %d distinct layers = %d BitLinears per "
+                               "step, quantise+product+rescale of every one" % (nl, 4 * nl),
+                   "packed_bytes_per_step": stack_bytes, "layout": layout,
+                   "launch": "hip graph; one bl_stack_run launch per step (persistent streaming kernel over a device "
+                             "table of %d products, absmax int8 quantiser inside the launch)" % (4 * nl)},
+        "roofline": {"bound": "hbm", "achieved": round(value, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": profiled_traffic("bl_stream_m1:30_layers"),
+                     "kernel": "bl_stream_m1", "bytes_per_launch": float(stack_bytes),
+                     "avg_launch_us": round(stream_avg_s * 1e6, 3),
+                     "achievable": achievable, "frac_of_achievable": round(value / achievable, 4),
+                     "achievable_detail": read_roof},
+        "roofline_one_layer_per_launch": {
+            "bound": "hbm", "achieved": round(layer_bytes / one_layer_s / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(layer_bytes / one_layer_s / 1e9 / HBM_PEAK_GBS, 4),
+            "traffic": profiled_traffic("bl_gemv_rows:one_layer"), "kernel": "bl_gemv_rows",
+            "bytes_per_launch": float(layer_bytes), "avg_launch_us": round(one_layer_s * 1e6, 3),
+            "note": "the same 120 BitLinears as 30 launches of bl_bitlinear_decode_group (17.4 MB each): launch and "
+                    "ramp bound, a plain read of 17.4 MB takes about 7 us"},
         "decode_alternatives": alt,
     }
 
@@ -355,14 +387,28 @@ def main():
             torch.cuda.synchronize()
             dt = e0.elapsed_time(e1) * 1e-3 / nl
             per_shape[name] = {"us": round(dt * 1e6, 2), "tops": round(2.0 * Mp * b.N * b.K / dt / 1e12, 1)}
-        log("[bench] prefill M=%d: %.1f us/layer, %.1f TOPS; %s" % (Mp, t_pre * 1e6, tops, per_shape))
+        # achievable roof of the matrix cores: a register-resident loop of the same MFMA instruction
+        import ctypes
+        mops = ctypes.c_double(0)
+        rc = lib.bl_probe_mfma_i8(20000, sink.data_ptr(), ctypes.byref(mops), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            lib.bl_probe_mfma_i8(20000, sink.data_ptr(), None, torch.cuda.current_stream().cuda_stream)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_roof = mops.value / (e0.elapsed_time(e1) * 1e-3 / 3) / 1e12
+        log("[bench] prefill M=%d: %.1f us/layer, %.1f TOPS (MFMA-only loop: %.0f); %s"
+            % (Mp, t_pre * 1e6, tops, mfma_roof, per_shape))
         out["prefill"] = {"workload": "config 3: M=%d, four layer shapes, int8 q + per-row scales -> fp32 y" % Mp,
                           "tops": round(tops, 2), "unit": "TOP/s", "us_per_layer": round(t_pre * 1e6, 2),
                           "per_shape": per_shape,
                           "roofline": {"bound": "mfma", "achieved": round(tops, 2), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
-                                       "traffic": PREFILL_TRAFFIC_BYTES if Mp == 2048 else None,
-                                       "kernel": "bl_gemm_tile256"}}
+                                       "traffic": profiled_traffic("bl_gemm_tile256:layer_m2048") if Mp == 2048 else None,
+                                       "kernel": "bl_gemm_tile256", "achievable": round(mfma_roof, 1),
+                                       "frac_of_achievable": round(tops / mfma_roof, 4)}}
 
     # ------------------------------------------- config 2: batched decode, M in {8, 32, 64}
     if not args.no_batched:
@@ -513,6 +559,9 @@ def main():
         torch.cuda.synchronize()
         yd = buf["down"].y.cpu().numpy()
         assert np.allclose(yd, r["y"], rtol=1e-6, atol=0), "GPU result differs from the oracle"
+        stack.run()                      # and the streamed launch: layer 0, down projection
+        torch.cuda.synchronize()
+        assert np.allclose(ys[3].cpu().numpy(), r["y"], rtol=1e-6, atol=0), "streamed result differs from the oracle"
         out["cpu_baseline"] = {"value": round(layer_bytes / dt / 1e9, 3), "unit": "GB/s",
                                "cores": oracle.omp_threads(), "kind": "oracle",
                                "sample": "layer 0 of the same workload (4 shapes, M=1, quantise+product+rescale), "
