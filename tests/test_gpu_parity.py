@@ -209,8 +209,9 @@ def test_long_rows_beyond_the_decode_kernels(bl, M):
 
 
 @pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
-@pytest.mark.parametrize("M", [1, 4])
+@pytest.mark.parametrize("M", [1, 4, 8, 32, 64])
 def test_gemv_layer_shapes(bl, name, M):
+    """Configs 1 and 2: every layer shape as a single product at M = 1, 4, 8, 32 and 64."""
     N, K = synth.LAYER_SHAPES[name]
     c = Case(0, M, N, K, layer=0, matrix=name, relu2=(name == "down"))
     for layout in (0, 1):
@@ -340,7 +341,7 @@ def test_fused_decode_zero_and_tiny_rows(bl):
 
 
 @pytest.mark.parametrize("M,fused", [(1, False), (1, True), (2, False), (2, True), (4, False), (4, True), (8, False), (8, True),
-                                     (8, "mixed"), (24, False), (40, False), (64, False)])
+                                     (8, "mixed"), (24, False), (32, False), (40, False), (64, False)])
 def test_grouped_decode_whole_layer(bl, M, fused):
     """The four shapes of one layer in ONE launch equal four oracle products."""
     cases, items, keep = [], [], []
@@ -378,9 +379,11 @@ def test_grouped_decode_residual_epilogue(bl, M):
               y=torch.empty((M, c.N), dtype=torch.float32, device="cuda:0"))
     bl.bl_bitlinear_decode_group(bl.make_decode_descs([it]), 1, M)
     _sync()
-    want = res + c.y           # one fp32 add per element, as the kernels do
+    # y = residual + t, t = float(acc)*(beta*scale): t is the same two fp32 multiplies on both
+    # sides, so the one fp32 add is compared bit for bit
+    want = res + c.y
     got = it["y"].cpu().numpy()
-    assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.abs(c.y) + 1.2e-7 * np.abs(want))
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
 @pytest.mark.parametrize("M", [6, 24, 56])
@@ -405,8 +408,7 @@ def test_grouped_decode_two_products_one_with_residual(bl, M):
     assert np.array_equal(items[1]["acc"].cpu().numpy(), cb.acc)
     assert_y_close(items[0]["y"].cpu().numpy(), ca.y)
     want = res + cb.y
-    got = items[1]["y"].cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(got - want) <= 1e-6 * np.abs(cb.y) + 1.2e-7 * np.abs(want))
+    assert np.array_equal(items[1]["y"].cpu().numpy().view(np.uint32), want.view(np.uint32))
 
 
 @pytest.mark.parametrize("seed", list(range(12)))
@@ -445,7 +447,7 @@ def test_grouped_decode_seeded_shape_mix(bl, seed):
             assert_y_close(got, c.y)
         else:
             want = res + c.y
-            assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.abs(c.y) + 1.2e-7 * np.abs(want))
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
 def test_fused_fixed_scale(bl):
