@@ -38,7 +38,8 @@
  * enqueued on the caller's stream `s` (a hipStream_t passed as void*; NULL is
  * the null stream) and no call synchronises.  Argument errors are found on the
  * host before any HIP call and reported as a status code (no exceptions, no
- * global error state).  Preconditions on every matrix: N >= 4, N % 4 == 0,
+ * global error state; the only process-wide state is the test hook below).  Preconditions on
+ * every matrix: N >= 4, N % 4 == 0,
  * K >= 64, K % 64 == 0; `packed` and `q` 16-byte aligned; otherwise
  * BL_ERR_SHAPE / BL_ERR_ALIGN.  Non-finite activations or weights: undefined.
  * There is no bias argument (the report removes all biases, Section 2).
@@ -68,8 +69,7 @@ typedef void* bl_stream;   /* hipStream_t */
 
 enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_K16 = 1 };
 enum { BL_IN_FP32_LATENT = 0, BL_IN_INT8_TERNARY = 1 };
-enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3,
-       BL_OP_FUSED_DECODE = 4, BL_OP_FFN_GLUE = 5 };
+enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3 };
 
 /* Library version (major*10000 + minor*100 + patch) and a static string
  * naming a status code.  Host-only, no GPU needed. */
@@ -119,7 +119,10 @@ bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K,
  *   rowsum device int32 [M] or NULL (this call derives what it needs from q).
  *   acc    device out int32 [M][N] or NULL;  y device out fp32 [M][N] or NULL;
  *          at least one of the two must be non-NULL.
- *   workspace unused by the current kernels (may be NULL). */
+ *   workspace needed only when K > 8192 and rowsum is NULL (such rows go through the
+ *          prefill kernel, which then computes the row sums there:
+ *          bl_workspace_bytes(BL_OP_GEMV, M, N, K) bytes; BL_ERR_WORKSPACE if NULL);
+ *          otherwise unused and may be NULL. */
 bl_status bl_gemv_w158a8(const uint8_t* packed, const float* beta, int layout,
                          const int8_t* q, const float* scale, const int32_t* rowsum,
                          int64_t M, int64_t N, int64_t K,
@@ -276,6 +279,13 @@ bl_status bl_gemm_w158a8_noalloc(const uint8_t* packed, const float* beta, int l
                                  const int8_t* q, const float* scale,
                                  int64_t M, int64_t N, int64_t K,
                                  int32_t* acc, float* y, bl_stream s);
+
+/* Test hook: which decode kernel the M <= 64 entry points take, so that tests can put every
+ * kernel through every case.  0 = the measured default, 1 = the dot4 kernel where it applies
+ * (M <= 4), 2 = the row-resident matrix-core kernel, 3 = the streaming panel kernel where it
+ * applies (int8 inputs).  Process-wide and atomic; results never depend on it, only the route.
+ * BL_ERR_VALUE outside 0..3. */
+bl_status bl_debug_force_path(int path);
 
 /* Measurement aids (not part of the product path): the achievable roofs the kernels are
  * priced against beside the datasheet peaks.

@@ -34,6 +34,7 @@ SIGNATURES = {
     "bl_stack_table_bytes": (_sz, [_vp, _ci]),
     "bl_stack_build": (_ci, [_vp, _ci, _ci, _i64, _vp, _vp, _vp]),
     "bl_stack_run": (_ci, [_vp, _vp, _vp]),
+    "bl_debug_force_path": (_ci, [_ci]),
     "bl_probe_stream_read": (_ci, [_vp, _sz, _ci, _vp, _vp]),
     "bl_probe_mfma_i8": (_ci, [_ci, _vp, _vp, _vp]),
     "bl_gemm_w158a8_noalloc": (_ci, [_vp, _vp, _ci, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),

@@ -1,6 +1,8 @@
 /* Host-only entry points of the BitLinear library: sizes, names, version. */
 #include "bl_host.h"
 
+#include <atomic>
+
 extern "C" int bl_version(void) { return 100; }
 
 extern "C" const char* bl_status_str(int status) {
@@ -32,4 +34,12 @@ extern "C" size_t bl_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
         case BL_OP_GEMM: return M > 0 ? (size_t)((M * 4 + 255) / 256 * 256) : 0;
         default: return 0;
     }
+}
+
+static std::atomic<int> g_forced_decode_path{0};
+int bl_forced_decode_path(void) { return g_forced_decode_path.load(std::memory_order_relaxed); }
+extern "C" bl_status bl_debug_force_path(int path) {
+    if (path < 0 || path > 3) return BL_ERR_VALUE;
+    g_forced_decode_path.store(path, std::memory_order_relaxed);
+    return BL_OK;
 }

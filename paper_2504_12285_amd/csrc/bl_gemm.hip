@@ -9,8 +9,6 @@
 #include "bl_device.h"
 #include "bl_host.h"
 
-#include <stdlib.h>
-
 #include <atomic>
 
 #define GEMM_THREADS 256
@@ -187,13 +185,14 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
     auto k1 = bl_gemm_mfma<BM, BN, BK, WGM, 1>;
     auto kern = layout == 0 ? k0 : k1;
     if (lds > 64 * 1024) {
-        static bool set0 = false, set1 = false;
-        bool& done = layout == 0 ? set0 : set1;
-        if (!done) {
+        /* (two threads may both set the attribute: the call is idempotent) */
+        static std::atomic<bool> set[2];
+        std::atomic<bool>& done = set[layout == 0 ? 0 : 1];
+        if (!done.load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
                 hipSuccess)
                 return BL_ERR_HIP;
-            done = true;
+            done.store(true, std::memory_order_release);
         }
     }
     kern<<<grid, GEMM_THREADS, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, residual, acc, y);
@@ -443,11 +442,11 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     constexpr int G3_BM = BM;
     constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4);
     auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set;
+    if (!attr_set.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return BL_ERR_HIP;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + BN - 1) / BN;
     /* rows of activations per XCD region: at most ~1.5 MB of int8 (measured, medians of six
@@ -455,37 +454,11 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
      * equal on the others) */
     int gm = 1;
     while (gm < 8 && (int64_t)((tiles_m + gm - 1) / gm) * BM * K > (3 << 19)) gm *= 2;
-    const char* eg = getenv("BL_GEMM_GM");
-    if (eg && *eg) { const int v = atoi(eg); if (v == 1 || v == 2 || v == 4 || v == 8) gm = v; }
     const int gn = 8 / gm;
     const int blocks = 8 * ((tiles_m + gm - 1) / gm) * ((tiles_n + gn - 1) / gn);
     kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, residual,
                                             acc, y);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
-}
-
-/* variant: 0 / 1 / 2 = 256x256 with 2x2 / 2x4 / 4x2 waves and three stages, 3 = 256x128 2x2 waves
- * with two stages, 4 / 5 = 128x128 2x2 waves with two / three stages (three / two workgroups
- * per CU), 6 = 64x256 1x4 waves with three stages (a tile wider in N than in M moves fewer
- * bytes per operation, packed weights costing a quarter of a byte; measured equal to 128x128
- * at M = 2048), 7 = 64x128 1x4 waves with two stages (twice the workgroups: for problems with
- * few tiles) */
-static bl_status launch_tile256(int variant, const uint8_t* packed, const float* beta, const int8_t* q,
-                                const float* scale, const int32_t* rowsum, int M, int N, int K,
-                                const float* residual, int32_t* acc, float* y, hipStream_t st) {
-#define BL_TILE(BMv, BNv, ST, WMv, WNv) \
-    launch_tile256_t<BMv, BNv, ST, WMv, WNv>(packed, beta, q, scale, rowsum, M, N, K, residual, acc, y, st)
-    switch (variant) {
-        case 1: return BL_TILE(256, 256, 3, 2, 4);
-        case 2: return BL_TILE(256, 256, 3, 4, 2);
-        case 3: return BL_TILE(256, 128, 2, 2, 2);
-        case 4: return BL_TILE(128, 128, 2, 2, 2);
-        case 5: return BL_TILE(128, 128, 3, 2, 2);
-        case 6: return BL_TILE(64, 256, 3, 1, 4);
-        case 7: return BL_TILE(64, 128, 2, 1, 4);
-        default: return BL_TILE(256, 256, 3, 2, 2);
-    }
-#undef BL_TILE
 }
 
 /* rowsum[m] = sum_k q[m][k]; one wave per row. */
@@ -518,33 +491,24 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
         bl_rowsum_kernel<<<(unsigned)((M + 3) / 4), 256, 0, st>>>(q, (int)M, (int)K, rs);
         rowsum = rs;
     }
-    /* Tile choice.  Measured on MI355X at M = 2048 on the four 2B-layer shapes:
-     * 128x128 tiles, k step 128, two LDS stages filled by direct global->LDS
-     * loads, XCD-aware tile order, three workgroups per CU (tile id 10): about
-     * 1450 TOPS over the layer against 1310 for the register-staged 128x128
-     * kernel and ~950 for 256x256 tiles.  Deeper pipelines (4 or 6 stages) that
-     * cost occupancy measured slower: what hides the load latency is the number of
-     * workgroups per CU, not the depth (forcing four per CU instead of three is no
-     * gain either).  The 64x256 tile (id 12) is equal within run-to-run noise.  When
-     * the problem has at most ~1.5 tiles of 128x128 per CU, 64x128 tiles (id 13) balance
-     * better: +17..21 % on the N = 2560 shapes at M = 2048 (1220 / 1690 against 1010 /
-     * 1450 TOPS), +22..27 % on every small shape at M = 1024, equal at 480 tiles and
-     * slower on the wide shape.  All need layout 1 and K % 128 == 0; other inputs use the
-     * register-staged kernel, which permutes the activation bytes for layout 0.
-     * BL_GEMM_TILE overrides for experiments:
-     * 0 = 128x128x64 staged, 5 = 128x128x128 staged, 6/7/8 = 256x256 with 2x2 /
-     * 2x4 / 4x2 waves, 9 = 256x128, 10 / 11 = 128x128 direct with 2 / 3 stages, 12 = 64x256,
-     * 13 = 64x128. */
-    const char* e = getenv("BL_GEMM_TILE");
+    /* Tile choice.  Measured on MI355X at M = 2048 on the four 2B-layer shapes: 128x128 tiles,
+     * k step 128, two LDS stages filled by direct global->LDS loads, XCD-aware tile order, three
+     * workgroups per CU: about 1450 TOPS over the layer against 1310 for the register-staged
+     * 128x128 kernel.  Also measured and dropped (no longer in the library): 256x256 tiles with
+     * 2x2 / 2x4 / 4x2 waves and 256x128 (0.9 - 1.1 POP/s), a three-stage 128x128 and 4- or 6-stage
+     * pipelines (what hides the load latency is the number of workgroups per CU, not the depth),
+     * 64x256 (equal within noise).  When the problem has at most ~1.5 tiles of 128x128 per CU,
+     * 64x128 tiles balance better: +17..21 % on the N = 2560 shapes at M = 2048, +22..27 % on every
+     * small shape at M = 1024, equal at 480 tiles and slower on the wide shape.  Both need layout 1
+     * and K % 128 == 0; other inputs use the register-staged kernel, which permutes the activation
+     * bytes for layout 0. */
     const int m = (int)M, n = (int)N, k = (int)K;
-    int tile = e && *e ? atoi(e) : -1;
-    const bool direct_ok = layout == 1 && k % G3_BK == 0;
-    if (tile < 0) tile = direct_ok ? ((int64_t)((m + 127) / 128) * ((n + 127) / 128) <= 400 ? 13 : 10) : (k % 128 == 0) ? 5 : 0;
-    if (tile >= 6 && tile <= 13 && !direct_ok) tile = (k % 128 == 0) ? 5 : 0;
-    if (tile == 5 && k % 128) tile = 0;
-    if (tile >= 6 && tile <= 13)
-        return launch_tile256(tile - 6, packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
-    if (tile == 5)
+    if (layout == 1 && k % G3_BK == 0) {
+        if ((int64_t)((m + 127) / 128) * ((n + 127) / 128) <= 400)
+            return launch_tile256_t<64, 128, 2, 1, 4>(packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
+        return launch_tile256_t<128, 128, 2, 2, 2>(packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
+    }
+    if (k % 128 == 0)
         return launch_gemm<128, 128, 128, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
     return launch_gemm<128, 128, 64, 2>(packed, beta, layout, q, scale, rowsum, m, n, k, residual, acc, y, st);
 }

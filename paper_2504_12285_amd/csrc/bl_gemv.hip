@@ -11,24 +11,12 @@
  * shifts.  Partial sums are reduced across lanes with DPP row operations and
  * across the waves of a workgroup through LDS.
  */
-#include <stdlib.h>
+#include <atomic>
 
 #include "bl_device.h"
 #include "bl_gemv_common.h"
 #include "bl_host.h"
 #include "bl_producer.h"
-
-#ifdef BL_TRACE   /* development aid: per-workgroup time stamps (100 MHz clock) */
-__device__ unsigned long long* bl_trace_ptr;
-extern "C" int bl_trace_set(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(bl_trace_ptr), &p, sizeof(p)); }
-#define BL_STAMP_DECL unsigned long long bl_ts[6] = {0, 0, 0, 0, 0, 0}
-#define BL_STAMP(i) bl_ts[i] = wall_clock64()
-#define BL_STAMP_FLUSH do { if (threadIdx.x == 0 && bl_trace_ptr) for (int i_ = 0; i_ < 6; ++i_) bl_trace_ptr[blockIdx.x * 8 + i_] = bl_ts[i_]; } while (0)
-#else
-#define BL_STAMP_DECL
-#define BL_STAMP(i)
-#define BL_STAMP_FLUSH
-#endif
 
 /* LDS image of the activations.  For token m and 64-wide k chunk c, sixteen
  * dwords indexed [s][d]: the bytes that pair with bit-pair level s of packed
@@ -81,8 +69,6 @@ template <int M, int G, int L, bool NORM>
 __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
     extern __shared__ int lds[];
     constexpr int R = 64 / G;
-    BL_STAMP_DECL;
-    BL_STAMP(0);
     const bl_gemv_prob P = bl_fetch_prob(grp);
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -127,7 +113,6 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
         p[i] = bl_v4i{0, 0, 0, 0};
         if (row_ok && chunk < nchunks) p[i] = __builtin_nontemporal_load(wrow + chunk);
     }
-    BL_STAMP(1);
 
     int* Q = lds;                       /* M*K/4 dwords                      */
     int* sq = Q + M * (K / 4);          /* M row sums                        */
@@ -214,7 +199,6 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
         }
         __syncthreads();
     }
-    BL_STAMP(2);
 
     int A[M][4];
 #pragma unroll
@@ -228,7 +212,6 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
                 bl_dot_chunk(p[i], (const bl_v4i*)(Q + (m * nchunks + chunk) * 16), A[m]);
         }
     }
-    BL_STAMP(3);
     int v[M];
 #pragma unroll
     for (int m = 0; m < M; ++m)
@@ -253,7 +236,6 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
 #pragma unroll
         for (int m = 0; m < M; ++m) o[m] = __shfl(v[m], (lane & (R - 1)) * G);
     }
-    BL_STAMP(4);
     const int n_out = ((int)blockIdx.x - P.block0) * rows_per_block + rg * R + lane;
     if (kp == 0 && lane < R && n_out < N) {
 #pragma unroll
@@ -266,8 +248,6 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
             }
         }
     }
-    BL_STAMP(5);
-    BL_STAMP_FLUSH;
 }
 
 #define BL_MMA_PAD 16    /* bytes added to each staged activation row (LDS bank spread) */
@@ -293,8 +273,6 @@ __global__ __launch_bounds__(256) void bl_gemv_rows(const bl_gemv_group grp) {
 template <int L, int MT, bool NEED_SUM, bool NORM>
 __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, const int M, const int LF, const int budget) {
     extern __shared__ int lds[];
-    BL_STAMP_DECL;
-    BL_STAMP(0);
     const bl_gemv_prob P = bl_fetch_prob(grp);
     const int N = P.N, K = P.K, nchunks = K / 64, ksplit = P.ksplit;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -406,8 +384,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             stage_phase(rot_ph + 1 < nph ? rot_ph + 1 : 0, 1);   /* nph >= 2 in phased mode */
         }
     }
-
-    BL_STAMP(1);
     /* 3. fused path: produce, quantise and stage every token.  Without normalisation a token
      * is one wave's work (absmax by a wave reduction, no workgroup barrier per token): the four
      * waves run four tokens side by side.  A lane keeps its first two groups in registers
@@ -626,7 +602,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             }
             __syncthreads();
         }
-        BL_STAMP(2);
 #pragma unroll
         for (int i = 0; i < L; ++i)
             if (i < L / 2 || (i * ksplit + kp) * 256 < K) step(p[i], i, Q, 0, false);
@@ -644,7 +619,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                 frs[tid] = rs_in;
             }
             __syncthreads();
-            if (ph == 0) BL_STAMP(2);
 #pragma unroll
             for (int i = 0; i < L; ++i) {
                 const int kfirst = (i * ksplit + kp) * 256;   /* wave-uniform: first k of this step */
@@ -660,7 +634,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
     }
     bl_v4i D[MT];
     bl_mfma_fence();
-    BL_STAMP(3);
 #pragma unroll
     for (int t = 0; t < MT; ++t) D[t] = (C[t][0] + C[t][1]) + (C[t][2] + C[t][3]) - (Cs[t][0] + Cs[t][1]);
 
@@ -675,7 +648,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
                 for (int t = 0; t < MT; ++t) D[t] += *(const bl_v4i*)(red + ((t * 4 + w + j) * 64 + lane) * 4);
         }
     }
-    BL_STAMP(4);
     if (kp == 0 && row_ok) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
@@ -696,13 +668,6 @@ __global__ __launch_bounds__(256) void bl_gemv_mma(const bl_gemv_group grp, cons
             }
         }
     }
-    BL_STAMP(5);
-    BL_STAMP_FLUSH;
-}
-
-static int bl_env_int(const char* name, int dflt) {
-    const char* e = getenv(name);
-    return e && *e ? atoi(e) : dflt;
 }
 
 template <int M, int G, int L, bool NORM>
@@ -728,7 +693,7 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStre
      * own, else small enough for two workgroups per CU.  int8 inputs that do not fit whole
      * are staged 1024 << LF columns at a time in two buffers; a phase is at most 64
      * (token, 1024-column) pieces: the kernel's 16 loads per wave. */
-    const int budget = bl_env_int("BL_GEMV_LDS", 150) * 1024;
+    const int budget = 150 * 1024;
     int LF = 0;
     while ((M << (LF + 1)) <= 64 && 2 * (size_t)M * ((1024 << (LF + 1)) + BL_MMA_PAD) <= (size_t)budget) ++LF;
     bool have_sums = true;   /* every product brings its own row sums */
@@ -746,12 +711,13 @@ static bl_status launch_mma(const bl_gemv_group& grp, int M, int blocks, hipStre
                      : (have_sums ? bl_gemv_mma<L, MT, false, false> : bl_gemv_mma<L, MT, true, false>);
     if (lds > 160 * 1024) return BL_ERR_SHAPE;
     if (lds > 64 * 1024) {
-        static bool done[2] = {false, false};
-        if (!done[have_sums]) {
+        /* (two threads may both set the attribute: the call is idempotent) */
+        static std::atomic<bool> done[2];
+        if (!done[have_sums].load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) !=
                 hipSuccess)
                 return BL_ERR_HIP;
-            done[have_sums] = true;
+            done[have_sums].store(true, std::memory_order_release);
         }
     }
     kern<<<blocks, 256, lds, st>>>(grp, M, LF, budget);
@@ -773,36 +739,32 @@ static bl_status launch_mma_l(int L, const bl_gemv_group& grp, int M, int blocks
  * Path: the VALU dot4 + DPP kernel for M <= 2, the matrix-core kernel above that (measured on
  * the four shapes of a layer in one launch, fused inputs: 7.4 / 14.0 / 18.6 / 23.0 us at M = 1..4
  * against 15.0 / 15.4 / 15.8 / 16.1; int8 inputs: 6.6 / 11.2 / 13.2 / 15.2 against 10.2 / 10.4 /
- * 10.6 / 10.8); normalising producers stay on the dot4 kernel up to M = 4.  BL_GEMV_PATH=rows / mma
- * forces one of them.  Returns BL_ERR_SHAPE if a K is too long for the register-resident row
+ * 10.6 / 10.8); normalising producers stay on the dot4 kernel up to M = 4.  The test hook
+ * bl_debug_force_path forces one of them.  Returns BL_ERR_SHAPE if a K is too long for the register-resident row
  * scheme (the caller then uses the prefill kernel). */
 bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
-    const char* path_env = getenv("BL_GEMV_PATH");
+    const int forced = bl_forced_decode_path();   /* 0 default, 1 dot4, 2 row-resident, 3 panel */
     bool any_norm = false, any_fused = false;
     for (int i = 0; i < grp.count; ++i) {
         any_norm = any_norm || (grp.p[i].fused && grp.p[i].prod.norm);
         any_fused = any_fused || grp.p[i].fused;
     }
     /* (a group of int8 products at M = 2 already does better on the panel kernel: 9.9 against 11.2) */
-    const bool dot4 = path_env && path_env[0] == 'm'   ? false
-                      : path_env && path_env[0] == 'r' ? M <= 4
-                      : path_env && path_env[0] == 'p' ? M <= 2 && any_fused
-                                                       : (M == 1 || (M == 2 && (any_fused || grp.count == 1)) ||
-                                                          (M <= 4 && any_norm));
-    int G = dot4 ? bl_env_int("BL_GEMV_G", 8) : 4;
-    if ((G != 4 && G != 8) || (dot4 && any_norm)) G = 8;
-    const int force_split = bl_env_int("BL_GEMV_KSPLIT", 0);
+    const bool dot4 = forced == 2   ? false
+                      : forced == 1 ? M <= 4
+                      : forced == 3 ? M <= 2 && any_fused
+                                    : (M == 1 || (M == 2 && (any_fused || grp.count == 1)) || (M <= 4 && any_norm));
+    const int G = dot4 ? 8 : 4;   /* lanes per weight row (8 measured better than 4 on the dot4 kernel) */
     /* workgroups wanted per product, measured: 150 for a product alone (best of 40..700) and
      * for the dot4 kernel; the matrix-core kernel, whose workgroups each stage all M rows,
      * does best with about 300 over the whole group */
-    const int want_blocks = bl_env_int("BL_GEMV_BLOCKS", dot4 || grp.count < 2 ? 150 : 300 / grp.count);
+    const int want_blocks = dot4 || grp.count < 2 ? 150 : 300 / grp.count;
     const int R = 64 / G;
     int blocks = 0, maxK = 0, L = 0;
     for (int i = 0; i < grp.count; ++i) {
         bl_gemv_prob& P = grp.p[i];
         int ks = 1;
         while (ks < 4 && (P.N + (4 / ks) * R - 1) / ((4 / ks) * R) < want_blocks) ks *= 2;
-        if (force_split == 1 || force_split == 2 || force_split == 4) ks = force_split;
         P.ksplit = ks;
         P.block0 = blocks;
         const int rows_per_block = (4 / ks) * R;
@@ -828,23 +790,17 @@ bl_status bl_gemv_launch_group(bl_gemv_group& grp, int M, hipStream_t st) {
          * the four shapes of a layer (us per layer, row-resident kernel / panel kernel):
          *   one launch:  M = 3: 10.5 / 9.9, 8: 11.7 / 10.0, 16: 17.1 / 10.2, 32: 26.8 / 10.7, 48: 38.2 / 14.0
          *   four calls:  M = 8: 23.4 / 28.9, 16: 26.7 / 29.3, 24: 37.1 / 29.7, 48: 54.1 / 38.1
-         * so a group goes to the panel kernel whenever it can, a product alone from 20 tokens.
-         * BL_GEMV_PATH=mma / panel force one of them. */
-        const bool want_panel =
-            !any_fused && (path_env ? path_env[0] == 'p' : (grp.count > 1 || M >= 20));
+         * so a group goes to the panel kernel whenever it can, a product alone from 20 tokens. */
+        const bool want_panel = !any_fused && (forced ? forced == 3 : (grp.count > 1 || M >= 20));
         if (want_panel) return bl_gemv_panel_launch(grp, M, st);
         if (M <= 16) return launch_mma_l<1>(L, grp, M, blocks, st);
         if (M <= 32) return launch_mma_l<2>(L, grp, M, blocks, st);
         return launch_mma_l<4>(L, grp, M, blocks, st);
     }
-    switch (M * 10 + G) {
-        case 14: return launch_rows_l<1, 4>(L, grp, blocks, maxK, st);
-        case 18: return launch_rows_l<1, 8>(L, grp, blocks, maxK, st);
-        case 24: return launch_rows_l<2, 4>(L, grp, blocks, maxK, st);
-        case 28: return launch_rows_l<2, 8>(L, grp, blocks, maxK, st);
-        case 34: return launch_rows_l<3, 4>(L, grp, blocks, maxK, st);
-        case 38: return launch_rows_l<3, 8>(L, grp, blocks, maxK, st);
-        case 44: return launch_rows_l<4, 4>(L, grp, blocks, maxK, st);
+    switch (M) {
+        case 1: return launch_rows_l<1, 8>(L, grp, blocks, maxK, st);
+        case 2: return launch_rows_l<2, 8>(L, grp, blocks, maxK, st);
+        case 3: return launch_rows_l<3, 8>(L, grp, blocks, maxK, st);
         default: return launch_rows_l<4, 8>(L, grp, blocks, maxK, st);
     }
 }

@@ -25,25 +25,13 @@
  *
  * Offset codes: the matrix cores multiply codes 0..2; sum_k q (given, or accumulated by one
  * more chain against an all-ones operand) is subtracted once per output. */
-#include <stdlib.h>
+#include <atomic>
 
 #include <type_traits>
 
 #include "bl_device.h"
 #include "bl_gemv_common.h"
 #include "bl_host.h"
-
-#ifdef BL_TRACE   /* development aid: per-workgroup time stamps (100 MHz clock) */
-__device__ unsigned long long* bl_ptrace_ptr;
-extern "C" int bl_trace_set_panel(void* p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(bl_ptrace_ptr), &p, sizeof(p)); }
-#define BL_PSTAMP_DECL unsigned long long bl_ts[6] = {0, 0, 0, 0, 0, 0}
-#define BL_PSTAMP(i) bl_ts[i] = wall_clock64()
-#define BL_PSTAMP_FLUSH do { if (threadIdx.x == 0 && bl_ptrace_ptr) for (int i_ = 0; i_ < 6; ++i_) bl_ptrace_ptr[blockIdx.x * 8 + i_] = bl_ts[i_]; } while (0)
-#else
-#define BL_PSTAMP_DECL
-#define BL_PSTAMP(i)
-#define BL_PSTAMP_FLUSH
-#endif
 
 #define BL_PANEL_HEAD 128   /* ints in front of the ring: 64 token scales, 64 row sums */
 
@@ -62,8 +50,6 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
     constexpr int KH = 8 / TB, NSUB = (KS / 32) / KH;      /* k parts; MFMA sub-steps per wave and step */
     static_assert((S - 2) * LOADS < 64, "vmcnt is a 6-bit count");
     static_assert(S * STG >= 8 * 4 * 4096, "the ring must hold the partial sums of the epilogue");
-    BL_PSTAMP_DECL;
-    BL_PSTAMP(0);
     const int N = P.N, K = P.K;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
@@ -213,7 +199,6 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
     };
 
     for (int s0 = 0; s0 < S - 1 && s0 < nsteps; ++s0) issue(s0, s0);
-    BL_PSTAMP(1);
     for (int it = 0; it < nsteps; ++it) {
         /* stage `it` has landed; the stages issued after it may stay in flight */
         const int later = nsteps - 1 - it;
@@ -221,8 +206,6 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (it == 0) BL_PSTAMP(2);
-        if (it == 1) BL_PSTAMP(3);
         const int nx = it + S - 1;
         if (nx < nsteps) issue(nx, nx % S);
         if (it * KS + KS > K) compute(it, it % S, std::true_type());
@@ -230,7 +213,6 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
     }
 
     bl_mfma_fence();
-    BL_PSTAMP(4);
     asm volatile("" ::: "memory");
     __syncthreads();                                       /* every wave is done with the ring */
     /* The k parts meet in LDS: wave w leaves its partial sums (minus its part of sum_k q) for
@@ -316,8 +298,6 @@ __device__ __forceinline__ void bl_panel_body(const bl_gemv_prob& P, const int M
         if (P.y && P.residual) emit(std::true_type());
         else emit(std::false_type());
     }
-    BL_PSTAMP(5);
-    BL_PSTAMP_FLUSH;
 }
 
 /* NI is a property of the workgroup's product: one specialised body per value, so that the
@@ -336,11 +316,12 @@ static bl_status launch_panel(const bl_gemv_group& grp, int M, int blocks, bool 
     constexpr int lds = BL_PANEL_HEAD * 4 + S * (TB * 32 * KS + 128 * (KS / 4));
     static_assert(lds <= 160 * 1024, "LDS of one CU");
     auto kern = have_sums ? bl_gemv_panel<TB, S, false, KS> : bl_gemv_panel<TB, S, true, KS>;
-    static bool done[2] = {false, false};
-    if (!done[have_sums]) {
+    /* (two threads may both set the attribute: the call is idempotent) */
+    static std::atomic<bool> done[2];
+    if (!done[have_sums].load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return BL_ERR_HIP;
-        done[have_sums] = true;
+        done[have_sums].store(true, std::memory_order_release);
     }
     kern<<<blocks, 512, lds, st>>>(grp, M);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
@@ -349,12 +330,10 @@ static bl_status launch_panel(const bl_gemv_group& grp, int M, int blocks, bool 
 /* M <= 64, int8 inputs only.  Rows per workgroup: 32 * NI.  A long k gets NI = 1: its
  * workgroups stream the most activation bytes and would otherwise finish last (measured on
  * the four shapes of a layer at M = 64: 18.9 us against 22.4 with NI = 2); every NI is halved
- * while the launch would leave most CUs without a workgroup.  BL_PANEL_NI forces one value. */
+ * while the launch would leave most CUs without a workgroup. */
 bl_status bl_gemv_panel_launch(bl_gemv_group& grp, int M, hipStream_t st) {
     if (M < 1 || M > 64) return BL_ERR_SHAPE;
     const int TB = M <= 32 ? 1 : 2;
-    const char* e = getenv("BL_PANEL_NI");
-    const int force = e && *e ? atoi(e) : 0;
     bool have_sums = true;
     int blocks = 0;
     for (int div = 1; div <= 4; div *= 2) {
@@ -367,17 +346,12 @@ bl_status bl_gemv_panel_launch(bl_gemv_group& grp, int M, hipStream_t st) {
             int ni = (P.K > 4096 ? 1 : 4) / div;
             if (ni <= 1) ni = 1;
             else floor_all = false;
-            if (force == 1 || force == 2 || force == 4) ni = force;
             P.ksplit = ni;
             P.block0 = blocks;
             blocks += (P.N + 32 * ni - 1) / (32 * ni);
         }
-        if (blocks >= 128 || floor_all || force) break;
+        if (blocks >= 128 || floor_all) break;
     }
-    const char* eks = getenv("BL_PANEL_KS");
-    if (eks && atoi(eks) == 256)
-        return TB == 1 ? launch_panel<1, 8, 256>(grp, M, blocks, have_sums, st)
-                       : launch_panel<2, 6, 256>(grp, M, blocks, have_sums, st);
     return TB == 1 ? launch_panel<1, 4, 512>(grp, M, blocks, have_sums, st)
                    : launch_panel<2, 3, 512>(grp, M, blocks, have_sums, st);
 }

@@ -12,3 +12,8 @@ static inline bool bl_shape_ok(int64_t N, int64_t K) {
     return N >= 4 && N % 4 == 0 && K >= 64 && K % 64 == 0 && N <= BL_MAX_DIM && K <= BL_MAX_DIM;
 }
 static inline bool bl_aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+/* Test hook (bl_debug_force_path): which decode kernel bl_gemv_launch_group takes.
+ * 0 = the measured default, 1 = dot4 kernel where it applies, 2 = row-resident matrix-core
+ * kernel, 3 = streaming panel kernel where it applies.  Process-wide, atomic. */
+int bl_forced_decode_path(void);

@@ -123,3 +123,12 @@ def test_noalloc_entry_point_checks_arguments_before_any_gpu_work(lib):
     assert lib.bl_gemm_w158a8_noalloc(p, p, 1, p, p, 0, 64, 64, p, p, None) == 2
     assert lib.bl_gemm_w158a8_noalloc(p, p, 9, p, p, 1, 64, 64, p, p, None) == 3         # layout
     assert lib.bl_gemm_w158a8_noalloc(p + 4, p, 1, p, p, 1, 64, 64, p, p, None) == 4     # alignment
+
+
+def test_debug_hook_and_gemv_workspace_status(lib):
+    assert lib.bl_debug_force_path(4) == 5 and lib.bl_debug_force_path(-1) == 5
+    assert lib.bl_debug_force_path(2) == 0 and lib.bl_debug_force_path(0) == 0
+    # a decode product with K > 8192 and no row sums needs the workspace: reported before any GPU work
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) & ~255
+    assert lib.bl_gemv_w158a8(p, p, 1, p, p, None, 1, 64, 8256, p, p, None, None) == 7

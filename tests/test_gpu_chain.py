@@ -210,12 +210,10 @@ def test_chain_two_layers_with_normalisation(bl, chain, mode, M):
 @pytest.mark.timeout(900)
 def test_config4_full_stack_decode_and_prefill(bl, chain):
     """30 layers of the 2B shapes.  Decode at M=1 is compared in full.  Prefill at M=4096 runs in
-    full on the GPU; compared with the oracle are (tokens are independent in this chain, so the
-    oracle runs just the rows it compares): EVERY one of the 4096 rows of layer 0 (quantised
-    inputs, scales, int32 accumulators and outputs of all four BitLinears: every tile and every
-    tile-to-XCD region of the M=4096 launches), and through all 30 layers one row in every 32-row
-    block (128 rows, at a different offset inside each block) plus the first two and the last row.
-    The whole 30-layer product for all rows would be 8.5e12 oracle multiply-adds (minutes)."""
+    full on the GPU and is compared here, through all 30 layers, on one row in every 32-row block
+    (128 rows, at a different offset inside each block) plus the first two and the last row
+    (tokens are independent in this chain, so the oracle runs just those rows); the comparison of
+    every row of every layer is test_config4_prefill_every_row_every_layer below."""
     n_layers, Mp = synth.N_LAYERS, 4096
     blocks = np.arange(Mp // 32)
     sample = np.unique(np.concatenate([blocks * 32 + (blocks * 7 + 3) % 32, [0, 1, Mp - 1]]))
@@ -246,27 +244,17 @@ def test_config4_full_stack_decode_and_prefill(bl, chain):
         _compare_records([rec_p], [tr_p], rows=sample)
         assert_y_close(dev_dec.cpu().numpy(), o_dec)
         assert_y_close(dev_pre.cpu().numpy()[sample], o_pre)
-        if l == 0:
-            # every row of the first layer
-            tr_all = []
-            o_all = oracle.chain_layer(x_pre, wts, trace=tr_all)
-            _compare_records([rec_p], [tr_all])
-            for r, t in zip(rec_p, tr_all):
-                if r["name"] != "down":      # (the down product's output has the residual added: checked below)
-                    assert_y_close(r["y"].cpu().numpy(), t["y"])
-            assert_y_close(dev_pre.cpu().numpy(), o_all)
-            del tr_all, o_all
         print("layer %d ok (|x| max %.3g)" % (l, float(np.abs(o_dec).max())), file=sys.stderr, flush=True)
         del gw, ow, wts, rec_p, rec_d
 
 
 @pytest.mark.timeout(3000)
-@pytest.mark.skipif(__import__("os").environ.get("BL_FULL_CONFIG4") != "1",
-                    reason="8.5e12 oracle multiply-adds (several minutes): opt in with BL_FULL_CONFIG4=1")
+@pytest.mark.skipif(__import__("os").environ.get("BL_SKIP_FULL_CONFIG4") == "1",
+                    reason="8.5e12 oracle multiply-adds (80 s on the 16 host cores of a GPU box): skipped on request")
 def test_config4_prefill_every_row_every_layer(bl, chain):
     """The complete comparison of the M=4096 prefill stack: every row, every BitLinear of all 30
-    layers (quantised inputs, scales, int32 accumulators) and the final residual stream.  Prints a
-    line per layer so that a long run is seen to move."""
+    layers (quantised inputs, scales, int32 accumulators) and the residual stream after every
+    layer.  Prints a line per layer so that a long run is seen to move (pytest -s)."""
     n_layers, Mp = synth.N_LAYERS, 4096
     x_pre = synth.bf16_bits_to_f32(synth.activations_bf16(0, Mp, 2560, layer=101))
     dev_pre, o_pre = to_dev(x_pre), x_pre

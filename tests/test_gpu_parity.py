@@ -25,6 +25,19 @@ def _sync():
     torch.cuda.synchronize()
 
 
+PATHS = {"rows": 1, "mma": 2, "panel": 3}
+
+
+@pytest.fixture
+def force_path(bl):
+    """Routes the decode entry points to one kernel through the library's test hook and puts the
+    default back afterwards."""
+    def set_path(name):
+        assert bl.load().bl_debug_force_path(PATHS[name]) == 0
+    yield set_path
+    assert bl.load().bl_debug_force_path(0) == 0
+
+
 # ------------------------------------------------------------------- packing
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("shape", [(4, 64), (48, 320), (2560, 2560), (2560, 6912)])
@@ -149,9 +162,9 @@ def test_gemv_batched_phases_and_tails(bl, M, N, K):
 
 @pytest.mark.parametrize("path", ["rows", "mma"])
 @pytest.mark.parametrize("M", [1, 2, 3, 4])
-def test_both_small_m_decode_kernels(bl, monkeypatch, path, M):
+def test_both_small_m_decode_kernels(bl, force_path, path, M):
     """1..4 tokens: the dot4 kernel and the matrix-core kernel, int8 and fused inputs."""
-    monkeypatch.setenv("BL_GEMV_PATH", path)
+    force_path(path)
     c = Case(39, M, 264, 1088)
     for layout in (0, 1):
         acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(layout == 0))
@@ -169,10 +182,10 @@ def test_both_small_m_decode_kernels(bl, monkeypatch, path, M):
 @pytest.mark.parametrize("path", ["mma", "panel"])
 @pytest.mark.parametrize("M,N,K", [(5, 264, 1088), (12, 2560, 2560), (17, 2560, 2560), (32, 264, 2624),
                                    (40, 100, 1088), (64, 2560, 6912), (64, 36, 192), (9, 20, 64)])
-def test_both_batched_decode_kernels_at_every_m(bl, monkeypatch, path, M, N, K):
-    """The library picks one of two matrix-core kernels by measured speed; BL_GEMV_PATH forces
+def test_both_batched_decode_kernels_at_every_m(bl, force_path, path, M, N, K):
+    """The library picks one of two matrix-core kernels by measured speed; the test hook forces
     either, and both must give the oracle's numbers on every shape."""
-    monkeypatch.setenv("BL_GEMV_PATH", path)
+    force_path(path)
     c = Case(37, M, N, K)
     for layout in (0, 1):
         acc, y = _run_product(bl, bl.bl_gemv_w158a8, c, layout, use_rowsum=(layout == 0))
