@@ -207,8 +207,11 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * behind the other's MFMAs (a single wave reaches only ~60 % of the MFMA rate
  * once the unpack instructions share its issue slot).
  *
- * LDS stage = A part (256 rows x 128 int8, 16-byte units XOR-swizzled by
- * row%8) + W part (256 rows x 32 packed bytes = two units, swapped by row/4%2).
+ * LDS stage = A part (BM rows x 128 int8, 16-byte units XOR-swizzled by
+ * (row/2)%8) + W part (BN rows x 32 packed bytes = two units, swapped by row/8%2): with these
+ * two patterns sixteen consecutive lanes of a ds_read_b128 fall on sixteen different 16-byte
+ * bank groups (measured on a read-only loop, 8 waves per CU: 152 - 154 B/clk/CU against 113 - 116
+ * for swizzles by row%8 and row/4%2, which are conflict-free only over eight lanes).
  * A direct load writes 64 consecutive units per wave, so the swizzle is applied
  * to the GLOBAL address each lane fetches, not to the LDS address.
  *
@@ -224,13 +227,13 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
 
 
 template <int BM, int BN, int STAGES, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
+__global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
                                                                 const int32_t* __restrict__ rowsum,
                                                                 const float* __restrict__ beta,
                                                                 const float* __restrict__ scale, int M, int N,
                                                                 int K, int tiles_m, int tiles_n, int gm,
-                                                                const float* __restrict__ residual,
+                                                                int vgrid, const float* __restrict__ residual,
                                                                 int32_t* __restrict__ acc, float* __restrict__ y) {
     constexpr int NW = WM * WN, THREADS = NW * 64;
     constexpr int G3_BM = BM, G3_A_BYTES = BM * G3_BK;
@@ -240,44 +243,69 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
     constexpr int W_LOADS = G3_W_BYTES / 16 / THREADS;
     constexpr int LOADS = A_LOADS + W_LOADS;
     static_assert((STAGES - 2) * LOADS < 64, "vmcnt is a 6-bit count");
+    static_assert(THREADS >= BM, "one thread per tile row fetches the row terms");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    /* behind the stages: the per-row terms of the tile in flight (row sum, beta*scale) */
+    int* const rs_s = (int*)(smem + STAGES * G3_STAGE_BYTES);
+    float* const cf_s = (float*)(rs_s + G3_BM);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
+    const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
+    const int kb = K / 4;
+    const int steps = K / G3_BK;
+    const float bt = y ? *beta : 0.0f;
 
     /* XCD-aware tile order: workgroup L runs on XCD L%8.  The tile grid is cut
      * into gm x gn = 8 rectangular regions, one per XCD, narrow enough in M that
      * a region's activation panel stays in that XCD's 4 MB L2 while its weight
-     * tiles stream through; inside a region the row tiles vary fastest. */
+     * tiles stream through; inside a region the row tiles vary fastest.  The grid is
+     * persistent: a workgroup takes virtual blocks vb = blockIdx.x, + gridDim.x, .. (gridDim.x
+     * is a multiple of 8, so a workgroup stays on its XCD's region). */
     const int gn = 8 / gm;
     const int rm = (tiles_m + gm - 1) / gm, rn = (tiles_n + gn - 1) / gn;
-    const int xcd = (int)blockIdx.x & 7, idx = (int)blockIdx.x >> 3;
-    const int tm = (xcd / gn) * rm + idx % rm, tn = (xcd % gn) * rn + idx / rm;
-    if (tm >= tiles_m || tn >= tiles_n) return;
-    const int m0 = tm * G3_BM, n0 = tn * BN;
-    const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
-    const int kb = K / 4;
+    auto tile_of = [&](int vb, int& tm, int& tn) {
+        const int xcd = vb & 7, idx = vb >> 3;
+        tm = (xcd / gn) * rm + idx % rm;
+        tn = (xcd % gn) * rn + idx / rm;
+        return tm < tiles_m && tn < tiles_n;
+    };
+    /* the next virtual block of this workgroup that maps to a real tile, or -1 */
+    auto next_tile = [&](int vb, int& tm, int& tn) {
+        for (; vb < vgrid; vb += (int)gridDim.x)
+            if (tile_of(vb, tm, tn)) return vb;
+        return -1;
+    };
 
-    /* per-lane global sources of the direct loads */
+    /* per-lane global sources of the direct loads of the tile (tm, tn) */
     const uint8_t* asrc[A_LOADS];
-    {
-        const int u = (lane & 7) ^ ((lane >> 3) & 7);
+    const uint8_t* wsrc[W_LOADS];
+    int row_rs = 0;
+    float row_cf = 0.0f;
+    auto setup = [&](int tm, int tn) {
+        const int m0 = tm * G3_BM, n0 = tn * BN;
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j) {
-            int m = m0 + (j * NW + wave) * 8 + (lane >> 3);
+            const int row = (j * NW + wave) * 8 + (lane >> 3);          /* row of the tile */
+            const int u = (lane & 7) ^ ((row >> 1) & 7);
+            int m = m0 + row;
             if (m >= M) m = M - 1;
             asrc[j] = (const uint8_t*)q + (int64_t)m * K + u * 16;
         }
-    }
-    const uint8_t* wsrc[W_LOADS];
-    {
-        const int u = (lane & 1) ^ ((lane >> 3) & 1);
+        const int u = (lane & 1) ^ ((lane >> 4) & 1);
 #pragma unroll
         for (int j = 0; j < W_LOADS; ++j) {
             int n = n0 + (j * NW + wave) * 32 + (lane >> 1);
             if (n >= N) n = N - 1;
             wsrc[j] = packed + (int64_t)n * kb + u * 16;
         }
-    }
+        /* the tile's per-row terms travel in two registers until the epilogue (a load there
+         * would put a memory round trip between the last MFMA and the first store) */
+        if (tid < G3_BM) {
+            const int m = m0 + tid;
+            row_rs = m < M ? rowsum[m] : 0;
+            row_cf = (y && m < M) ? bt * scale[m] : 0.0f;
+        }
+    };
     auto issue = [&](int kk, int buf) {
         uint8_t* st = smem + buf * G3_STAGE_BYTES;
 #pragma unroll
@@ -290,68 +318,39 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                                              (bl_lptr)(st + G3_A_BYTES + (j * NW + wave) * 1024), 16, 0, 0);
     };
 
-    bl_v16i C[MI][NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) C[mi][ni][v] = 0;
-
     /* per-lane LDS read offsets (bytes) inside a stage */
     const int a_row_off = (wm0 + l32) * G3_BK;
-    const int a_swz = l32 & 7;
-    const int w_off = G3_A_BYTES + ((wn0 + l32) * 2 + (h ^ ((l32 >> 2) & 1))) * 16;
+    const int a_swz = (l32 >> 1) & 7;
+    const int w_off = G3_A_BYTES + ((wn0 + l32) * 2 + (h ^ ((l32 >> 3) & 1))) * 16;
 
-    const int steps = K / G3_BK;
+    int tm, tn;
+    int vb = next_tile((int)blockIdx.x, tm, tn);
+    if (vb < 0) return;
+    setup(tm, tn);
     /* STAGES - 1 k steps are in flight ahead of the matrix cores: a k step of one workgroup
      * takes far less time than a load, so the depth, not the tile, hides the latency */
     for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
-    for (int kk = 0; kk < steps; ++kk) {
-        /* stage kk must have landed; the stages issued after it may stay in flight */
-        const int later = steps - 1 - kk;
-        bl_wait_stages<STAGES - 2, LOADS>(later < STAGES - 2 ? later : STAGES - 2);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        if (kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
-        const uint8_t* st = smem + (kk % STAGES) * G3_STAGE_BYTES;
-        if (NW == 8) {
-            /* Two waves share a SIMD.  A wave's own VALU and MFMA instructions do
-             * not overlap, but one wave's MFMAs run while the other unpacks and
-             * reads LDS.  So each half k step is three pinned phases - LDS reads,
-             * unpack, a solid block of MFMAs - and the two waves of a SIMD fall
-             * into opposite phases by themselves. */
-            bl_v4i wq[NI];
+
+    while (true) {
+        const int m0 = tm * G3_BM, n0 = tn * BN;
+        bl_v16i C[MI][NI];
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) wq[ni] = *(const bl_v4i*)(st + w_off + ni * 32 * 32);
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                bl_v4i a[2][MI], bop[2][NI];
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    const int unit = ((4 * h + half * 2 + k2) ^ a_swz) * 16;
-#pragma unroll
-                    for (int mi = 0; mi < MI; ++mi)
-                        a[k2][mi] = *(const bl_v4i*)(st + a_row_off + mi * 32 * G3_BK + unit);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) bop[k2][ni] = bl_unpack16((uint32_t)wq[ni][half * 2 + k2]);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                        for (int mi = 0; mi < MI; ++mi)
-                            C[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[k2][mi], bop[k2][ni], C[mi][ni], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        } else {
-            /* one wave per SIMD: operands of sub-step ks+1 are fetched while ks multiplies */
+                for (int v = 0; v < 16; ++v) C[mi][ni][v] = 0;
+
+        for (int kk = 0; kk < steps; ++kk) {
+            /* stage kk must have landed; the stages issued after it may stay in flight */
+            const int later = steps - 1 - kk;
+            bl_wait_stages<STAGES - 2, LOADS>(later < STAGES - 2 ? later : STAGES - 2);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
+            const uint8_t* st = smem + (kk % STAGES) * G3_STAGE_BYTES;
+            /* operands of sub-step ks+1 are fetched while ks multiplies */
             bl_v4i wq[NI], a[2][MI];
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) wq[ni] = *(const bl_v4i*)(st + w_off + ni * 32 * 32);
@@ -375,64 +374,74 @@ __global__ __launch_bounds__(WM * WN * 64) void bl_gemm_tile256(const uint8_t* _
                 }
             }
         }
-    }
 
-    /* Epilogue.  The per-row terms go through LDS once (the stages are free now):
-     * a load per output row inside the store loop would serialise on latency. */
-    bl_mfma_fence();
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    int* rs_s = (int*)smem;
-    float* cf_s = (float*)(smem + G3_BM * 4);
-    if (tid < G3_BM) {   /* THREADS >= BM for every instantiation */
-        const int m = m0 + tid;
-        rs_s[tid] = m < M ? rowsum[m] : 0;
-        cf_s[tid] = (y && m < M) ? *beta * scale[m] : 0.0f;
-    }
-    __syncthreads();
+        /* Epilogue.  The per-row terms go through LDS once: a load per output row inside the
+         * store loop would serialise on latency.  Every wave is past its last stage read after
+         * the barrier, so the first stages of this workgroup's NEXT tile are requested here and
+         * travel while this tile is stored. */
+        bl_mfma_fence();
+        if (tid < G3_BM) {
+            rs_s[tid] = row_rs;
+            cf_s[tid] = row_cf;
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        int tm2 = 0, tn2 = 0;
+        const int vb2 = next_tile(vb + (int)gridDim.x, tm2, tn2);
+        if (vb2 >= 0) {
+            setup(tm2, tn2);
+            for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
+        }
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            /* the residual values of four rows first, then their stores back to back: a load
-             * between two stores would make each store wait for the one before it */
-            float rres[4][NI];
-            if (residual && y) {
+            for (int vq = 0; vq < 4; ++vq) {
+                /* the residual values of four rows first, then their stores back to back: a load
+                 * between two stores would make each store wait for the one before it */
+                float rres[4][NI];
+                if (residual && y) {
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const int m = m0 + wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        const int m = m0 + wm0 + mi * 32 + vq * 8 + h * 4 + v4;
 #pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        const int n = n0 + wn0 + ni * 32 + l32;
-                        rres[v4][ni] = (m < M && n < N) ? residual[(int64_t)m * N + n] : 0.0f;
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int n = n0 + wn0 + ni * 32 + l32;
+                            rres[v4][ni] = (m < M && n < N) ? residual[(int64_t)m * N + n] : 0.0f;
+                        }
                     }
                 }
-            }
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int v = vq * 4 + v4;
-                const int ml = wm0 + mi * 32 + vq * 8 + h * 4 + v4;
-                const int m = m0 + ml;
-                if (m < M) {
-                    const int rs = rs_s[ml];
-                    const float c = cf_s[ml];
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int v = vq * 4 + v4;
+                    const int ml = wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+                    const int m = m0 + ml;
+                    if (m < M) {
+                        const int rs = rs_s[ml];
+                        const float c = cf_s[ml];
 #pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        const int n = n0 + wn0 + ni * 32 + l32;
-                        if (n < N) {
-                            const int val = C[mi][ni][v] - rs;
-                            if (acc) acc[(int64_t)m * N + n] = val;
-                            if (y) {
-                                const float t = (float)val * c;
-                                const float out = residual ? rres[v4][ni] + t : t;
-                                __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int n = n0 + wn0 + ni * 32 + l32;
+                            if (n < N) {
+                                const int val = C[mi][ni][v] - rs;
+                                if (acc) acc[(int64_t)m * N + n] = val;
+                                if (y) {
+                                    const float t = (float)val * c;
+                                    const float out = residual ? rres[v4][ni] + t : t;
+                                    __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
+                                }
                             }
                         }
                     }
                 }
             }
-        }
+        if (vb2 < 0) break;
+        vb = vb2;
+        tm = tm2;
+        tn = tn2;
+        /* the next tile's epilogue rewrites rs_s / cf_s only after its own k loop, whose barriers
+         * every wave passes after it has finished the reads above */
+    }
 }
 
 template <int BM, int BN, int STAGES, int WM, int WN>
@@ -440,7 +449,7 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
                                   const int32_t* rowsum, int M, int N, int K, const float* residual,
                                   int32_t* acc, float* y, hipStream_t st) {
     constexpr int G3_BM = BM;
-    constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4);
+    constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4) + BM * 8;
     auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN>;
     static std::atomic<bool> attr_set;
     if (!attr_set.load(std::memory_order_acquire)) {
@@ -455,9 +464,24 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     int gm = 1;
     while (gm < 8 && (int64_t)((tiles_m + gm - 1) / gm) * BM * K > (3 << 19)) gm *= 2;
     const int gn = 8 / gm;
-    const int blocks = 8 * ((tiles_m + gm - 1) / gm) * ((tiles_n + gn - 1) / gn);
-    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, residual,
-                                            acc, y);
+    const int vgrid = 8 * ((tiles_m + gm - 1) / gm) * ((tiles_n + gn - 1) / gn);
+    /* persistent grid: what is resident at once (a multiple of 8 keeps a workgroup on its XCD's region) */
+    static std::atomic<int> resident{0};
+    int blocks = resident.load(std::memory_order_acquire);
+    if (blocks == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, WM * WN * 64, lds) != hipSuccess ||
+            cus < 1 || per_cu < 1)
+            return BL_ERR_HIP;
+        blocks = cus * per_cu / 8 * 8;
+        if (blocks < 8) blocks = 8;
+        resident.store(blocks, std::memory_order_release);
+    }
+    if (blocks > vgrid) blocks = vgrid;
+    kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, vgrid,
+                                            residual, acc, y);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
