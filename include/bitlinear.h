@@ -232,6 +232,40 @@ bl_status bl_gemm_w158a8_res(const uint8_t* packed, const float* beta, int layou
                              int64_t M, int64_t N, int64_t K, const float* residual,
                              int32_t* acc, float* y, void* workspace, bl_stream s);
 
+/* Prefill product with a FUSED PRODUCER EPILOGUE (Section 2: per-token absmax activation
+ * quantisation, ReLU^2 in the FFN): the elementwise step that turns this product's output into
+ * the next BitLinear's input runs in the product's epilogue, so the fp32 output is not written
+ * and read again just to be narrowed.  The epilogue writes the bf16 input of the next BitLinear
+ * and folds the row maximum of its absolute values into absmax[] (an order-free maximum on the
+ * float bits, across all workgroups of the launch); bl_quant_from_absmax then quantises in one
+ * pass.  Bit for bit the same numbers as bl_gemm_w158a8[_res] followed by bl_quant_act_ex.
+ *   BL_EPI_RESIDUAL    t = residual[m][n] + acc*(beta*scale[m]);  N_out = N
+ *   BL_EPI_RELU2_GATE  the matrix is a fused [gate | up] pair (rows n and N/2 + n):
+ *                      g = acc_g*(beta*scale[m]), u = acc_u*(..), t = (max(g,0)*max(g,0))*u;
+ *                      N_out = N/2; needs N % 128 == 0
+ *   y       device out fp32 [M][N_out] or NULL: t itself (wanted when t is a later residual)
+ *   x_bf16  device out bf16 [M][N_out]: bf16(t)
+ *   absmax  device in/out fp32 [M]: must hold 0 (or an earlier partial maximum of the same rows)
+ *           before the launch; receives max_n |bf16(t)|.  bl_quant_from_absmax clears it again.
+ *   acc     device out int32 [M][N] or NULL (the raw accumulators, natural column order).
+ * Needs layout BL_LAYOUT_K16, K % 128 == 0 and rowsum (BL_ERR_LAYOUT / BL_ERR_SHAPE / BL_ERR_NULL). */
+enum { BL_EPI_RESIDUAL = 1, BL_EPI_RELU2_GATE = 2 };
+typedef struct {
+    int kind;
+    const float* residual;   /* BL_EPI_RESIDUAL: fp32 [M][N] */
+    float* y;
+    uint16_t* x_bf16;
+    float* absmax;
+} bl_gemm_epilogue;
+bl_status bl_gemm_w158a8_fused(const uint8_t* packed, const float* beta, int layout,
+                               const int8_t* q, const float* scale, const int32_t* rowsum,
+                               int64_t M, int64_t N, int64_t K, const bl_gemm_epilogue* ep /* HOST */,
+                               int32_t* acc, bl_stream s);
+/* One-pass quantiser for rows whose absmax is already known: like bl_quant_act_int8 with
+ * gamma = absmax[m] given; clears absmax[m] to 0 afterwards. */
+bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int64_t K,
+                               int8_t* q, float* scale, int32_t* rowsum, bl_stream s);
+
 /* Persistent streaming decode over a TABLE of products (Section 5.1: the decode kernel is
  * there to use as little memory bandwidth as possible, which on this GPU means the weight
  * stream of a whole stack of BitLinears must never stop).  One launch walks every product

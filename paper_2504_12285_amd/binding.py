@@ -31,6 +31,8 @@ SIGNATURES = {
     "bl_bitlinear_decode_group": (_ci, [_vp, _ci, _ci, _i64, _vp]),
     "bl_quant_act_ex": (_ci, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_gemm_w158a8_res": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "bl_gemm_w158a8_fused": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "bl_quant_from_absmax": (_ci, [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_stack_table_bytes": (_sz, [_vp, _ci]),
     "bl_stack_build": (_ci, [_vp, _ci, _ci, _i64, _vp, _vp, _vp]),
     "bl_stack_run": (_ci, [_vp, _vp, _vp]),
@@ -64,6 +66,14 @@ class DecodeDesc(ctypes.Structure):
     _fields_ = [("packed", _vp), ("beta", _vp), ("X", _vp), ("q", _vp), ("scale", _vp), ("rowsum", _vp),
                 ("N", _i64), ("K", _i64), ("acc", _vp), ("y", _vp), ("q_out", _vp), ("scale_out", _vp),
                 ("fixed_scale", ctypes.c_float), ("prod", Producer), ("residual", _vp)]
+
+
+BL_EPI_RESIDUAL, BL_EPI_RELU2_GATE = 1, 2
+
+
+class GemmEpilogue(ctypes.Structure):
+    """Mirror of bl_gemm_epilogue."""
+    _fields_ = [("kind", _ci), ("residual", _vp), ("y", _vp), ("x_bf16", _vp), ("absmax", _vp)]
 
 
 class StackPlan(ctypes.Structure):
@@ -306,3 +316,29 @@ class Stack:
 
     def run(self):
         _check(load().bl_stack_run(_ptr(self.table), ctypes.byref(self.plan), _stream()), "bl_stack_run")
+
+
+def bl_gemm_w158a8_fused(packed, beta, layout, q, scale, rowsum, N, kind, x_bf16, absmax, residual=None, y=None,
+                         acc=None):
+    """Prefill product with a fused producer epilogue (bl_gemm_w158a8_fused).  x_bf16: bf16 [M][N_out]
+    out; absmax: fp32 [M], zero before the call."""
+    M, K = q.shape
+    ep = GemmEpilogue()
+    ep.kind, ep.residual, ep.y, ep.x_bf16, ep.absmax = int(kind), _ptr(residual), _ptr(y), _ptr(x_bf16), _ptr(absmax)
+    _check(load().bl_gemm_w158a8_fused(_ptr(packed), _ptr(beta), layout, _ptr(q), _ptr(scale), _ptr(rowsum), M, N, K,
+                                       ctypes.byref(ep), _ptr(acc), _stream()), "bl_gemm_w158a8_fused")
+
+
+def bl_quant_from_absmax(X, absmax, q=None, scale=None, rowsum=None):
+    """One-pass quantiser of bf16 rows X [M][K] with known row maxima (cleared by the call)."""
+    import torch
+    M, K = X.shape
+    if q is None:
+        q = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    if scale is None:
+        scale = torch.empty(M, dtype=torch.float32, device=X.device)
+    if rowsum is None:
+        rowsum = torch.empty(M, dtype=torch.int32, device=X.device)
+    _check(load().bl_quant_from_absmax(_ptr(X), _ptr(absmax), M, K, _ptr(q), _ptr(scale), _ptr(rowsum), _stream()),
+           "bl_quant_from_absmax")
+    return q, scale, rowsum

@@ -36,6 +36,11 @@ class ChainBuffers:
         self.q = {k: torch.empty((M, K), dtype=torch.int8, device=device) for k, K in (("h", 2560), ("f", 6912))}
         self.scale = torch.empty(M, **f32)
         self.rowsum = torch.empty(M, dtype=torch.int32, device=device)
+        # fused producer epilogues: bf16 inputs of the next BitLinear and their row maxima (kept at zero
+        # between uses: the one-pass quantiser clears what the epilogue accumulated)
+        self.xb = {k: torch.empty((M, K), dtype=torch.bfloat16, device=device) for k, K in (("h", 2560), ("f", 6912))}
+        self.absmax = torch.zeros(M, **f32)
+        self.q_valid_for = None       # data_ptr of the residual stream whose int8 form sits in q["h"]
 
 
 def _producers(x, B, gains=None, eps=1e-5):
@@ -76,10 +81,65 @@ def layer_decode(weights, layout, x, B, records=None, gains=None):
 
 
 def layer_prefill(weights, layout, x, B, records=None, gains=None):
+    """One layer for any M.  Without gains (and with the kernel-native layout) the elementwise glue
+    runs in the products' epilogues: o -> h1 = x + o, gate_up -> relu(g)^2 * u, down -> x' = h1 + down,
+    each written once as bf16 with its row maximum, then quantised in one pass (the input of the qkv
+    product of the NEXT layer included).  With gains (RMS normalisation, a float reduction over the
+    row) or layout 0: producer + quantiser kernel in front of every product."""
+    import torch
+    if gains is not None or layout != bl.BL_LAYOUT_K16:
+        return _layer_prefill_unfused(weights, layout, x, B, records, gains)
+    M, dev = B.M, B.device
+
+    def rec(name, acc, q, y):
+        if records is not None:
+            records.append(dict(name=name, acc=acc, q=q.clone(), scale=B.scale.clone(), y=y))
+
+    def new_acc(N):
+        return torch.empty((M, N), dtype=torch.int32, device=dev) if records is not None else None
+
+    qh, qf = B.q["h"], B.q["f"]
+    # qkv: its input was quantised by the previous layer's down epilogue, or comes from outside
+    if B.q_valid_for != x.data_ptr():
+        bl.bl_quant_act_ex(bl.make_producer(bl.BL_PROD_F32, x), M, 2560, dev, q=qh, scale=B.scale, rowsum=B.rowsum)
+    packed, beta = weights["qkv"]
+    acc = new_acc(3840)
+    bl.bl_gemm_w158a8_res(packed, beta, layout, qh, B.unit, B.rowsum, 3840, None, want_acc=records is not None,
+                          acc=acc, y=B.qkv)
+    rec("qkv", acc, qh, B.qkv.clone() if records is not None else None)
+    # o: context-length-1 attention = V broadcast (a gather, not an epilogue of qkv), then h1 = x + o
+    bl.bl_quant_act_ex(bl.make_producer(bl.BL_PROD_ATTN_V, B.qkv, n_q=N_Q, n_kv=N_KV, head_dim=HEAD_DIM), M, 2560, dev,
+                       q=qh, scale=B.scale, rowsum=B.rowsum)
+    packed, beta = weights["o"]
+    acc = new_acc(2560)
+    bl.bl_gemm_w158a8_fused(packed, beta, layout, qh, B.unit, B.rowsum, 2560, bl.BL_EPI_RESIDUAL, B.xb["h"], B.absmax,
+                            residual=x, y=B.h1, acc=acc)
+    rec("o", acc, qh, None)
+    # gate_up: input bf16(h1); epilogue relu(g)^2 * u
+    bl.bl_quant_from_absmax(B.xb["h"], B.absmax, q=qh, scale=B.scale, rowsum=B.rowsum)
+    packed, beta = weights["gate_up"]
+    acc = new_acc(13824)
+    bl.bl_gemm_w158a8_fused(packed, beta, layout, qh, B.unit, B.rowsum, 13824, bl.BL_EPI_RELU2_GATE, B.xb["f"], B.absmax,
+                            acc=acc)
+    rec("gate_up", acc, qh, None)
+    # down: epilogue x' = h1 + down, and the int8 form of x' for the next layer's qkv
+    bl.bl_quant_from_absmax(B.xb["f"], B.absmax, q=qf, scale=B.scale, rowsum=B.rowsum)
+    packed, beta = weights["down"]
+    acc = new_acc(2560)
+    bl.bl_gemm_w158a8_fused(packed, beta, layout, qf, B.unit, B.rowsum, 2560, bl.BL_EPI_RESIDUAL, B.xb["h"], B.absmax,
+                            residual=B.h1, y=B.x_next, acc=acc)
+    rec("down", acc, qf, None)
+    bl.bl_quant_from_absmax(B.xb["h"], B.absmax, q=qh, scale=B.scale, rowsum=B.rowsum)
+    B.q_valid_for = B.x_next.data_ptr()
+    return B.x_next
+
+
+def _layer_prefill_unfused(weights, layout, x, B, records=None, gains=None):
     """One layer for any M: producer+quantiser kernel, then the matrix-core
     product (residual fused into the last epilogue)."""
     import torch
     M = B.M
+    B.q_valid_for = None
     prods = _producers(x, B, gains)
     outs = {"qkv": B.qkv, "o": B.o, "gate_up": B.gu, "down": B.x_next}
     for name in ("qkv", "o", "gate_up", "down"):

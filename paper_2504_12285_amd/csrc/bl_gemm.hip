@@ -226,7 +226,13 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
 #define G3_BK 128
 
 
-template <int BM, int BN, int STAGES, int WM, int WN>
+/* EPI: 0 = plain epilogue (int32 and/or fp32 outputs, optional residual); 1 = fused producer
+ * epilogue "residual": t = residual + product, written as fp32 (y, optional) and as bf16 (xb) with
+ * the row maximum of |bf16(t)| folded into absmax[m]; 2 = "squared-ReLU gate": the tile's 128 weight
+ * rows are 2 x 32 gate rows and the 2 x 32 matching up rows (n and N/2 + n), t = (relu(g)*relu(g))*u
+ * for N/2 output columns, written as bf16 with its row maximum (Section 2: ReLU^2 in the FFN,
+ * per-token absmax quantisation of the next BitLinear's input). */
+template <int BM, int BN, int STAGES, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
                                                                 const int32_t* __restrict__ rowsum,
@@ -234,7 +240,9 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                                                                 const float* __restrict__ scale, int M, int N,
                                                                 int K, int tiles_m, int tiles_n, int gm,
                                                                 int vgrid, const float* __restrict__ residual,
-                                                                int32_t* __restrict__ acc, float* __restrict__ y) {
+                                                                int32_t* __restrict__ acc, float* __restrict__ y,
+                                                                uint16_t* __restrict__ xb, int* __restrict__ absmax) {
+    static_assert(EPI != 2 || (BN == 128 && WN == 2 && BN / WN / 32 == 2), "the gate epilogue pairs ni = 0 with ni = 1");
     constexpr int NW = WM * WN, THREADS = NW * 64;
     constexpr int G3_BM = BM, G3_A_BYTES = BM * G3_BK;
     constexpr int G3_W_BYTES = BN * G3_BK / 4, G3_STAGE_BYTES = G3_A_BYTES + G3_W_BYTES;
@@ -253,7 +261,8 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
     const int kb = K / 4;
     const int steps = K / G3_BK;
-    const float bt = y ? *beta : 0.0f;
+    const bool want_cf = EPI != 0 || y != nullptr;      /* the fused epilogues always rescale */
+    const float bt = want_cf ? *beta : 0.0f;
 
     /* XCD-aware tile order: workgroup L runs on XCD L%8.  The tile grid is cut
      * into gm x gn = 8 rectangular regions, one per XCD, narrow enough in M that
@@ -294,7 +303,10 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         const int u = (lane & 1) ^ ((lane >> 4) & 1);
 #pragma unroll
         for (int j = 0; j < W_LOADS; ++j) {
-            int n = n0 + (j * NW + wave) * 32 + (lane >> 1);
+            const int trow = (j * NW + wave) * 32 + (lane >> 1);        /* row of the weight tile */
+            int n = n0 + trow;
+            if (EPI == 2)   /* tile rows [64w, 64w+32) = gate rows, [64w+32, 64w+64) = the matching up rows */
+                n = ((trow >> 5) & 1) * (N / 2) + tn * (BN / 2) + (trow >> 6) * 32 + (trow & 31);
             if (n >= N) n = N - 1;
             wsrc[j] = packed + (int64_t)n * kb + u * 16;
         }
@@ -303,7 +315,7 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         if (tid < G3_BM) {
             const int m = m0 + tid;
             row_rs = m < M ? rowsum[m] : 0;
-            row_cf = (y && m < M) ? bt * scale[m] : 0.0f;
+            row_cf = (want_cf && m < M) ? bt * scale[m] : 0.0f;
         }
     };
     auto issue = [&](int kk, int buf) {
@@ -393,6 +405,7 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
             setup(tm2, tn2);
             for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
         }
+        if constexpr (EPI == 0) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -435,6 +448,87 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                     }
                 }
             }
+        } else {
+            /* fused producer epilogue: glue value t, its bf16 narrowing (the next BitLinear's input
+             * before quantisation) and the row maximum of |bf16(t)|: over the lane's columns, then over
+             * the 32 lanes of a half wave (butterfly), then one atomic max per row on the float bits
+             * (non-negative floats order like integers, so the result does not depend on the order) */
+            const int NOUT = EPI == 2 ? N / 2 : N;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    float rres[4][NI];
+                    if (EPI == 1) {
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4) {
+                            const int m = m0 + wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+#pragma unroll
+                            for (int ni = 0; ni < NI; ++ni) {
+                                const int n = n0 + wn0 + ni * 32 + l32;
+                                rres[v4][ni] = (m < M && n < N) ? residual[(int64_t)m * N + n] : 0.0f;
+                            }
+                        }
+                    }
+                    float rowmax[4];
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        const int v = vq * 4 + v4;
+                        const int ml = wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+                        const int m = m0 + ml;
+                        float mx = 0.0f;
+                        if (m < M) {
+                            const int rs = rs_s[ml];
+                            const float c = cf_s[ml];
+                            if (EPI == 1) {
+#pragma unroll
+                                for (int ni = 0; ni < NI; ++ni) {
+                                    const int n = n0 + wn0 + ni * 32 + l32;
+                                    if (n < N) {
+                                        const int val = C[mi][ni][v] - rs;
+                                        if (acc) acc[(int64_t)m * N + n] = val;
+                                        const float t = (float)val * c;
+                                        const float o = rres[v4][ni] + t;
+                                        if (y) __builtin_nontemporal_store(o, y + (int64_t)m * N + n);
+                                        const uint32_t bits = bl_f32_to_bf16(o);
+                                        xb[(int64_t)m * NOUT + n] = (uint16_t)bits;
+                                        mx = fmaxf(mx, fabsf(bl_bf16_to_f32(bits)));
+                                    }
+                                }
+                            } else {
+                                const int j = tn * (BN / 2) + wn0 / 2 + l32;     /* column of the gated output */
+                                if (j < NOUT) {
+                                    const int vg = C[mi][0][v] - rs, vu = C[mi][NI - 1][v] - rs;
+                                    if (acc) {
+                                        acc[(int64_t)m * N + j] = vg;
+                                        acc[(int64_t)m * N + NOUT + j] = vu;
+                                    }
+                                    const float g = (float)vg * c, u = (float)vu * c;
+                                    const float r = fmaxf(g, 0.0f);
+                                    const float r2 = r * r;
+                                    const float o = r2 * u;
+                                    if (y) __builtin_nontemporal_store(o, y + (int64_t)m * NOUT + j);
+                                    const uint32_t bits = bl_f32_to_bf16(o);
+                                    xb[(int64_t)m * NOUT + j] = (uint16_t)bits;
+                                    mx = fmaxf(mx, fabsf(bl_bf16_to_f32(bits)));
+                                }
+                            }
+                        }
+                        rowmax[v4] = mx;
+                    }
+#pragma unroll
+                    for (int off = 1; off < 32; off <<= 1)
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4) rowmax[v4] = fmaxf(rowmax[v4], __shfl_xor(rowmax[v4], off));
+                    if (l32 == 0) {
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4) {
+                            const int m = m0 + wm0 + mi * 32 + vq * 8 + h * 4 + v4;
+                            if (m < M) atomicMax(absmax + m, __float_as_int(rowmax[v4]));
+                        }
+                    }
+                }
+        }
         if (vb2 < 0) break;
         vb = vb2;
         tm = tm2;
@@ -444,20 +538,27 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
     }
 }
 
-template <int BM, int BN, int STAGES, int WM, int WN>
+/* Outputs of the fused producer epilogues (device pointers; see bl_gemm_tile256). */
+struct bl_epi_args {
+    uint16_t* xb;
+    int* absmax;
+};
+
+template <int BM, int BN, int STAGES, int WM, int WN, int EPI = 0>
 static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, const int8_t* q, const float* scale,
                                   const int32_t* rowsum, int M, int N, int K, const float* residual,
-                                  int32_t* acc, float* y, hipStream_t st) {
+                                  int32_t* acc, float* y, hipStream_t st, bl_epi_args ep = bl_epi_args{nullptr, nullptr}) {
     constexpr int G3_BM = BM;
     constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4) + BM * 8;
-    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN>;
+    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN, EPI>;
     static std::atomic<bool> attr_set;
     if (!attr_set.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return BL_ERR_HIP;
         attr_set.store(true, std::memory_order_release);
     }
-    const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = (N + BN - 1) / BN;
+    /* the gate epilogue's tile holds 64 gate rows and the 64 matching up rows: N/2 / 64 column tiles */
+    const int tiles_m = (M + G3_BM - 1) / G3_BM, tiles_n = EPI == 2 ? (N / 2 + BN / 2 - 1) / (BN / 2) : (N + BN - 1) / BN;
     /* rows of activations per XCD region: at most ~1.5 MB of int8 (measured, medians of six
      * interleaved rounds at M = 2048: +7 % on the 13824-wide shape against whole-M regions,
      * equal on the others) */
@@ -481,7 +582,7 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     }
     if (blocks > vgrid) blocks = vgrid;
     kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, vgrid,
-                                            residual, acc, y);
+                                            residual, acc, y, ep.xb, ep.absmax);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
@@ -557,6 +658,30 @@ extern "C" bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, in
                                     const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
                                     int32_t* acc, float* y, void* workspace, bl_stream s) {
     return bl_gemm_w158a8_res(packed, beta, layout, q, scale, rowsum, M, N, K, nullptr, acc, y, workspace, s);
+}
+
+/* Prefill product with a fused producer epilogue (see bl_gemm_tile256, EPI = 1 and 2). */
+extern "C" bl_status bl_gemm_w158a8_fused(const uint8_t* packed, const float* beta, int layout, const int8_t* q,
+                                          const float* scale, const int32_t* rowsum, int64_t M, int64_t N, int64_t K,
+                                          const bl_gemm_epilogue* ep, int32_t* acc, bl_stream s) {
+    if (!packed || !beta || !q || !scale || !rowsum || !ep) return BL_ERR_NULL;
+    if (!ep->x_bf16 || !ep->absmax) return BL_ERR_NULL;
+    if (ep->kind != BL_EPI_RESIDUAL && ep->kind != BL_EPI_RELU2_GATE) return BL_ERR_VALUE;
+    if (ep->kind == BL_EPI_RESIDUAL && !ep->residual) return BL_ERR_NULL;
+    if (M < 1 || M > BL_MAX_DIM || !bl_shape_ok(N, K) || K % G3_BK != 0) return BL_ERR_SHAPE;
+    if (ep->kind == BL_EPI_RELU2_GATE && N % 128 != 0) return BL_ERR_SHAPE;   /* N/2 gate columns in tiles of 64 */
+    if (layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (!bl_aligned(packed, 16) || !bl_aligned(q, 16) || !bl_aligned(acc, 4) || !bl_aligned(ep->y, 4) ||
+        !bl_aligned(scale, 4) || !bl_aligned(beta, 4) || !bl_aligned(rowsum, 4) || !bl_aligned(ep->residual, 4) ||
+        !bl_aligned(ep->x_bf16, 2) || !bl_aligned(ep->absmax, 4))
+        return BL_ERR_ALIGN;
+    const bl_epi_args ea = {ep->x_bf16, (int*)ep->absmax};
+    hipStream_t st = (hipStream_t)s;
+    if (ep->kind == BL_EPI_RESIDUAL)
+        return launch_tile256_t<128, 128, 2, 2, 2, 1>(packed, beta, q, scale, rowsum, (int)M, (int)N, (int)K,
+                                                      ep->residual, acc, ep->y, st, ea);
+    return launch_tile256_t<128, 128, 2, 2, 2, 2>(packed, beta, q, scale, rowsum, (int)M, (int)N, (int)K, nullptr, acc,
+                                                  ep->y, st, ea);
 }
 
 /* ---- entry point that allocates nothing ---------------------------------------------------

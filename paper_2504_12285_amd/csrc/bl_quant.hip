@@ -166,6 +166,54 @@ extern "C" bl_status bl_quant_act_ex(const bl_producer* prod, int64_t M, int64_t
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
+/* Quantiser behind a fused producer epilogue: the bf16 row and its absmax already exist, so one
+ * pass quantises.  absmax[m] holds the float bits of max_k |x|; it is read by every thread and then
+ * cleared, so that the next product's epilogue can fold its maxima into it again. */
+__global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows_absmax(const uint4* __restrict__ X, int K8,
+                                                                       int* __restrict__ absmax,
+                                                                       uint2* __restrict__ q, float* __restrict__ scale,
+                                                                       int32_t* __restrict__ rowsum) {
+    __shared__ int ssum[QUANT_THREADS / BL_WAVE];
+    const int64_t m = blockIdx.x;
+    const uint4* x = X + m * K8;
+    uint2* qo = q + m * K8;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const float gamma = __int_as_float(absmax[m]);
+    const float g = fmaxf(gamma, 1e-5f);
+    const float inv = bl_div_rn(127.0f, g);
+    int sum = 0;
+    for (int i = threadIdx.x; i < K8; i += QUANT_THREADS) {
+        uint2 o;
+        sum += bl_quant8(x[i], inv, &o);
+        qo[i] = o;
+    }
+    sum = bl_wave_sum(sum);
+    if (lane == 0) ssum[w] = sum;
+    __syncthreads();                      /* every thread has read absmax[m] */
+    if (threadIdx.x == 0) {
+        absmax[m] = 0;
+        scale[m] = bl_div_rn(g, 127.0f);
+        if (rowsum) {
+            int t = 0;
+#pragma unroll
+            for (int i = 0; i < QUANT_THREADS / BL_WAVE; ++i) t += ssum[i];
+            rowsum[m] = t;
+        }
+    }
+}
+
+extern "C" bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int64_t K, int8_t* q,
+                                          float* scale, int32_t* rowsum, bl_stream s) {
+    if (!X || !absmax || !q || !scale) return BL_ERR_NULL;
+    if (M < 1 || M > BL_MAX_DIM || K < 64 || K % 64 != 0 || K > BL_MAX_DIM) return BL_ERR_SHAPE;
+    if (!bl_aligned(X, 16) || !bl_aligned(q, 16) || !bl_aligned(scale, 4) || !bl_aligned(rowsum, 4) ||
+        !bl_aligned(absmax, 4))
+        return BL_ERR_ALIGN;
+    bl_quant_rows_absmax<<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>((const uint4*)X, (int)(K / 8), (int*)absmax,
+                                                                           (uint2*)q, scale, rowsum);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
 extern "C" bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K, int8_t* q, float* scale,
                                        int32_t* rowsum, bl_stream s) {
     if (!X || !q || !scale) return BL_ERR_NULL;

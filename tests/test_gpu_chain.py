@@ -248,6 +248,74 @@ def test_config4_full_stack_decode_and_prefill(bl, chain):
         del gw, ow, wts, rec_p, rec_d
 
 
+# ------------------------------------------------- fused producer epilogues of the prefill product
+@pytest.mark.parametrize("M,N,K", [(150, 384, 1280), (257, 2560, 2560), (64, 128, 128)])
+def test_prefill_epilogue_residual(bl, M, N, K):
+    """Product + residual + bf16 narrowing + row absmax in the GEMM epilogue, then the one-pass
+    quantiser: every output bit for bit against the oracle's separate steps."""
+    rng = np.random.default_rng(31)
+    Wt = synth.uniform_i8(80, (N, K), -1, 1)
+    beta = np.float32(0.0173)
+    q = synth.uniform_i8(81, (M, K), -127, 127)
+    scale = (rng.uniform(0.5, 2.0, size=M) / 127.0).astype(np.float32)
+    rowsum = q.astype(np.int32).sum(axis=1).astype(np.int32)
+    res = (rng.standard_normal((M, N)) * 5).astype(np.float32)
+    acc_o = oracle.matmul_i32(q, Wt)
+    t_o = oracle.chain_residual(res, oracle.rescale(acc_o, beta, scale))
+    xb_o = oracle.f32_to_bf16(t_o)
+    dev = "cuda:0"
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+    y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    xb = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    absmax = torch.zeros(M, dtype=torch.float32, device=dev)
+    bl.bl_gemm_w158a8_fused(to_dev(oracle.pack(Wt, 1)), to_dev(np.array([beta], dtype=np.float32)), 1, to_dev(q),
+                            to_dev(scale), to_dev(rowsum), N, bl.BL_EPI_RESIDUAL, xb, absmax, residual=to_dev(res),
+                            y=y, acc=acc)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_o)
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), t_o.view(np.uint32))
+    assert np.array_equal(xb.view(torch.int16).cpu().numpy().view(np.uint16), xb_o)
+    want_max = np.abs(synth.bf16_bits_to_f32(xb_o)).max(axis=1)
+    assert np.array_equal(absmax.cpu().numpy(), want_max)
+    q2, s2, r2 = bl.bl_quant_from_absmax(xb, absmax)
+    torch.cuda.synchronize()
+    q_o, s_o, r_o = oracle.quant_act(xb_o)
+    assert np.array_equal(q2.cpu().numpy(), q_o)
+    assert np.array_equal(s2.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
+    assert np.array_equal(r2.cpu().numpy(), r_o)
+    assert not absmax.cpu().numpy().any()          # cleared for the next product
+
+
+@pytest.mark.parametrize("M,F,K", [(130, 192, 1280), (300, 6912, 2560), (5, 64, 128)])
+def test_prefill_epilogue_relu2_gate(bl, M, F, K):
+    """[gate | up] product with the squared-ReLU gate, bf16 narrowing and row absmax in the epilogue."""
+    rng = np.random.default_rng(32)
+    N = 2 * F
+    Wt = synth.uniform_i8(82, (N, K), -1, 1)
+    beta = np.float32(0.0161)
+    q = synth.uniform_i8(83, (M, K), -127, 127)
+    scale = (rng.uniform(0.5, 2.0, size=M) / 127.0 / 40.0).astype(np.float32)
+    rowsum = q.astype(np.int32).sum(axis=1).astype(np.int32)
+    acc_o = oracle.matmul_i32(q, Wt)
+    gu_o = oracle.rescale(acc_o, beta, scale)
+    f_o = oracle.chain_relu2_gate(gu_o)
+    dev = "cuda:0"
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+    xb = torch.empty((M, F), dtype=torch.bfloat16, device=dev)
+    absmax = torch.zeros(M, dtype=torch.float32, device=dev)
+    bl.bl_gemm_w158a8_fused(to_dev(oracle.pack(Wt, 1)), to_dev(np.array([beta], dtype=np.float32)), 1, to_dev(q),
+                            to_dev(scale), to_dev(rowsum), N, bl.BL_EPI_RELU2_GATE, xb, absmax, acc=acc)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_o)
+    assert np.array_equal(xb.view(torch.int16).cpu().numpy().view(np.uint16), f_o)
+    assert np.array_equal(absmax.cpu().numpy(), np.abs(synth.bf16_bits_to_f32(f_o)).max(axis=1))
+    q2, s2, r2 = bl.bl_quant_from_absmax(xb, absmax)
+    torch.cuda.synchronize()
+    q_o, s_o, r_o = oracle.quant_act(f_o)
+    assert np.array_equal(q2.cpu().numpy(), q_o) and np.array_equal(r2.cpu().numpy(), r_o)
+    assert np.array_equal(s2.cpu().numpy().view(np.uint32), s_o.view(np.uint32))
+
+
 @pytest.mark.timeout(3000)
 @pytest.mark.skipif(__import__("os").environ.get("BL_SKIP_FULL_CONFIG4") == "1",
                     reason="8.5e12 oracle multiply-adds (80 s on the 16 host cores of a GPU box): skipped on request")
