@@ -23,15 +23,20 @@
  *   contraction    acc[m][n] = sum_k q[m][k] * Wt[n][k]      (exact, int32)
  *   rescale        y[m][n] = (float)acc[m][n] * (beta * scale[m])
  *
- * PACKED LAYOUTS.  A packed matrix is N*K/4 bytes, 2 bits per weight.
- *   BL_LAYOUT_ROWMAJOR (0): byte index b = n*(K/4) + k/4 ; weight k occupies
+ * PACKED LAYOUTS.  2 bits per weight.  Rows are padded: Kp = bl_padded_k(K) (K rounded up to
+ * a multiple of 64) weights per row and Np = N rounded up to a multiple of 4 rows; every field
+ * outside the N x K matrix holds code 1 (weight 0).  A packed matrix is Np*Kp/4 bytes
+ * (= N*K/4 when K % 64 == 0 and N % 4 == 0).
+ *   BL_LAYOUT_ROWMAJOR (0): byte index b = n*(Kp/4) + k/4 ; weight k occupies
  *     bits [2*(k%4), 2*(k%4)+1] of byte b (lowest bits = lowest k).
  *   BL_LAYOUT_K16 (1): same byte count and the same 4-byte word per group of
  *     16 consecutive k of a row, but inside the word the two index digits are
  *     swapped: with i = k % 16, weight k occupies bits [2*(i/4), 2*(i/4)+1] of
- *     byte n*(K/4) + (k/16)*4 + i%4.  (So `(word >> 2s) & 0x03030303` yields the
+ *     byte n*(Kp/4) + (k/16)*4 + i%4.  (So `(word >> 2s) & 0x03030303` yields the
  *     codes of k = 4s..4s+3 as four bytes in natural order: the kernels' native
  *     form.  Layout 0 is supported by permuting the activation bytes instead.)
+ * QUANTISED ACTIVATIONS are int8 [M][Kp]: leading dimension Kp, zeros in columns K..Kp-1 (what
+ * bl_quant_act_int8 writes), so that a padded weight meets a zero.  Outputs are [M][N].
  *
  * CONVENTIONS.  Every pointer is a DEVICE pointer owned by the caller unless a
  * comment says "host".  The library allocates and frees nothing; all work is
@@ -39,9 +44,11 @@
  * the null stream) and no call synchronises.  Argument errors are found on the
  * host before any HIP call and reported as a status code (no exceptions, no
  * global error state; the only process-wide state is the test hook below).  Preconditions on
- * every matrix: N >= 4, N % 4 == 0,
- * K >= 64, K % 64 == 0; `packed` and `q` 16-byte aligned; otherwise
- * BL_ERR_SHAPE / BL_ERR_ALIGN.  Non-finite activations or weights: undefined.
+ * every matrix: 1 <= N, K <= 2^24; `packed` and `q` 16-byte aligned; otherwise
+ * BL_ERR_SHAPE / BL_ERR_ALIGN.  Entry points that read bf16 or fp32 activations inside a
+ * product kernel (fused producers, epilogues, bl_stack_* with X) need K % 64 == 0 and say so;
+ * a ragged K goes through bl_quant_act_int8 and the int8 inputs of the products.
+ * Non-finite activations or weights: undefined.
  * There is no bias argument (the report removes all biases, Section 2).
  */
 #ifndef BITLINEAR_H
@@ -76,9 +83,13 @@ enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3 };
 int         bl_version(void);
 const char* bl_status_str(int status);
 
-/* Bytes of a packed N x K matrix (N*K/4 for every layout); 0 if the shape or
- * layout is not permitted.  Host-only.  (Section 5.1: 4 values per byte.) */
+/* Bytes of a packed N x K matrix (Np*Kp/4 for every layout, see PACKED LAYOUTS); 0 if the
+ * shape or layout is not permitted.  Host-only.  (Section 5.1: 4 values per byte.) */
 size_t bl_packed_bytes(int64_t N, int64_t K, int layout);
+
+/* Kp: K rounded up to a multiple of 64, the row length of packed weights and the leading
+ * dimension of quantised activations; 0 if K is out of range.  Host-only. */
+int64_t bl_padded_k(int64_t K);
 
 /* Bytes of device scratch the given op needs for the given shape (may be 0).
  * The workspace is caller-allocated, 256-byte aligned, and may be reused by
@@ -106,8 +117,10 @@ bl_status bl_unpack_ternary(const uint8_t* packed, int64_t N, int64_t K, int lay
 
 /* Per-token absmax int8 activation quantisation (Section 2, "Activation
  * Quantization").
- *   X      device bf16 [M][K] row-major (raw 16-bit patterns).
- *   q      device out int8 [M][K];  scale device out fp32 [M] (= max(gamma,1e-5)/127);
+ *   X      device bf16 [M][K] row-major (raw 16-bit patterns), 16-byte aligned
+ *          (2-byte aligned is enough when K % 64 != 0).
+ *   q      device out int8 [M][Kp], zeros in the padding;
+ *   scale  device out fp32 [M] (= max(gamma,1e-5)/127);
  *   rowsum device out int32 [M], may be NULL.          M >= 1. */
 bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K,
                             int8_t* q, float* scale, int32_t* rowsum, bl_stream s);
@@ -115,7 +128,7 @@ bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K,
 /* W1.58A8 product for decode batches, 1 <= M <= 64 (Section 5.1).  Streams the
  * packed weights once per call.
  *   packed/beta/layout  as written by bl_pack_ternary.
- *   q      device int8 [M][K];  scale device fp32 [M] (needed only if y != NULL).
+ *   q      device int8 [M][Kp];  scale device fp32 [M] (needed only if y != NULL).
  *   rowsum device int32 [M] or NULL (this call derives what it needs from q).
  *   acc    device out int32 [M][N] or NULL;  y device out fp32 [M][N] or NULL;
  *          at least one of the two must be non-NULL.
@@ -138,7 +151,7 @@ bl_status bl_gemm_w158a8(const uint8_t* packed, const float* beta, int layout,
                          int64_t M, int64_t N, int64_t K,
                          int32_t* acc, float* y, void* workspace, bl_stream s);
 
-/* Fused BitLinear for decode, 1 <= M <= 16, K <= 8192, M*(K+16) <= 96 KiB: the per-token absmax
+/* Fused BitLinear for decode, 1 <= M <= 16, K <= 8192, K % 64 == 0, M*(K+16) <= 96 KiB: the per-token absmax
  * int8 quantiser (Section 2) runs inside the product kernel (Section 5.1), so
  * one launch takes bf16 activations to fp32 outputs.  Same arithmetic, bit for
  * bit, as bl_quant_act_int8 followed by bl_gemv_w158a8.
@@ -214,14 +227,15 @@ typedef struct {
  * in one kernel launch, e.g. the four BitLinear shapes of a layer on
  * independent inputs.  Results are identical to separate calls; the point is
  * one launch and one continuous weight stream instead of four.
- * Limits: a product with a fused input (X or prod) needs M <= 16 and
- * M*(K+16) <= 96 KiB; a product with int8 input (q) takes M <= 64.
+ * Limits: a product with a fused input (X or prod) needs M <= 16, K % 64 == 0 and
+ * M*(K+16) <= 96 KiB; a product with int8 input (q, [M][Kp]) takes M <= 64 and any K.
  * Errors: BL_ERR_SHAPE outside these limits or for count outside 1..4. */
 bl_status bl_bitlinear_decode_group(const bl_decode_desc* descs, int count, int layout, int64_t M, bl_stream s);
 
 /* Producer + per-token absmax int8 quantiser for prefill (Section 2): like
  * bl_quant_act_int8, but the bf16 activations come from `prod` (HOST pointer to
- * the descriptor; its tensors are device memory).  One workgroup per token. */
+ * the descriptor; its tensors are device memory).  One workgroup per token.
+ * Needs K % 64 == 0 (BL_ERR_SHAPE otherwise). */
 bl_status bl_quant_act_ex(const bl_producer* prod, int64_t M, int64_t K,
                           int8_t* q, float* scale, int32_t* rowsum, bl_stream s);
 
@@ -262,7 +276,7 @@ bl_status bl_gemm_w158a8_fused(const uint8_t* packed, const float* beta, int lay
                                int64_t M, int64_t N, int64_t K, const bl_gemm_epilogue* ep /* HOST */,
                                int32_t* acc, bl_stream s);
 /* One-pass quantiser for rows whose absmax is already known: like bl_quant_act_int8 with
- * gamma = absmax[m] given; clears absmax[m] to 0 afterwards. */
+ * gamma = absmax[m] given; clears absmax[m] to 0 afterwards.  Needs K % 64 == 0. */
 bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int64_t K,
                                int8_t* q, float* scale, int32_t* rowsum, bl_stream s);
 
@@ -278,6 +292,7 @@ bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int6
  * workgroup per such entry, into scratch inside `table`; the same launch computes a missing
  * rowsum of an int8 entry); int8 entries are streamed as they are.
  * The products of one table are INDEPENDENT: none may read what another writes.
+ * Entries with a fused input need K % 64 == 0; int8 entries (q of Kp bytes) take any K.
  *   bl_stack_table_bytes  device bytes `table` needs for these descriptors (HOST array): the
  *                         table itself plus the scratch for quantised rows.  0: bad count or K.
  *   bl_stack_build        setup call: checks the descriptors (HOST array), lays the work out

@@ -132,6 +132,31 @@ def pack(Wt, layout=0):
     return out
 
 
+def padded_k(K):
+    """Row length of the packed form and of the quantised activations: K rounded up to a multiple of 64."""
+    return -(-int(K) // 64) * 64
+
+
+def pack_padded(Wt, layout=0):
+    """Packed form of any N x K ternary matrix: the library's format (its own, like layout 1) pads every
+    row with weight 0 to padded_k(K) weights and the row count with all-zero rows to a multiple of 4,
+    then packs as above (Section 5.1).  Equal to pack() when nothing needs padding."""
+    Wt = _c(Wt, np.int8)
+    N, K = Wt.shape
+    P = np.zeros((-(-N // 4) * 4, padded_k(K)), dtype=np.int8)
+    P[:N, :K] = Wt
+    return pack(P, layout)
+
+
+def pad_q(q):
+    """Quantised activations in the library's [M][padded_k(K)] form: zeros behind column K."""
+    q = _c(q, np.int8)
+    M, K = q.shape
+    P = np.zeros((M, padded_k(K)), dtype=np.int8)
+    P[:, :K] = q
+    return P
+
+
 def unpack(packed, N, K, layout=0):
     """Inverse of pack; returns (Wt int8 [N][K], number of invalid codes)."""
     packed = _c(packed, np.uint8)

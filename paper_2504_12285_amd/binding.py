@@ -21,6 +21,7 @@ SIGNATURES = {
     "bl_version": (_ci, []),
     "bl_status_str": (ctypes.c_char_p, [_ci]),
     "bl_packed_bytes": (_sz, [_i64, _i64, _ci]),
+    "bl_padded_k": (_i64, [_i64]),
     "bl_workspace_bytes": (_sz, [_ci, _i64, _i64, _i64]),
     "bl_pack_ternary": (_ci, [_vp, _ci, _i64, _i64, _ci, _vp, _vp, _vp, _vp]),
     "bl_unpack_ternary": (_ci, [_vp, _i64, _i64, _ci, _vp, _vp, _vp]),
@@ -134,6 +135,10 @@ def bl_packed_bytes(N, K, layout=BL_LAYOUT_K16):
     return load().bl_packed_bytes(N, K, layout)
 
 
+def bl_padded_k(K):
+    return load().bl_padded_k(K)
+
+
 def bl_workspace_bytes(op, M, N, K):
     return load().bl_workspace_bytes(op, M, N, K)
 
@@ -179,11 +184,12 @@ def bl_unpack_ternary(packed, N, K, layout=BL_LAYOUT_K16):
 
 
 def bl_quant_act_int8(X, want_rowsum=True):
-    """X: cuda bfloat16 [M][K].  Returns (q int8 [M][K], scale fp32 [M], rowsum int32 [M] or None)."""
+    """X: cuda bfloat16 [M][K].  Returns (q int8 [M][Kp] with Kp = bl_padded_k(K) and zeros in the padding,
+    scale fp32 [M], rowsum int32 [M] or None)."""
     import torch
     assert X.is_cuda and X.is_contiguous() and X.dtype == torch.bfloat16
     M, K = X.shape
-    q = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    q = torch.empty((M, bl_padded_k(K)), dtype=torch.int8, device=X.device)
     scale = torch.empty(M, dtype=torch.float32, device=X.device)
     rowsum = torch.empty(M, dtype=torch.int32, device=X.device) if want_rowsum else None
     _check(load().bl_quant_act_int8(_ptr(X), M, K, _ptr(q), _ptr(scale), _ptr(rowsum), _stream()),
@@ -191,9 +197,11 @@ def bl_quant_act_int8(X, want_rowsum=True):
     return q, scale, rowsum
 
 
-def _matmul(fn_name, op, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y, acc, y, workspace):
+def _matmul(fn_name, op, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y, acc, y, workspace, K=None):
     import torch
-    M, K = q.shape
+    M = q.shape[0]
+    K = q.shape[1] if K is None else K          # q is [M][Kp]: pass the true K of a ragged matrix explicitly
+    assert q.shape[1] == bl_padded_k(K)
     assert q.is_cuda and q.is_contiguous() and q.dtype == torch.int8
     if want_acc and acc is None:
         acc = torch.empty((M, N), dtype=torch.int32, device=q.device)
@@ -208,17 +216,17 @@ def _matmul(fn_name, op, packed, beta, layout, q, scale, rowsum, N, want_acc, wa
 
 
 def bl_gemv_w158a8(packed, beta, layout, q, scale, rowsum, N, want_acc=True, want_y=True,
-                   acc=None, y=None, workspace=None):
+                   acc=None, y=None, workspace=None, K=None):
     """Decode product, 1 <= M <= 64.  Returns (acc int32 [M][N] or None, y fp32 [M][N] or None)."""
     return _matmul("bl_gemv_w158a8", BL_OP_GEMV, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y,
-                   acc, y, workspace)
+                   acc, y, workspace, K)
 
 
 def bl_gemm_w158a8(packed, beta, layout, q, scale, rowsum, N, want_acc=True, want_y=True,
-                   acc=None, y=None, workspace=None):
+                   acc=None, y=None, workspace=None, K=None):
     """Prefill product, any M.  Returns (acc, y) like bl_gemv_w158a8."""
     return _matmul("bl_gemm_w158a8", BL_OP_GEMM, packed, beta, layout, q, scale, rowsum, N, want_acc, want_y,
-                   acc, y, workspace)
+                   acc, y, workspace, K)
 
 
 def bl_bitlinear_decode(packed, beta, layout, X, N, want_acc=False, want_y=True, want_q=False, acc=None, y=None):

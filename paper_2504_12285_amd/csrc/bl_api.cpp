@@ -22,8 +22,10 @@ extern "C" const char* bl_status_str(int status) {
 extern "C" size_t bl_packed_bytes(int64_t N, int64_t K, int layout) {
     if (!bl_shape_ok(N, K)) return 0;
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return 0;
-    return (size_t)(N * K / 4);
+    return (size_t)(bl_npad(N) * bl_kpad(K) / 4);
 }
+
+extern "C" int64_t bl_padded_k(int64_t K) { return K >= 1 && K <= BL_MAX_DIM ? bl_kpad(K) : 0; }
 
 extern "C" size_t bl_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
     (void)N;

@@ -650,7 +650,7 @@ extern "C" bl_status bl_gemm_w158a8_res(const uint8_t* packed, const float* beta
     if (!bl_aligned(packed, 16) || !bl_aligned(q, 16) || !bl_aligned(acc, 4) || !bl_aligned(y, 4) ||
         !bl_aligned(scale, 4) || !bl_aligned(beta, 4) || !bl_aligned(rowsum, 4) || !bl_aligned(residual, 4))
         return BL_ERR_ALIGN;
-    return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, residual, acc, y, workspace,
+    return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, bl_kpad(K), residual, acc, y, workspace,
                             (hipStream_t)s);
 }
 
@@ -668,7 +668,7 @@ extern "C" bl_status bl_gemm_w158a8_fused(const uint8_t* packed, const float* be
     if (!ep->x_bf16 || !ep->absmax) return BL_ERR_NULL;
     if (ep->kind != BL_EPI_RESIDUAL && ep->kind != BL_EPI_RELU2_GATE) return BL_ERR_VALUE;
     if (ep->kind == BL_EPI_RESIDUAL && !ep->residual) return BL_ERR_NULL;
-    if (M < 1 || M > BL_MAX_DIM || !bl_shape_ok(N, K) || K % G3_BK != 0) return BL_ERR_SHAPE;
+    if (M < 1 || M > BL_MAX_DIM || !bl_shape_ok(N, K) || K % G3_BK != 0 || N % 4 != 0) return BL_ERR_SHAPE;
     if (ep->kind == BL_EPI_RELU2_GATE && N % 128 != 0) return BL_ERR_SHAPE;   /* N/2 gate columns in tiles of 64 */
     if (layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(packed, 16) || !bl_aligned(q, 16) || !bl_aligned(acc, 4) || !bl_aligned(ep->y, 4) ||
@@ -725,5 +725,5 @@ extern "C" bl_status bl_gemm_w158a8_noalloc(const uint8_t* packed, const float* 
     if (st != BL_OK) return st;
     /* the row-sum kernel overwrites entries 0..M-1 and nothing reads beyond them, so what an
      * earlier (larger) call left behind needs no clearing */
-    return bl_gemm_dispatch(packed, beta, layout, q, scale, nullptr, M, N, K, nullptr, acc, y, rs, (hipStream_t)s);
+    return bl_gemm_dispatch(packed, beta, layout, q, scale, nullptr, M, N, bl_kpad(K), nullptr, acc, y, rs, (hipStream_t)s);
 }

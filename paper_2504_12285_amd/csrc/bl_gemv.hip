@@ -821,6 +821,7 @@ extern "C" bl_status bl_gemv_w158a8(const uint8_t* packed, const float* beta, in
         !bl_aligned(scale, 4) || !bl_aligned(beta, 4) || !bl_aligned(rowsum, 4))
         return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
+    K = bl_kpad(K);                 /* row length of the packed weights and of q */
     if (K > 8192)
         return bl_gemm_dispatch(packed, beta, layout, q, scale, rowsum, M, N, K, nullptr, acc, y, workspace, st);
 
@@ -840,7 +841,7 @@ static bl_status check_decode_desc(const bl_decode_desc& d, int64_t M, int layou
     if (!d.acc && !d.y) return BL_ERR_NULL;
     if (!fused && d.y && !d.scale) return BL_ERR_NULL;
     if (M < 1 || M > 64 || !bl_shape_ok(d.N, d.K) || d.K > 8192) return BL_ERR_SHAPE;
-    if (fused && (M > 16 || M * (d.K + BL_MMA_PAD) > 96 * 1024)) return BL_ERR_SHAPE;
+    if (fused && (M > 16 || d.K % 64 != 0 || M * (d.K + BL_MMA_PAD) > 96 * 1024)) return BL_ERR_SHAPE;
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
         !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||
@@ -865,7 +866,7 @@ extern "C" bl_status bl_bitlinear_decode_group(const bl_decode_desc* descs, int 
         if (P.fused && !bl_make_prod(d.prod, d.X, d.K, &P.prod)) return BL_ERR_VALUE;
         P.packed = (const bl_v4i*)d.packed; P.q = P.fused ? nullptr : d.q; P.beta = d.beta; P.scale = d.scale;
         P.rowsum = d.rowsum; P.acc = d.acc; P.y = d.y; P.q_out = d.q_out; P.scale_out = d.scale_out;
-        P.N = (int)d.N; P.K = (int)d.K; P.layout = layout; P.ksplit = 1; P.fixed_scale = d.fixed_scale;
+        P.N = (int)d.N; P.K = (int)bl_kpad(d.K); P.layout = layout; P.ksplit = 1; P.fixed_scale = d.fixed_scale;
         P.residual = d.residual;
     }
     return bl_gemv_launch_group(grp, (int)M, (hipStream_t)s);

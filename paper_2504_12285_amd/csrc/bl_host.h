@@ -9,8 +9,12 @@
 #define BL_MAX_DIM ((int64_t)1 << 24)  /* upper bound on M, N and K                 */
 
 static inline bool bl_shape_ok(int64_t N, int64_t K) {
-    return N >= 4 && N % 4 == 0 && K >= 64 && K % 64 == 0 && N <= BL_MAX_DIM && K <= BL_MAX_DIM;
+    return N >= 1 && K >= 1 && N <= BL_MAX_DIM && K <= BL_MAX_DIM;
 }
+/* Padded sizes of the packed matrix and of the quantised activations (bitlinear.h, PACKED LAYOUTS). */
+static inline int64_t bl_kpad(int64_t K) { return (K + 63) / 64 * 64; }
+static inline int64_t bl_npad(int64_t N) { return (N + 3) / 4 * 4; }
+static inline bool bl_shape_unpadded(int64_t N, int64_t K) { return N % 4 == 0 && K % 64 == 0; }
 static inline bool bl_aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 /* Test hook (bl_debug_force_path): which decode kernel bl_gemv_launch_group takes.

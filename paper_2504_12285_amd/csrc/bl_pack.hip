@@ -118,6 +118,77 @@ __global__ __launch_bounds__(PACK_THREADS) void bl_unpack_kernel(const uint32_t*
     if (nbad) atomicAdd(bad, nbad);
 }
 
+/* ---- shapes with a ragged K (not a multiple of 64) or N (not a multiple of 4) ------------------
+ * Element-wise versions of the kernels above: the packed matrix has Np rows of Kp weights and
+ * every field outside the N x K matrix holds code 1 (weight 0). */
+__global__ __launch_bounds__(PACK_THREADS) void bl_abs_sum_partial_any(const float* __restrict__ W, int64_t count,
+                                                                        double* __restrict__ partial) {
+    __shared__ double red[PACK_THREADS];
+    const int64_t per = (count + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x;
+    const int64_t hi = lo + per < count ? lo + per : count;
+    double s = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += PACK_THREADS) s += (double)fabsf(W[i]);
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = PACK_THREADS / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+/* One thread = one packed word = 16 consecutive k of one padded row.  IN = 0: fp32 latent
+ * weights, ternarised here; IN = 1: int8 ternary weights. */
+template <int LAYOUT, int IN>
+__global__ __launch_bounds__(PACK_THREADS) void bl_pack_any(const void* __restrict__ Wv, const float* __restrict__ beta,
+                                                             int64_t N, int64_t K, int64_t wpr, int64_t words,
+                                                             uint32_t* __restrict__ packed) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const int64_t n = g / wpr, k0 = (g % wpr) * 16;
+    const float d = IN == 0 ? *beta + 1e-5f : 1.0f;
+    int c[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t k = k0 + i;
+        int t = 0;
+        if (n < N && k < K) {
+            if (IN == 0) {
+                float f = rintf(bl_div_rn(((const float*)Wv)[n * K + k], d));
+                f = fminf(fmaxf(f, -1.0f), 1.0f);
+                t = (int)f;
+            } else {
+                const int b = ((const int8_t*)Wv)[n * K + k];
+                t = b < -1 ? -1 : (b > 1 ? 1 : b);
+            }
+        }
+        c[i] = t + 1;
+    }
+    packed[g] = bl_code_word<LAYOUT>(c);
+}
+
+template <int LAYOUT>
+__global__ __launch_bounds__(PACK_THREADS) void bl_unpack_any(const uint32_t* __restrict__ packed, int64_t N, int64_t K,
+                                                               int64_t wpr, int64_t words, int8_t* __restrict__ Wt,
+                                                               int32_t* __restrict__ bad) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const int64_t n = g / wpr, k0 = (g % wpr) * 16;
+    if (n >= N) return;
+    const uint32_t w = packed[g];
+    int nbad = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = (int)((w >> bl_bitpos<LAYOUT>(i)) & 3u);
+        if (k0 + i < K) {
+            nbad += (c == 3);
+            Wt[n * K + k0 + i] = (int8_t)(c - 1);
+        }
+    }
+    if (nbad) atomicAdd(bad, nbad);
+}
+
 __global__ void bl_zero_i32(int32_t* p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -131,6 +202,26 @@ extern "C" bl_status bl_pack_ternary(const void* W, int in_kind, int64_t N, int6
     if (in_kind != BL_IN_FP32_LATENT && in_kind != BL_IN_INT8_TERNARY) return BL_ERR_VALUE;
     if (!bl_aligned(W, 16) || !bl_aligned(packed, 16) || !bl_aligned(beta, 4)) return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
+    if (!bl_shape_unpadded(N, K)) {
+        const int64_t wpr = bl_kpad(K) / 16, pwords = bl_npad(N) * wpr;
+        const unsigned pgrid = (unsigned)((pwords + PACK_THREADS - 1) / PACK_THREADS);
+        uint32_t* out = (uint32_t*)packed;
+        if (in_kind == BL_IN_FP32_LATENT) {
+            if (!workspace) return BL_ERR_WORKSPACE;
+            if (!bl_aligned(workspace, 8)) return BL_ERR_ALIGN;
+            double* partial = (double*)workspace;
+            const int64_t count = N * K;
+            const int np = (int)(count < BL_PACK_PARTIALS ? count : BL_PACK_PARTIALS);
+            bl_abs_sum_partial_any<<<np, PACK_THREADS, 0, st>>>((const float*)W, count, partial);
+            bl_abs_sum_final<<<1, PACK_THREADS, 0, st>>>(partial, np, (double)count, beta);
+            if (layout == 0) bl_pack_any<0, 0><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+            else bl_pack_any<1, 0><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+        } else {
+            if (layout == 0) bl_pack_any<0, 1><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+            else bl_pack_any<1, 1><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+        }
+        return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+    }
     const int64_t words = N * K / 16;
     const unsigned grid = (unsigned)((words + PACK_THREADS - 1) / PACK_THREADS);
     if (in_kind == BL_IN_FP32_LATENT) {
@@ -161,6 +252,14 @@ extern "C" bl_status bl_unpack_ternary(const uint8_t* packed, int64_t N, int64_t
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(packed, 16) || !bl_aligned(Wt, 16) || !bl_aligned(bad, 4)) return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
+    if (!bl_shape_unpadded(N, K)) {
+        const int64_t wpr = bl_kpad(K) / 16, pwords = bl_npad(N) * wpr;
+        const unsigned pgrid = (unsigned)((pwords + PACK_THREADS - 1) / PACK_THREADS);
+        bl_zero_i32<<<1, 64, 0, st>>>(bad, 1);
+        if (layout == 0) bl_unpack_any<0><<<pgrid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, N, K, wpr, pwords, Wt, bad);
+        else bl_unpack_any<1><<<pgrid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, N, K, wpr, pwords, Wt, bad);
+        return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+    }
     const int64_t words = N * K / 16;
     const unsigned grid = (unsigned)((words + PACK_THREADS - 1) / PACK_THREADS);
     bl_zero_i32<<<1, 64, 0, st>>>(bad, 1);

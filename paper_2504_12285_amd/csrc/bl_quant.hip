@@ -79,6 +79,53 @@ __global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows(const uint4* __re
     }
 }
 
+/* The same quantiser for a ragged K (not a multiple of 64): element-wise reads of the bf16 row
+ * (its start need not be 16-byte aligned), output row of Kp = ceil(K/64)*64 bytes with zeros in
+ * the padding. */
+__global__ __launch_bounds__(QUANT_THREADS) void bl_quant_rows_any(const uint16_t* __restrict__ X, int K, int Kp,
+                                                                    int8_t* __restrict__ q, float* __restrict__ scale,
+                                                                    int32_t* __restrict__ rowsum) {
+    __shared__ float smax[QUANT_THREADS / BL_WAVE];
+    __shared__ int ssum[QUANT_THREADS / BL_WAVE];
+    const int64_t m = blockIdx.x;
+    const uint16_t* x = X + m * K;
+    int8_t* qo = q + m * Kp;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    float mx = 0.0f;
+    for (int i = threadIdx.x; i < K; i += QUANT_THREADS) mx = fmaxf(mx, fabsf(bl_bf16_to_f32(x[i])));
+    mx = bl_wave_max(mx);
+    if (lane == 0) smax[w] = mx;
+    __syncthreads();
+    float gamma = smax[0];
+#pragma unroll
+    for (int i = 1; i < QUANT_THREADS / BL_WAVE; ++i) gamma = fmaxf(gamma, smax[i]);
+    const float g = fmaxf(gamma, 1e-5f);
+    const float inv = bl_div_rn(127.0f, g);
+    int sum = 0;
+    for (int i = threadIdx.x; i < Kp; i += QUANT_THREADS) {
+        int qi = 0;
+        if (i < K) {
+            float r = rintf(bl_bf16_to_f32(x[i]) * inv);
+            r = fminf(fmaxf(r, -127.0f), 127.0f);
+            qi = (int)r;
+        }
+        sum += qi;
+        qo[i] = (int8_t)qi;
+    }
+    sum = bl_wave_sum(sum);
+    if (lane == 0) ssum[w] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        scale[m] = bl_div_rn(g, 127.0f);
+        if (rowsum) {
+            int t = 0;
+#pragma unroll
+            for (int i = 0; i < QUANT_THREADS / BL_WAVE; ++i) t += ssum[i];
+            rowsum[m] = t;
+        }
+    }
+}
+
 /* Producer + quantiser: the bf16 row is produced on the fly (bl_produce16) and
  * kept in registers between the absmax pass and the quantise pass (two
  * 16-element groups per thread cover K <= 8192; longer rows are produced twice). */
@@ -217,7 +264,13 @@ extern "C" bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int6
 extern "C" bl_status bl_quant_act_int8(const uint16_t* X, int64_t M, int64_t K, int8_t* q, float* scale,
                                        int32_t* rowsum, bl_stream s) {
     if (!X || !q || !scale) return BL_ERR_NULL;
-    if (M < 1 || M > BL_MAX_DIM || K < 64 || K % 64 != 0 || K > BL_MAX_DIM) return BL_ERR_SHAPE;
+    if (M < 1 || M > BL_MAX_DIM || K < 1 || K > BL_MAX_DIM) return BL_ERR_SHAPE;
+    if (K % 64 != 0) {
+        if (!bl_aligned(X, 2) || !bl_aligned(q, 16) || !bl_aligned(scale, 4) || !bl_aligned(rowsum, 4))
+            return BL_ERR_ALIGN;
+        bl_quant_rows_any<<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>(X, (int)K, (int)bl_kpad(K), q, scale, rowsum);
+        return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+    }
     if (!bl_aligned(X, 16) || !bl_aligned(q, 16) || !bl_aligned(scale, 4) || !bl_aligned(rowsum, 4))
         return BL_ERR_ALIGN;
     bl_quant_rows<<<(unsigned)M, QUANT_THREADS, 0, (hipStream_t)s>>>((const uint4*)X, (int)(K / 8), (uint2*)q,

@@ -405,6 +405,7 @@ static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
     if (!d.acc && !d.y) return BL_ERR_NULL;
     if (!fused && d.y && !d.scale) return BL_ERR_NULL;
     if (!bl_shape_ok(d.N, d.K) || d.K > 64 * 64 * BL_STREAM_LMAX || d.N > (1 << 28)) return BL_ERR_SHAPE;
+    if (fused && d.K % 64 != 0) return BL_ERR_SHAPE;     /* bf16 / producer rows are read 16 elements at a time */
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
     if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
         !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||
@@ -417,7 +418,7 @@ extern "C" size_t bl_stack_table_bytes(const bl_decode_desc* descs, int count) {
     if (!descs || count < 1 || count > BL_STACK_MAX_COUNT) return 0;
     size_t q_bytes = 0;
     for (int i = 0; i < count; ++i) {
-        if (descs[i].K < 64 || descs[i].K > 64 * 64 * BL_STREAM_LMAX) return 0;
+        if (descs[i].K < 1 || descs[i].K > 64 * 64 * BL_STREAM_LMAX) return 0;
         if (desc_is_fused(descs[i])) q_bytes += align_up((size_t)descs[i].K, 256);
     }
     return stream_layout(count, q_bytes).total;
@@ -446,6 +447,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     for (int i = 0; i < count; ++i) {
         const bl_decode_desc& d = descs[i];
         const bool fused = desc_is_fused(d);
+        const int64_t Kp = bl_kpad(d.K);                 /* row length of the packed weights and of q */
         bl_stream_item it;
         memset(&it, 0, sizeof(it));
         it.packed = (const bl_v4i*)d.packed;
@@ -454,8 +456,8 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
         it.acc = d.acc;
         it.y = d.y;
         it.N = (int)d.N;
-        it.nchunks = (int)(d.K / 64);
-        if ((int)d.K > max_k) max_k = (int)d.K;
+        it.nchunks = (int)(Kp / 64);
+        if ((int)Kp > max_k) max_k = (int)Kp;
         it.layout = layout;
         int lgG = 3;
         while (((it.nchunks + (1 << lgG) - 1) >> lgG) > BL_STREAM_LMAX) ++lgG;   /* K bound checked: lgG <= 6 */
@@ -473,7 +475,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
         } else if (fused || !d.rowsum) {
             bl_stream_prep_item pp;
             memset(&pp, 0, sizeof(pp));
-            pp.K = (int)d.K;
+            pp.K = (int)Kp;
             pp.rowsum_ws = (int32_t*)(dev_base + L.rowsum_off) + i;
             it.rowsum = pp.rowsum_ws;
             if (fused) {
@@ -499,10 +501,10 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
             it.scale = d.scale;
             it.rowsum = d.rowsum;
         }
-        unit_bytes[(size_t)i] = (int64_t)R * (d.K / 4);
+        unit_bytes[(size_t)i] = (int64_t)R * (Kp / 4);
         total += (int64_t)it.units * unit_bytes[(size_t)i];
         total_units += it.units;
-        packed_bytes += d.N * d.K / 4;
+        packed_bytes += d.N * Kp / 4;
         items[(size_t)i] = it;
     }
     /* persistent grid: the workgroups that are resident at once, but no more than one per four

@@ -42,8 +42,14 @@ def test_sizes(lib):
         assert lib.bl_packed_bytes(13824, 2560, layout) == 8847360
         assert lib.bl_packed_bytes(2560, 6912, layout) == 4423680
     assert lib.bl_packed_bytes(2560, 2560, 7) == 0
-    assert lib.bl_packed_bytes(2560, 100, 0) == 0   # K % 64
-    assert lib.bl_packed_bytes(6, 128, 0) == 0      # N % 4
+    # ragged shapes are padded: rows of ceil(K/64)*64 weights, ceil(N/4)*4 rows
+    assert lib.bl_packed_bytes(2560, 100, 0) == 2560 * 128 // 4
+    assert lib.bl_packed_bytes(6, 128, 0) == 8 * 128 // 4
+    assert lib.bl_packed_bytes(1, 1, 1) == 4 * 64 // 4
+    assert lib.bl_packed_bytes(0, 64, 0) == 0 and lib.bl_packed_bytes(64, 0, 0) == 0
+    assert lib.bl_packed_bytes((1 << 24) + 1, 64, 0) == 0
+    assert [lib.bl_padded_k(k) for k in (1, 63, 64, 65, 2560, 6912, 6913)] == [64, 64, 64, 128, 2560, 6912, 6976]
+    assert lib.bl_padded_k(0) == 0 and lib.bl_padded_k((1 << 24) + 1) == 0
     assert lib.bl_workspace_bytes(bl.BL_OP_PACK, 0, 2560, 2560) >= 8192
     assert lib.bl_workspace_bytes(bl.BL_OP_GEMM, 2048, 2560, 2560) >= 2048 * 4
     assert b"BL_ERR_SHAPE" in lib.bl_status_str(2)
@@ -59,12 +65,16 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.bl_gemv_w158a8(p, p, 0, p, p, NULL, 1, 64, 64, NULL, NULL, NULL, NULL) == 1  # no output
     assert lib.bl_gemv_w158a8(p, p, 0, p, NULL, NULL, 1, 64, 64, NULL, p, NULL, NULL) == 1  # y without scale
     # shapes
-    assert lib.bl_pack_ternary(p, 0, 64, 100, 0, p, p, p, NULL) == 2
-    assert lib.bl_pack_ternary(p, 0, 6, 64, 0, p, p, p, NULL) == 2
+    assert lib.bl_pack_ternary(p, 0, 64, 0, 0, p, p, p, NULL) == 2
+    assert lib.bl_pack_ternary(p, 0, 0, 64, 0, p, p, p, NULL) == 2
+    assert lib.bl_pack_ternary(p, 0, (1 << 24) + 1, 64, 0, p, p, p, NULL) == 2
+    assert lib.bl_pack_ternary(p, 0, 6, 100, 0, p, p, NULL, NULL) == 7       # ragged shape: same workspace rule
     assert lib.bl_quant_act_int8(p, 0, 64, p, p, NULL, NULL) == 2
+    assert lib.bl_quant_act_int8(p, 1, 0, p, p, NULL, NULL) == 2
     assert lib.bl_gemv_w158a8(p, p, 0, p, p, NULL, 65, 64, 64, p, NULL, NULL, NULL) == 2   # M > 64
     assert lib.bl_gemv_w158a8(p, p, 0, p, p, NULL, 0, 64, 64, p, NULL, NULL, NULL) == 2
-    assert lib.bl_gemm_w158a8(p, p, 0, p, p, NULL, 8, 64, 96, p, NULL, NULL, NULL) == 2
+    assert lib.bl_gemm_w158a8(p, p, 0, p, p, NULL, 8, 64, 0, p, NULL, NULL, NULL) == 2
+    assert lib.bl_gemm_w158a8(p, p, 0, p, p, NULL, 8, 0, 96, p, NULL, NULL, NULL) == 2
     # layout / kind
     assert lib.bl_pack_ternary(p, 0, 64, 64, 5, p, p, p, NULL) == 3
     assert lib.bl_gemv_w158a8(p, p, 9, p, p, NULL, 1, 64, 64, p, NULL, NULL, NULL) == 3
@@ -105,6 +115,10 @@ def test_producer_and_group_descriptors_are_checked_on_the_host(lib):
     assert lib.bl_bitlinear_decode_group(d_q, 5, 1, 1, None) == 2
     assert lib.bl_bitlinear_decode_group(d_q, 1, 1, 65, None) == 2                # int8 inputs: M <= 64
     assert lib.bl_bitlinear_decode_group(d_x, 1, 1, 17, None) == 2                # fused inputs: M <= 16
+    d_x100 = bl.make_decode_descs([dict(packed=t, beta=beta, N=64, K=100, y=t, X=t)])
+    assert lib.bl_bitlinear_decode_group(d_x100, 1, 1, 1, None) == 2              # fused inputs: K % 64 == 0
+    d_q100 = bl.make_decode_descs([dict(packed=t, beta=beta, N=7, K=100, y=t, q=t, scale=t)])
+    assert lib.bl_bitlinear_decode_group(d_q100, 1, 9, 1, None) == 3              # int8 inputs: any N, K (layout checked)
     assert lib.bl_bitlinear_decode_group(d_q, 1, 7, 1, None) == 3
     assert lib.bl_bitlinear_decode_group(None, 1, 1, 1, None) == 1
 

@@ -502,3 +502,32 @@ def test_rmsnorm_against_fp64_formula_and_gains():
     t = rng.standard_normal((3, 4096)).astype(np.float32) * 7
     out = _bf16_to_f32(oracle.rmsnorm_rows(t, None, 1e-5)).astype(np.float64)
     assert np.all(np.abs(np.sqrt((out ** 2).mean(axis=1)) - 1.0) < 2e-3)
+
+
+def test_padded_pack_is_plain_pack_of_the_zero_padded_matrix():
+    """The library's format for a ragged K or N: weight 0 (code 1) outside the matrix, rows of
+    ceil(K/64)*64 weights, ceil(N/4)*4 rows.  Pinned by decoding the bytes by hand (layout 0: two
+    bits per weight, lowest bits = lowest k) and by the round trip through unpack."""
+    rng = np.random.default_rng(3)
+    for N, K in [(1, 1), (3, 17), (5, 65), (8, 64), (6, 130)]:
+        Wt = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+        Np, Kp = -(-N // 4) * 4, oracle.padded_k(K)
+        assert Kp % 64 == 0 and Kp >= K and Kp - K < 64
+        for layout in (0, 1):
+            p = oracle.pack_padded(Wt, layout)
+            assert p.size == Np * Kp // 4
+            back, bad = oracle.unpack(p, Np, Kp, layout)
+            assert bad == 0
+            assert np.array_equal(back[:N, :K], Wt)
+            assert not back[N:].any() and not back[:, K:].any()
+        p0 = oracle.pack_padded(Wt, 0).reshape(Np, Kp // 4)
+        for n in range(Np):
+            for k in range(Kp):
+                code = (int(p0[n, k // 4]) >> (2 * (k % 4))) & 3
+                assert code == (int(Wt[n, k]) + 1 if n < N and k < K else 1)
+    Wt = rng.integers(-1, 2, size=(8, 128)).astype(np.int8)
+    for layout in (0, 1):
+        assert np.array_equal(oracle.pack_padded(Wt, layout), oracle.pack(Wt, layout))
+    q = rng.integers(-127, 128, size=(3, 70)).astype(np.int8)
+    pq = oracle.pad_q(q)
+    assert pq.shape == (3, 128) and np.array_equal(pq[:, :70], q) and not pq[:, 70:].any()
