@@ -280,6 +280,30 @@ def main():
                           "GBps": round(big_n * 2560 / 4 / (t_big / 10) / 1e9, 1)}
         del big, yb, stb
 
+        # the same 120 BitLinears with five weights per byte (layout 2: a fifth fewer bytes, three times
+        # the decode arithmetic per weight): repacked on the GPU from the 2-bit form
+        items5, keep5 = [], []
+        for L in layers:
+            for n in SHAPE_ORDER:
+                Wt, _bad = bl.bl_unpack_ternary(L.packed[n], buf[n].N, buf[n].K, layout)
+                p5, _ = bl.bl_pack_ternary(Wt, bl.BL_LAYOUT_TRIT5, beta=L.beta[n])
+                keep5.append(p5)
+                items5.append(dict(packed=p5, beta=L.beta[n], N=buf[n].N, K=buf[n].K, X=buf[n].X,
+                                   y=torch.empty((1, buf[n].N), dtype=torch.float32, device=dev)))
+                del Wt
+        st5 = bl.Stack(items5, bl.BL_LAYOUT_TRIT5, 1, dev)
+        st5.run()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a["y"], y) for a, y in zip(items5, ys)), "five-per-byte form disagrees with the 2-bit form"
+        g = capture(torch, lambda: [st5.run() for _ in range(10)])
+        g.replay()
+        t5, _ = time_graph_steps(torch, [(g, 10, 5)], 50)
+        alt["stream_five_weights_per_byte"] = {
+            "us_per_step": round(t5 / 50 * 1e6, 2), "packed_bytes_per_step": int(st5.plan.packed_bytes),
+            "GBps_of_its_own_bytes": round(st5.plan.packed_bytes / (t5 / 50) / 1e9, 1),
+            "GBps_in_2bit_bytes": round(stack_bytes / (t5 / 50) / 1e9, 1)}
+        del st5, items5, keep5
+
         # achievable roof: a plain 128-bit streaming read (same slicing, no arithmetic) of 2 GiB, and
         # of as many bytes as one step streams, at the stream kernel's occupancy and at the best one
         probe = torch.randint(0, 256, (2 << 30,), dtype=torch.uint8, device=dev)

@@ -35,6 +35,15 @@
  *     byte n*(Kp/4) + (k/16)*4 + i%4.  (So `(word >> 2s) & 0x03030303` yields the
  *     codes of k = 4s..4s+3 as four bytes in natural order: the kernels' native
  *     form.  Layout 0 is supported by permuting the activation bytes instead.)
+ *   BL_LAYOUT_TRIT5 (2): five weights per byte, 1.6 bits per weight (the density behind the
+ *     memory footprint of Table 1; the 2-bit forms above are the ones Section 5.1 describes).
+ *     Rows of Kq = K rounded up to a multiple of 80 weights (Kq/5 bytes, a whole number of
+ *     16-byte loads), Np rows, code 1 outside the matrix: Np*Kq/5 bytes.  Inside a row, the 4-byte
+ *     word g covers k = 20g .. 20g+19; its byte j holds the codes c_i of k = 20g + 4i + j,
+ *     i = 0..4, as b = ceil(v * 256 / 243) with v = sum_i c_i * 3^(4-i) (so that c_0 = (3b) >> 8,
+ *     and the same step on the low byte of 3b yields c_1, and so on: no table, no division).
+ *     Accepted by bl_pack_ternary, bl_unpack_ternary, bl_packed_bytes and bl_stack_build (the
+ *     bandwidth-bound M = 1 decode, where bytes are time); BL_ERR_LAYOUT elsewhere.
  * QUANTISED ACTIVATIONS are int8 [M][Kp]: leading dimension Kp, zeros in columns K..Kp-1 (what
  * bl_quant_act_int8 writes), so that a padded weight meets a zero.  Outputs are [M][N].
  *
@@ -74,7 +83,7 @@ typedef enum {
 
 typedef void* bl_stream;   /* hipStream_t */
 
-enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_K16 = 1 };
+enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_K16 = 1, BL_LAYOUT_TRIT5 = 2 };
 enum { BL_IN_FP32_LATENT = 0, BL_IN_INT8_TERNARY = 1 };
 enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3 };
 
@@ -306,9 +315,9 @@ bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int6
  *                         in place; runs on one table must not overlap (they share the scratch). */
 enum { BL_STACK_MAX_COUNT = 1024 };
 typedef struct {
-    int32_t count, blocks, prep_count, inline_count, norm, lds_bytes;
+    int32_t count, blocks, prep_count, inline_count, norm, lds_bytes, layout, reserved;
     int64_t wg_offset, prep_offset;   /* byte offsets inside `table`                            */
-    int64_t packed_bytes;             /* sum of N*K/4 over the products: bytes one run streams */
+    int64_t packed_bytes;             /* packed weight bytes of the products: what one run streams */
     int64_t table_bytes;
 } bl_stack_plan;
 size_t    bl_stack_table_bytes(const bl_decode_desc* descs, int count);

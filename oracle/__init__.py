@@ -157,6 +157,51 @@ def pad_q(q):
     return P
 
 
+def padded_k5(K):
+    """Row length of the five-weights-per-byte form: K rounded up to a multiple of 80."""
+    return -(-int(K) // 80) * 80
+
+
+def pack_trit5(Wt):
+    """Five weights per byte (1.6 bits per weight, the density behind the memory figure of Table 1;
+    the library's layout 2, its own format).  Rows padded with weight 0 to padded_k5(K) weights and
+    the row count to a multiple of 4.  The 4-byte word g of a row covers k = 20g .. 20g+19 and its
+    byte j holds the offset codes c_i = Wt[k] + 1 of k = 20g + 4i + j, i = 0..4, as
+    b = ceil(v * 256 / 243), v = sum_i c_i * 3^(4-i)."""
+    Wt = _c(Wt, np.int8)
+    if Wt.min(initial=0) < -1 or Wt.max(initial=0) > 1:
+        raise ValueError("weights outside {-1,0,1}")
+    N, K = Wt.shape
+    Np, Kq = -(-N // 4) * 4, padded_k5(K)
+    codes = np.ones((Np, Kq), dtype=np.int64)
+    codes[:N, :K] = Wt.astype(np.int64) + 1
+    c = codes.reshape(Np, Kq // 20, 5, 4)               # [row][word g][digit i][byte j]
+    v = np.zeros((Np, Kq // 20, 4), dtype=np.int64)
+    for i in range(5):
+        v += c[:, :, i, :] * 3 ** (4 - i)
+    b = (v * 256 + 242) // 243                          # ceil(v * 256 / 243)
+    return b.astype(np.uint8).reshape(-1)
+
+
+def unpack_trit5(packed, N, K):
+    """Inverse of pack_trit5 by the decoding rule the format is built for: the leading digit of a byte
+    is (3*b) >> 8, the low byte of 3*b carries the remaining digits.  Returns (Wt, number of bytes that
+    are not the code of their own digits)."""
+    Np, Kq = -(-N // 4) * 4, padded_k5(K)
+    b = _c(packed, np.uint8).astype(np.int64).reshape(Np, Kq // 20, 4)
+    r = b.copy()
+    codes = np.empty((Np, Kq // 20, 5, 4), dtype=np.int64)
+    v = np.zeros_like(b)
+    for i in range(5):
+        t = r * 3
+        codes[:, :, i, :] = t >> 8
+        r = t & 255
+        v = v * 3 + codes[:, :, i, :]
+    bad = int(np.count_nonzero((v * 256 + 242) // 243 != b))
+    Wt = (codes.reshape(Np, Kq) - 1).astype(np.int8)
+    return np.ascontiguousarray(Wt[:N, :K]), bad
+
+
 def unpack(packed, N, K, layout=0):
     """Inverse of pack; returns (Wt int8 [N][K], number of invalid codes)."""
     packed = _c(packed, np.uint8)

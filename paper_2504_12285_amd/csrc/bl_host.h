@@ -14,6 +14,8 @@ static inline bool bl_shape_ok(int64_t N, int64_t K) {
 /* Padded sizes of the packed matrix and of the quantised activations (bitlinear.h, PACKED LAYOUTS). */
 static inline int64_t bl_kpad(int64_t K) { return (K + 63) / 64 * 64; }
 static inline int64_t bl_npad(int64_t N) { return (N + 3) / 4 * 4; }
+/* Five-per-byte form: rows of ceil(K/80)*80 weights = a whole number of 16-byte loads. */
+static inline int64_t bl_kpad5(int64_t K) { return (K + 79) / 80 * 80; }
 static inline bool bl_shape_unpadded(int64_t N, int64_t K) { return N % 4 == 0 && K % 64 == 0; }
 static inline bool bl_aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 

@@ -44,7 +44,8 @@ struct bl_stream_item {
     int8_t* q_out;            /* xbf16 only: the caller's optional copies of q and absmax/127 */
     float* scale_out;
     float fixed_scale;        /* xbf16 only: > 0 replaces absmax/127 in the rescale */
-    int N, nchunks, lgG, lp, layout, units, pad0;
+    int N, nchunks, lgG, lp, layout, units;
+    int qgroups;              /* 16-byte groups of the quantised row (its padded length / 16) */
 };
 
 /* What the preparation kernel needs: the fused producer + quantiser of one product. */
@@ -347,6 +348,170 @@ __device__ __forceinline__ void bl_stream_slice(const bl_stream_item& P, const i
     }
 }
 
+/* ---- five weights per byte (BL_LAYOUT_TRIT5) ---------------------------------------------------
+ * A byte b = ceil(v * 256 / 243) holds v = sum_i c_i * 3^(4-i), five offset codes c_i in {0,1,2}.
+ * Multiplying by 3 moves the leading base-3 digit into bits 8..9 and leaves the rest of the
+ * number in the low byte: five multiply-and-mask steps give the five digits, no table and no
+ * division.  The four bytes of a word are handled as two pairs in 16-bit lanes (a byte times 3
+ * fits 10 bits), and a byte permute gathers the four digits of step i into one register whose
+ * bytes pair with k = 20*word + 4*i + 0..3: an operand of v_dot4_i32_i8 against the activations
+ * in their natural order.  Per 16-byte load: 80 weights, 20 dot products, ~100 more vector
+ * instructions: three times the work per weight of the 2-bit form. */
+#define BL_T5_QSTRIDE 24      /* dwords per 80-weight chunk in LDS: 20 + 4 of padding */
+
+__device__ __forceinline__ int bl_t5_dot(const bl_v4i p, const bl_v4i* a, int A) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t w = (uint32_t)p[d];
+        uint32_t e = w & 0x00FF00FFu, o = (w >> 8) & 0x00FF00FFu;
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            e = (e << 1) + e;
+            o = (o << 1) + o;
+            const uint32_t dg = __builtin_amdgcn_perm(o, e, 0x07030501u);   /* bits 8..15 of the four lanes */
+            A = __builtin_amdgcn_sdot4((int)dg, a[(5 * d + i) >> 2][(5 * d + i) & 3], A, false);
+            if (i < 4) {
+                e &= 0x00FF00FFu;
+                o &= 0x00FF00FFu;
+            }
+        }
+    }
+    return A;
+}
+
+/* Stages the activation row for the five-per-byte form: the int8 row in its natural order, 80
+ * bytes per chunk, zeros from the end of the row to the end of the last chunk and one all-zero
+ * chunk behind it.  misc as in bl_stream_stage.  Ends with a barrier. */
+__device__ __forceinline__ void bl_stream_stage_t5(const bl_stream_item& P, int* __restrict__ Qs,
+                                                       int* __restrict__ misc, bool owner) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int groups = P.qgroups;
+    float* fs = (float*)(misc + 2);
+    int* ssum = misc + 6;
+    auto put = [&](int u, bl_v4i v) { *(bl_v4i*)(Qs + (u / 5) * BL_T5_QSTRIDE + (u % 5) * 4) = v; };
+    for (int u = groups + tid; u < (P.nchunks + 1) * 5; u += 256) put(u, bl_v4i{0, 0, 0, 0});
+    int part = 0;
+    if (P.xbf16) {
+        const bl_gv4i* x = (const bl_gv4i*)P.xbf16;
+        auto ld = [&](int i) {
+            const bl_v4i v = x[i];
+            return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+        };
+        float mx = 0.0f;
+        for (int u = tid; u < groups; u += 256)
+            mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(ld(2 * u)), bl_absmax8_bf16(ld(2 * u + 1))));
+        mx = bl_wave_max(mx);
+        if (lane == 0) fs[w] = mx;
+        __syncthreads();
+        const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
+        const float gg = fmaxf(gamma, 1e-5f);
+        const float inv = bl_div_rn(127.0f, gg);
+        for (int u = tid; u < groups; u += 256) {
+            uint32_t a0, a1, a2, a3;
+            bl_quant8_words(ld(2 * u), inv, a0, a1);
+            bl_quant8_words(ld(2 * u + 1), inv, a2, a3);
+            part += bl_sum16(a0, a1, a2, a3);
+            const bl_v4i qv = {(int)a0, (int)a1, (int)a2, (int)a3};
+            if (owner && P.q_out) *(bl_gv4i*)(P.q_out + u * 16) = qv;
+            put(u, qv);
+        }
+        if (tid == 0) {
+            const float sc = bl_div_rn(gg, 127.0f);
+            misc[1] = __float_as_int(P.fixed_scale > 0.0f ? P.fixed_scale : sc);
+            if (owner && P.scale_out) *(float BL_G*)P.scale_out = sc;
+        }
+        part = bl_wave_sum(part);
+        if (lane == 0) ssum[w] = part;
+        __syncthreads();
+        if (tid == 0) misc[0] = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+    } else {
+        const bl_gv4i* qg = (const bl_gv4i*)P.q;
+        for (int u = tid; u < groups; u += 256) put(u, qg[u]);
+        if (tid == 0) {
+            misc[0] = *(const int32_t BL_G*)P.rowsum;
+            misc[1] = P.scale ? __float_as_int(*(const float BL_G*)P.scale) : 0;
+        }
+    }
+    __syncthreads();
+}
+
+/* bl_stream_slice for the five-per-byte form: the same double-buffered, unconditional loads; a
+ * load is 80 weights against 20 activation dwords read from LDS right before its dot products. */
+template <int LP>
+__device__ __forceinline__ void bl_stream_slice_t5(const bl_stream_item& P, const int ub, const int ue,
+                                                       int* __restrict__ Qs, int* __restrict__ misc,
+                                                       const bool restage) {
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = P.N, nchunks = P.nchunks, lgG = P.lgG;
+    const int R = 64 >> lgG;
+    const int r = lane >> lgG, g = lane & ((1 << lgG) - 1);
+    const int nunits = ue - ub;
+    const bl_gv4i* const wbase = (const bl_gv4i*)P.packed;
+    int32_t BL_G* const acc_g = (int32_t BL_G*)P.acc;
+    float BL_G* const y_g = (float BL_G*)P.y;
+    const float BL_G* const res_g = (const float BL_G*)P.residual;
+    const float BL_G* const res_base = res_g ? res_g : (const float BL_G*)P.beta;
+    int coff[LP], qoff[LP];
+#pragma unroll
+    for (int i = 0; i < LP; ++i) {
+        const int chunk = g + (i << lgG);
+        coff[i] = chunk < nchunks ? chunk : nchunks - 1;
+        qoff[i] = (chunk < nchunks ? chunk : nchunks) * BL_T5_QSTRIDE;
+    }
+    auto issue = [&](bl_v4i* p, float& rv, int unit) {
+        int n = (ub + unit) * R + r;
+        n = n < N ? n : N - 1;
+        const bl_gv4i* wrow = wbase + (int64_t)n * nchunks;
+#pragma unroll
+        for (int i = 0; i < LP; ++i) p[i] = __builtin_nontemporal_load(wrow + coff[i]);
+        rv = res_base[res_g ? n : 0];
+    };
+    bl_v4i pa[LP], pb[LP];
+    float ra = 0.0f, rb = 0.0f;
+    int u = w;
+    if (u < nunits) issue(pa, ra, u);
+    if (restage) __syncthreads();
+    bl_stream_stage_t5(P, Qs, misc, ub == 0);
+    if (u >= nunits) return;
+    const int rs = misc[0];
+    float cf = 0.0f;
+    if (y_g) cf = *(const float BL_G*)P.beta * __int_as_float(misc[1]);
+
+    auto finish = [&](const bl_v4i* p, const float rv, int unit) {
+        int A = 0;
+#pragma unroll
+        for (int i = 0; i < LP; ++i) {
+            int qo = qoff[i];
+            asm volatile("" : "+v"(qo));          /* keeps the reads inside the loop (see bl_stream_slice) */
+            bl_v4i a[5];
+#pragma unroll
+            for (int t = 0; t < 5; ++t) a[t] = *(const bl_v4i*)(Qs + qo + t * 4);
+            A = bl_t5_dot(p[i], a, A);
+        }
+        const int v = bl_group_sum_rt(A, lgG);
+        const int rg = ub + unit;
+        const int n = rg * R + r;
+        if (g == 0 && n < N) {
+            const int val = v - rs;
+            if (acc_g) acc_g[n] = val;
+            if (y_g) {
+                const float t = (float)val * cf;
+                y_g[n] = res_g ? rv + t : t;
+            }
+        }
+    };
+    for (;;) {
+        if (u + 4 >= nunits) { finish(pa, ra, u); break; }
+        issue(pb, rb, u + 4);
+        finish(pa, ra, u);
+        u += 4;
+        if (u + 4 >= nunits) { finish(pb, rb, u); break; }
+        issue(pa, ra, u + 4);
+        finish(pb, rb, u);
+        u += 4;
+    }
+}
+
 /* Persistent grid: workgroup b walks the table slice wgstart[b] .. wgstart[b+1], each entry
  * (product, row group).  Two loop shapes cover every product: five loads per lane and row, and
  * up to four (a product with fewer leaves slots idle: clamped loads that hit the cache, the
@@ -373,11 +538,33 @@ void bl_stream_m1(const bl_stream_item* __restrict__ items, const int2* __restri
     }
 }
 
+/* The same walk for a table in the five-per-byte form. */
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void bl_stream_m1_t5(const bl_stream_item* __restrict__ items, const int2* __restrict__ wgstart, const int q_ints) {
+    extern __shared__ int lds[];
+    int* Qs = lds;
+    int* misc = lds + q_ints;
+    const int2 s0 = wgstart[blockIdx.x], s1 = wgstart[blockIdx.x + 1];
+    const int p_first = __builtin_amdgcn_readfirstlane(s0.x), u_first = __builtin_amdgcn_readfirstlane(s0.y);
+    const int p_last = __builtin_amdgcn_readfirstlane(s1.x), u_last = __builtin_amdgcn_readfirstlane(s1.y);
+    bool staged = false;
+    for (int pi = p_first; pi <= p_last; ++pi) {
+        if (pi == p_last && u_last == 0) break;
+        const bl_stream_item P = items[pi];
+        const int ub = pi == p_first ? u_first : 0;
+        const int ue = pi == p_last ? u_last : P.units;
+        if (ub >= ue) continue;
+        if (P.lp == 5) bl_stream_slice_t5<5>(P, ub, ue, Qs, misc, staged);
+        else bl_stream_slice_t5<4>(P, ub, ue, Qs, misc, staged);
+        staged = true;
+    }
+}
+
 /* ---- host side ---------------------------------------------------------------------------- */
 
 #define BL_STREAM_LMAX 5
 #define BL_STREAM_MAX_BLOCKS 4096
-#define BL_STREAM_LDS_BYTES ((max_k / 64 + 1) * BL_QSTRIDE * 4 + 64)
+#define BL_STREAM_LDS_BYTES ((max_chunks + 1) * (layout == BL_LAYOUT_TRIT5 ? BL_T5_QSTRIDE : BL_QSTRIDE) * 4 + 64)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -406,7 +593,7 @@ static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
     if (!fused && d.y && !d.scale) return BL_ERR_NULL;
     if (!bl_shape_ok(d.N, d.K) || d.K > 64 * 64 * BL_STREAM_LMAX || d.N > (1 << 28)) return BL_ERR_SHAPE;
     if (fused && d.K % 64 != 0) return BL_ERR_SHAPE;     /* bf16 / producer rows are read 16 elements at a time */
-    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16 && layout != BL_LAYOUT_TRIT5) return BL_ERR_LAYOUT;
     if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
         !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||
         !bl_aligned(d.rowsum, 4) || !bl_aligned(d.scale_out, 4) || !bl_aligned(d.residual, 4))
@@ -439,7 +626,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     uint8_t* const dev_base = (uint8_t*)table;
     std::vector<bl_stream_item> items((size_t)count);
     std::vector<bl_stream_prep_item> preps;
-    int inline_count = 0, max_k = 0;
+    int inline_count = 0, max_chunks = 0;
     std::vector<int64_t> unit_bytes((size_t)count);
     bool any_norm = false;
     int64_t total = 0, packed_bytes = 0, total_units = 0;
@@ -456,8 +643,11 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
         it.acc = d.acc;
         it.y = d.y;
         it.N = (int)d.N;
-        it.nchunks = (int)(Kp / 64);
-        if ((int)Kp > max_k) max_k = (int)Kp;
+        /* 16-byte loads per weight row: 64 weights each, or 80 in the five-per-byte form */
+        const int64_t row_bytes = layout == BL_LAYOUT_TRIT5 ? bl_kpad5(d.K) / 5 : Kp / 4;
+        it.nchunks = (int)(row_bytes / 16);
+        it.qgroups = (int)(Kp / 16);
+        if (it.nchunks > max_chunks) max_chunks = it.nchunks;
         it.layout = layout;
         int lgG = 3;
         while (((it.nchunks + (1 << lgG) - 1) >> lgG) > BL_STREAM_LMAX) ++lgG;   /* K bound checked: lgG <= 6 */
@@ -501,10 +691,10 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
             it.scale = d.scale;
             it.rowsum = d.rowsum;
         }
-        unit_bytes[(size_t)i] = (int64_t)R * (Kp / 4);
+        unit_bytes[(size_t)i] = (int64_t)R * row_bytes;
         total += (int64_t)it.units * unit_bytes[(size_t)i];
         total_units += it.units;
-        packed_bytes += d.N * Kp / 4;
+        packed_bytes += d.N * row_bytes;
         items[(size_t)i] = it;
     }
     /* persistent grid: the workgroups that are resident at once, but no more than one per four
@@ -512,8 +702,9 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)bl_stream_m1, 256,
-                                                     (size_t)BL_STREAM_LDS_BYTES) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &per_cu, layout == BL_LAYOUT_TRIT5 ? (const void*)bl_stream_m1_t5 : (const void*)bl_stream_m1, 256,
+            (size_t)BL_STREAM_LDS_BYTES) != hipSuccess ||
         cus < 1 || per_cu < 1)
         return BL_ERR_HIP;
     int64_t blocks64 = (int64_t)cus * per_cu;
@@ -593,6 +784,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     plan->inline_count = inline_count;
     plan->norm = any_norm ? 1 : 0;
     plan->lds_bytes = BL_STREAM_LDS_BYTES;
+    plan->layout = layout;
     plan->wg_offset = (int64_t)L.wg_off;
     plan->prep_offset = (int64_t)L.prep_off;
     plan->packed_bytes = packed_bytes;
@@ -605,7 +797,8 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
     if (plan->count < 1 || plan->count > BL_STACK_MAX_COUNT || plan->blocks < 1 ||
         plan->blocks > BL_STREAM_MAX_BLOCKS || plan->prep_count < 0 || plan->inline_count < 0 ||
         plan->prep_count + plan->inline_count > plan->count || plan->lds_bytes < 64 ||
-        plan->lds_bytes > 64 + (64 * BL_STREAM_LMAX + 1) * BL_QSTRIDE * 4 || plan->lds_bytes % 16)
+        plan->lds_bytes > 64 + (64 * BL_STREAM_LMAX + 1) * BL_T5_QSTRIDE * 4 || plan->lds_bytes % 16 ||
+        plan->layout < 0 || plan->layout > BL_LAYOUT_TRIT5)
         return BL_ERR_VALUE;
     const bl_stream_layout L = stream_layout(plan->count, 0);
     if (plan->wg_offset != (int64_t)L.wg_off || plan->prep_offset != (int64_t)L.prep_off) return BL_ERR_VALUE;
@@ -618,7 +811,11 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
         else bl_stream_prep<false><<<plan->prep_count, 256, 0, st>>>(pp);
         if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
     }
-    bl_stream_m1<<<plan->blocks, 256, (size_t)plan->lds_bytes, st>>>(
-        (const bl_stream_item*)base, (const int2*)(base + L.wg_off), (plan->lds_bytes - 64) / 4);
+    if (plan->layout == BL_LAYOUT_TRIT5)
+        bl_stream_m1_t5<<<plan->blocks, 256, (size_t)plan->lds_bytes, st>>>(
+            (const bl_stream_item*)base, (const int2*)(base + L.wg_off), (plan->lds_bytes - 64) / 4);
+    else
+        bl_stream_m1<<<plan->blocks, 256, (size_t)plan->lds_bytes, st>>>(
+            (const bl_stream_item*)base, (const int2*)(base + L.wg_off), (plan->lds_bytes - 64) / 4);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }

@@ -22,7 +22,7 @@ class Case:
             self.y = oracle.rescale(self.acc, self.beta, self.scale)
 
     def packed(self, layout):
-        return oracle.pack(self.Wt, layout)
+        return oracle.pack_trit5(self.Wt) if layout == 2 else oracle.pack_padded(self.Wt, layout)
 
 
 def to_dev(a, dev="cuda:0"):

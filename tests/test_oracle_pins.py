@@ -531,3 +531,60 @@ def test_padded_pack_is_plain_pack_of_the_zero_padded_matrix():
     q = rng.integers(-127, 128, size=(3, 70)).astype(np.int8)
     pq = oracle.pad_q(q)
     assert pq.shape == (3, 128) and np.array_equal(pq[:, :70], q) and not pq[:, 70:].any()
+
+
+def test_trit5_codes_exhaustive_and_hand_worked():
+    """Five weights per byte.  Hand-worked bytes: all weights 0 -> codes 1,1,1,1,1 -> v = 81+27+9+3+1 = 121
+    -> ceil(121*256/243) = ceil(127.47) = 128; all -1 -> v = 0 -> 0; all +1 -> v = 242 -> ceil(254.95) = 255;
+    leading weight +1, rest -1 -> v = 2*81 = 162 -> ceil(170.67) = 171.  Then every one of the 243 digit
+    strings, with the digits taken by plain integer division as the reference for the multiply-by-3 rule."""
+    def one_byte(ws):      # ws: the five weights of byte 0 of word 0 = k 0, 4, 8, 12, 16
+        Wt = np.zeros((1, 20), dtype=np.int8)
+        Wt[0, 0:20:4] = ws
+        return int(oracle.pack_trit5(Wt)[0])
+    assert one_byte([0, 0, 0, 0, 0]) == 128
+    assert one_byte([-1, -1, -1, -1, -1]) == 0
+    assert one_byte([1, 1, 1, 1, 1]) == 255
+    assert one_byte([1, -1, -1, -1, -1]) == 171
+    seen = set()
+    for v in range(243):
+        digits = [(v // 3 ** (4 - i)) % 3 for i in range(5)]
+        b = one_byte([d - 1 for d in digits])
+        assert b == -(-v * 256 // 243) and 0 <= b <= 255
+        seen.add(b)
+        r, out = b, []
+        for _ in range(5):
+            t = r * 3
+            out.append(t >> 8)
+            r = t & 255
+        assert out == digits
+    assert len(seen) == 243                                   # distinct bytes: the code is invertible
+
+
+def test_trit5_positions_padding_and_round_trip():
+    """A single +1 at position k lands in word k // 20, byte (k % 20) % 4, digit (k % 20) // 4; padding
+    decodes to weight 0; sizes are Np * ceil(K/80)*80 / 5; random matrices survive the round trip."""
+    N, K = 3, 100
+    Np, Kq = 4, 160
+    zero_byte = 128
+    for (n, k) in [(0, 0), (0, 1), (0, 4), (0, 19), (0, 20), (2, 99), (1, 57)]:
+        Wt = np.zeros((N, K), dtype=np.int8)
+        Wt[n, k] = 1
+        p = oracle.pack_trit5(Wt).reshape(Np, Kq // 5)
+        assert p.size == Np * Kq // 5
+        g, j, i = k // 20, (k % 20) % 4, (k % 20) // 4
+        want = np.full((Np, Kq // 5), zero_byte, dtype=np.uint8)
+        want[n, 4 * g + j] = -(-(121 + 3 ** (4 - i)) * 256 // 243)
+        assert np.array_equal(p, want)
+    rng = np.random.default_rng(11)
+    for N, K in [(1, 1), (4, 80), (5, 81), (7, 2560), (2, 6912)]:
+        Wt = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+        p = oracle.pack_trit5(Wt)
+        assert p.size == (-(-N // 4) * 4) * oracle.padded_k5(K) // 5
+        back, bad = oracle.unpack_trit5(p, N, K)
+        assert bad == 0 and np.array_equal(back, Wt)
+    assert oracle.padded_k5(2560) == 2560 and oracle.padded_k5(6912) == 6960
+    p = oracle.pack_trit5(np.zeros((4, 80), dtype=np.int8)).copy()
+    p[3] = 129                                                # 129 -> digits of v = 122 -> re-encodes to 129: valid
+    p[5] = 1                                                  # 1 is not ceil(v*256/243) of any v (v=0 -> 0, v=1 -> 2)
+    assert oracle.unpack_trit5(p, 4, 80)[1] == 1
