@@ -304,6 +304,52 @@ def main():
             "GBps_in_2bit_bytes": round(stack_bytes / (t5 / 50) / 1e9, 1)}
         del st5, items5, keep5
 
+        # the 30 down projections as one table: dense (layout 1) against the k-major form (layout 3), which
+        # does not read the weights of zero activations; with the squared-ReLU inputs as generated and with
+        # ordinary activations of which a seeded half is set to zero
+        def down_tables(Xs):
+            dense, sparse, keep = [], [], []
+            for L, X in zip(layers, Xs):
+                Wt, _bad = bl.bl_unpack_ternary(L.packed["down"], 2560, 6912, layout)
+                pk, _ = bl.bl_pack_ternary(Wt, bl.BL_LAYOUT_KMAJOR, beta=L.beta["down"])
+                del Wt
+                keep.append(pk)
+                for lst, pw in ((dense, L.packed["down"]), (sparse, pk)):
+                    lst.append(dict(packed=pw, beta=L.beta["down"], N=2560, K=6912, X=X,
+                                    y=torch.empty((1, 2560), dtype=torch.float32, device=dev)))
+            return dense, sparse, keep
+        rng_s = np.random.default_rng(11)
+        x_gen = [torch.from_numpy(synth.activations_bf16(0, 1, 6912, layer=l, matrix="down", relu2=True).view(np.int16))
+                 .to(dev).view(torch.bfloat16) for l in range(nl)]
+        x_half = []
+        for l in range(nl):
+            xb = synth.activations_bf16(0, 1, 6912, layer=l, matrix="down", relu2=False)
+            xb = np.where(rng_s.random(xb.shape) < 0.5, xb, np.uint16(0)).astype(np.uint16)
+            x_half.append(torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16))
+        sparsity = {}
+        for tag, Xs in (("squared_relu_inputs_as_generated", x_gen), ("half_of_the_inputs_zero", x_half)):
+            dense, sparse, keep = down_tables(Xs)
+            qs = [bl.bl_quant_act_int8(X)[0] for X in Xs]
+            nz = float(np.mean([float((q != 0).float().mean().item()) for q in qs]))
+            res = {"nonzero_fraction_of_q": round(nz, 4)}
+            outs = {}
+            for name, tab, lay in (("dense_layout1", dense, layout), ("k_major", sparse, bl.BL_LAYOUT_KMAJOR)):
+                st_ = bl.Stack(tab, lay, 1, dev)
+                st_.run()
+                torch.cuda.synchronize()
+                outs[name] = [t_["y"].clone() for t_ in tab]
+                g = capture(torch, lambda: [st_.run() for _ in range(10)])
+                g.replay()
+                tt, _ = time_graph_steps(torch, [(g, 10, 5)], 50)
+                res[name] = {"us_per_30_products": round(tt / 50 * 1e6, 2), "packed_bytes": int(st_.plan.packed_bytes)}
+                del st_
+            assert all(torch.equal(a, b) for a, b in zip(outs["dense_layout1"], outs["k_major"]))
+            res["k_major"]["weight_bytes_of_nonzero_rows"] = int(res["k_major"]["packed_bytes"] * nz)
+            sparsity[tag] = res
+            del dense, sparse, keep
+        alt["down_projection_sparsity"] = sparsity
+        log("[bench] down projection, 30 layers per launch: %s" % sparsity)
+
         # achievable roof: a plain 128-bit streaming read (same slicing, no arithmetic) of 2 GiB, and
         # of as many bytes as one step streams, at the stream kernel's occupancy and at the best one
         probe = torch.randint(0, 256, (2 << 30,), dtype=torch.uint8, device=dev)

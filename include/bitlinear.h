@@ -44,6 +44,13 @@
  *     and the same step on the low byte of 3b yields c_1, and so on: no table, no division).
  *     Accepted by bl_pack_ternary, bl_unpack_ternary, bl_packed_bytes and bl_stack_build (the
  *     bandwidth-bound M = 1 decode, where bytes are time); BL_ERR_LAYOUT elsewhere.
+ *   BL_LAYOUT_KMAJOR (3): the transposed matrix, one row per input feature k (K rows, no padding
+ *     of K), each row the 2-bit codes of n = 0 .. Nq-1, Nq = N rounded up to a multiple of 64, packed
+ *     like layout 0 along n (byte index k*(Nq/4) + n/4, bits [2*(n%4), 2*(n%4)+1]), code 1 behind
+ *     column N: K*Nq/4 bytes.  For activations that are mostly zero (Section 2 takes squared ReLU
+ *     for the sparsity it gives the input of the down projection): the rows of zero activations
+ *     are never read.  N <= 3072.  Accepted by bl_pack_ternary, bl_unpack_ternary,
+ *     bl_packed_bytes and bl_stack_build; BL_ERR_LAYOUT elsewhere.
  * QUANTISED ACTIVATIONS are int8 [M][Kp]: leading dimension Kp, zeros in columns K..Kp-1 (what
  * bl_quant_act_int8 writes), so that a padded weight meets a zero.  Outputs are [M][N].
  *
@@ -83,7 +90,7 @@ typedef enum {
 
 typedef void* bl_stream;   /* hipStream_t */
 
-enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_K16 = 1, BL_LAYOUT_TRIT5 = 2 };
+enum { BL_LAYOUT_ROWMAJOR = 0, BL_LAYOUT_K16 = 1, BL_LAYOUT_TRIT5 = 2, BL_LAYOUT_KMAJOR = 3 };
 enum { BL_IN_FP32_LATENT = 0, BL_IN_INT8_TERNARY = 1 };
 enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_GEMV = 2, BL_OP_GEMM = 3 };
 
@@ -315,7 +322,7 @@ bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int6
  *                         in place; runs on one table must not overlap (they share the scratch). */
 enum { BL_STACK_MAX_COUNT = 1024 };
 typedef struct {
-    int32_t count, blocks, prep_count, inline_count, norm, lds_bytes, layout, reserved;
+    int32_t count, blocks, prep_count, inline_count, norm, lds_bytes, layout, red_ints;
     int64_t wg_offset, prep_offset;   /* byte offsets inside `table`                            */
     int64_t packed_bytes;             /* packed weight bytes of the products: what one run streams */
     int64_t table_bytes;

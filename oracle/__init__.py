@@ -202,6 +202,25 @@ def unpack_trit5(packed, N, K):
     return np.ascontiguousarray(Wt[:N, :K]), bad
 
 
+def pack_kmajor(Wt):
+    """k-major form (the library's layout 3, its own format): the transposed matrix, one row per input
+    feature k, each row padded with weight 0 to a multiple of 64 output features and packed along n
+    like layout 0 (Section 5.1: four 2-bit codes per byte).  Lets a decode kernel leave out the rows
+    of zero activations (Section 2: squared ReLU is chosen for the sparsity it gives)."""
+    Wt = _c(Wt, np.int8)
+    N, K = Wt.shape
+    Nq = -(-N // 64) * 64
+    T = np.zeros((K, Nq), dtype=np.int8)
+    T[:, :N] = Wt.T
+    return pack(T, 0)
+
+
+def unpack_kmajor(packed, N, K):
+    Nq = -(-N // 64) * 64
+    T, bad = unpack(packed, K, Nq, 0)
+    return np.ascontiguousarray(T[:, :N].T), bad
+
+
 def unpack(packed, N, K, layout=0):
     """Inverse of pack; returns (Wt int8 [N][K], number of invalid codes)."""
     packed = _c(packed, np.uint8)

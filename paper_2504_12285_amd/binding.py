@@ -10,7 +10,7 @@ import os
 from . import build as _build
 
 BL_OK = 0
-BL_LAYOUT_ROWMAJOR, BL_LAYOUT_K16, BL_LAYOUT_TRIT5 = 0, 1, 2
+BL_LAYOUT_ROWMAJOR, BL_LAYOUT_K16, BL_LAYOUT_TRIT5, BL_LAYOUT_KMAJOR = 0, 1, 2, 3
 BL_IN_FP32_LATENT, BL_IN_INT8_TERNARY = 0, 1
 BL_OP_PACK, BL_OP_QUANT, BL_OP_GEMV, BL_OP_GEMM = 0, 1, 2, 3
 
@@ -81,7 +81,7 @@ class StackPlan(ctypes.Structure):
     """Mirror of bl_stack_plan."""
     _fields_ = [("count", ctypes.c_int32), ("blocks", ctypes.c_int32), ("prep_count", ctypes.c_int32),
                 ("inline_count", ctypes.c_int32), ("norm", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
-                ("layout", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("layout", ctypes.c_int32), ("red_ints", ctypes.c_int32),
                 ("wg_offset", _i64), ("prep_offset", _i64),
                 ("packed_bytes", _i64), ("table_bytes", _i64)]
 
@@ -157,7 +157,7 @@ def bl_pack_ternary(W, layout=BL_LAYOUT_K16, beta=None):
     assert W.is_cuda and W.is_contiguous()
     nbytes = bl_packed_bytes(N, K, layout)
     if nbytes == 0:
-        raise BitLinearError(2 if layout in (0, 1, 2) else 3, "bl_packed_bytes")
+        raise BitLinearError(2 if layout in (0, 1, 2, 3) else 3, "bl_packed_bytes")
     packed = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
     if W.dtype == torch.float32:
         kind = BL_IN_FP32_LATENT

@@ -22,6 +22,7 @@ extern "C" const char* bl_status_str(int status) {
 extern "C" size_t bl_packed_bytes(int64_t N, int64_t K, int layout) {
     if (!bl_shape_ok(N, K)) return 0;
     if (layout == BL_LAYOUT_TRIT5) return (size_t)(bl_npad(N) * bl_kpad5(K) / 5);
+    if (layout == BL_LAYOUT_KMAJOR) return (size_t)(K * ((N + 63) / 64 * 16));
     if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16) return 0;
     return (size_t)(bl_npad(N) * bl_kpad(K) / 4);
 }

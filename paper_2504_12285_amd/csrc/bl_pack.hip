@@ -252,6 +252,55 @@ __global__ __launch_bounds__(PACK_THREADS) void bl_unpack_t5(const uint32_t* __r
     if (nbad) atomicAdd(bad, nbad);
 }
 
+/* ---- k-major form (BL_LAYOUT_KMAJOR, see bitlinear.h): the transposed matrix, one row per k ------
+ * One thread = one packed word = 16 consecutive n of one k. */
+template <int IN>
+__global__ __launch_bounds__(PACK_THREADS) void bl_pack_km(const void* __restrict__ Wv, const float* __restrict__ beta,
+                                                            int64_t N, int64_t K, int64_t wpr, int64_t words,
+                                                            uint32_t* __restrict__ packed) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const int64_t k = g / wpr, n0 = (g % wpr) * 16;
+    const float d = IN == 0 ? *beta + 1e-5f : 1.0f;
+    uint32_t word = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t n = n0 + i;
+        int t = 0;
+        if (n < N) {
+            if (IN == 0) {
+                float f = rintf(bl_div_rn(((const float*)Wv)[n * K + k], d));
+                f = fminf(fmaxf(f, -1.0f), 1.0f);
+                t = (int)f;
+            } else {
+                const int b = ((const int8_t*)Wv)[n * K + k];
+                t = b < -1 ? -1 : (b > 1 ? 1 : b);
+            }
+        }
+        word |= (uint32_t)(t + 1) << (2 * i);
+    }
+    packed[g] = word;
+}
+
+__global__ __launch_bounds__(PACK_THREADS) void bl_unpack_km(const uint32_t* __restrict__ packed, int64_t N, int64_t K,
+                                                              int64_t wpr, int64_t words, int8_t* __restrict__ Wt,
+                                                              int32_t* __restrict__ bad) {
+    const int64_t g = (int64_t)blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (g >= words) return;
+    const int64_t k = g / wpr, n0 = (g % wpr) * 16;
+    const uint32_t w = packed[g];
+    int nbad = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = (int)((w >> (2 * i)) & 3u);
+        if (n0 + i < N) {
+            nbad += (c == 3);
+            Wt[(n0 + i) * K + k] = (int8_t)(c - 1);
+        }
+    }
+    if (nbad) atomicAdd(bad, nbad);
+}
+
 __global__ void bl_zero_i32(int32_t* p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -261,12 +310,13 @@ extern "C" bl_status bl_pack_ternary(const void* W, int in_kind, int64_t N, int6
                                      uint8_t* packed, float* beta, void* workspace, bl_stream s) {
     if (!W || !packed || !beta) return BL_ERR_NULL;
     if (!bl_shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16 && layout != BL_LAYOUT_TRIT5) return BL_ERR_LAYOUT;
+    if (layout < BL_LAYOUT_ROWMAJOR || layout > BL_LAYOUT_KMAJOR) return BL_ERR_LAYOUT;
     if (in_kind != BL_IN_FP32_LATENT && in_kind != BL_IN_INT8_TERNARY) return BL_ERR_VALUE;
     if (!bl_aligned(W, 16) || !bl_aligned(packed, 16) || !bl_aligned(beta, 4)) return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
-    if (layout == BL_LAYOUT_TRIT5) {
-        const int64_t wpr = bl_kpad5(K) / 20, pwords = bl_npad(N) * wpr;
+    if (layout == BL_LAYOUT_TRIT5 || layout == BL_LAYOUT_KMAJOR) {
+        const bool km = layout == BL_LAYOUT_KMAJOR;
+        const int64_t wpr = km ? (N + 63) / 64 * 4 : bl_kpad5(K) / 20, pwords = (km ? K : bl_npad(N)) * wpr;
         const unsigned pgrid = (unsigned)((pwords + PACK_THREADS - 1) / PACK_THREADS);
         uint32_t* out = (uint32_t*)packed;
         if (in_kind == BL_IN_FP32_LATENT) {
@@ -277,9 +327,11 @@ extern "C" bl_status bl_pack_ternary(const void* W, int in_kind, int64_t N, int6
             const int np = (int)(count < BL_PACK_PARTIALS ? count : BL_PACK_PARTIALS);
             bl_abs_sum_partial_any<<<np, PACK_THREADS, 0, st>>>((const float*)W, count, partial);
             bl_abs_sum_final<<<1, PACK_THREADS, 0, st>>>(partial, np, (double)count, beta);
-            bl_pack_t5<0><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+            if (km) bl_pack_km<0><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+            else bl_pack_t5<0><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
         } else {
-            bl_pack_t5<1><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+            if (km) bl_pack_km<1><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
+            else bl_pack_t5<1><<<pgrid, PACK_THREADS, 0, st>>>(W, beta, N, K, wpr, pwords, out);
         }
         return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
     }
@@ -330,14 +382,16 @@ extern "C" bl_status bl_unpack_ternary(const uint8_t* packed, int64_t N, int64_t
                                        int8_t* Wt, int32_t* bad, bl_stream s) {
     if (!packed || !Wt || !bad) return BL_ERR_NULL;
     if (!bl_shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16 && layout != BL_LAYOUT_TRIT5) return BL_ERR_LAYOUT;
+    if (layout < BL_LAYOUT_ROWMAJOR || layout > BL_LAYOUT_KMAJOR) return BL_ERR_LAYOUT;
     if (!bl_aligned(packed, 16) || !bl_aligned(Wt, 16) || !bl_aligned(bad, 4)) return BL_ERR_ALIGN;
     hipStream_t st = (hipStream_t)s;
-    if (layout == BL_LAYOUT_TRIT5) {
-        const int64_t wpr = bl_kpad5(K) / 20, pwords = bl_npad(N) * wpr;
+    if (layout == BL_LAYOUT_TRIT5 || layout == BL_LAYOUT_KMAJOR) {
+        const bool km = layout == BL_LAYOUT_KMAJOR;
+        const int64_t wpr = km ? (N + 63) / 64 * 4 : bl_kpad5(K) / 20, pwords = (km ? K : bl_npad(N)) * wpr;
         const unsigned pgrid = (unsigned)((pwords + PACK_THREADS - 1) / PACK_THREADS);
         bl_zero_i32<<<1, 64, 0, st>>>(bad, 1);
-        bl_unpack_t5<<<pgrid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, N, K, wpr, pwords, Wt, bad);
+        if (km) bl_unpack_km<<<pgrid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, N, K, wpr, pwords, Wt, bad);
+        else bl_unpack_t5<<<pgrid, PACK_THREADS, 0, st>>>((const uint32_t*)packed, N, K, wpr, pwords, Wt, bad);
         return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
     }
     if (!bl_shape_unpadded(N, K)) {

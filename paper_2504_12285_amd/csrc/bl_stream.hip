@@ -46,6 +46,12 @@ struct bl_stream_item {
     float fixed_scale;        /* xbf16 only: > 0 replaces absmax/127 in the rescale */
     int N, nchunks, lgG, lp, layout, units;
     int qgroups;              /* 16-byte groups of the quantised row (its padded length / 16) */
+    /* k-major form only: partial sums of all workgroups, and what the finishing kernel reads */
+    int32_t* acc_ws;          /* [N] int32, zero between runs */
+    const int32_t* rowsum_fin;
+    const float* scale_fin;
+    int32_t* rowsum_pub;      /* bf16 input: where the owner workgroup publishes sum_k q and the scale */
+    float* scale_pub;
 };
 
 /* What the preparation kernel needs: the fused producer + quantiser of one product. */
@@ -560,26 +566,234 @@ void bl_stream_m1_t5(const bl_stream_item* __restrict__ items, const int2* __res
     }
 }
 
+/* ---- k-major form (BL_LAYOUT_KMAJOR): skipping the weights of zero activations -----------------
+ * Section 2 of the report takes squared ReLU in the feed-forward block for the sparsity it gives
+ * the activations of the down projection.  Stored k-major (one row of N codes per input feature k),
+ * the weights of a zero activation are simply not read.  A wave takes 64 consecutive k, finds the
+ * non-zero activations with one ballot and walks them four at a time: lane l loads its dword
+ * (16 output features) from each of the four rows, a byte permute puts the same byte of the four
+ * rows side by side, and the mask-only level trick of the other kernels turns that into operands
+ * of v_dot4_i32_i8 against the four activations (uniform, so they sit in a scalar register).
+ * Every workgroup holds partial sums over its own k range: they meet in LDS, then in an int32
+ * array in device memory (integer atomics: exact, order-free), and a small finishing kernel
+ * subtracts the row sum, rescales, adds the residual and clears the array for the next run. */
+template <int CB>
+__device__ __forceinline__ void bl_km_slice(const bl_stream_item& P, const int ub, const int ue,
+                                                int* __restrict__ Qs, int* __restrict__ misc,
+                                                int* __restrict__ red, const bool restage) {
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ncols = P.nchunks, N = P.N;
+    const uint32_t BL_G* const wbase = (const uint32_t BL_G*)P.packed;
+    int col[CB];
+    bool ok[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        const int c = 64 * j + lane;
+        ok[j] = c < ncols;
+        col[j] = ok[j] ? c : ncols - 1;
+    }
+    if (restage) __syncthreads();
+    /* the int8 row in its natural order, zeros up to the end of the last 64-wide k block */
+    {
+        const int groups = P.qgroups, lw = tid >> 6;
+        float* fs = (float*)(misc + 2);
+        int* ssum = misc + 6;
+        bl_v4i* Q4 = (bl_v4i*)Qs;
+        for (int u = groups + tid; u < P.units * 4; u += 256) Q4[u] = bl_v4i{0, 0, 0, 0};
+        for (int n = tid; n < ncols * 16; n += 256) red[n] = 0;
+        if (P.xbf16) {
+            const bl_gv4i* x = (const bl_gv4i*)P.xbf16;
+            auto ld = [&](int i) {
+                const bl_v4i v = x[i];
+                return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+            };
+            float mx = 0.0f;
+            for (int u = tid; u < groups; u += 256)
+                mx = fmaxf(mx, fmaxf(bl_absmax8_bf16(ld(2 * u)), bl_absmax8_bf16(ld(2 * u + 1))));
+            mx = bl_wave_max(mx);
+            if (lane == 0) fs[lw] = mx;
+            __syncthreads();
+            const float gamma = fmaxf(fmaxf(fs[0], fs[1]), fmaxf(fs[2], fs[3]));
+            const float gg = fmaxf(gamma, 1e-5f);
+            const float inv = bl_div_rn(127.0f, gg);
+            int part = 0;
+            for (int u = tid; u < groups; u += 256) {
+                uint32_t a0, a1, a2, a3;
+                bl_quant8_words(ld(2 * u), inv, a0, a1);
+                bl_quant8_words(ld(2 * u + 1), inv, a2, a3);
+                part += bl_sum16(a0, a1, a2, a3);
+                const bl_v4i qv = {(int)a0, (int)a1, (int)a2, (int)a3};
+                if (ub == 0 && P.q_out) *(bl_gv4i*)(P.q_out + u * 16) = qv;
+                Q4[u] = qv;
+            }
+            part = bl_wave_sum(part);
+            if (lane == 0) ssum[lw] = part;
+            __syncthreads();
+            if (tid == 0 && ub == 0) {
+                const float sc = bl_div_rn(gg, 127.0f);
+                *(int32_t BL_G*)P.rowsum_pub = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+                *(float BL_G*)P.scale_pub = P.fixed_scale > 0.0f ? P.fixed_scale : sc;
+                if (P.scale_out) *(float BL_G*)P.scale_out = sc;
+            }
+        } else {
+            const bl_gv4i* qg = (const bl_gv4i*)P.q;
+            for (int u = tid; u < groups; u += 256) Q4[u] = qg[u];
+        }
+        __syncthreads();
+    }
+    int A[CB][4][4];
+#pragma unroll
+    for (int j = 0; j < CB; ++j)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) A[j][b][t] = 0;
+
+    /* the stream of (four non-zero activations, their weight dwords): one step ahead of the arithmetic */
+    int u = ub + w, k0 = 0, qv = 0;
+    uint64_t mask = 0;
+    auto fetch = [&](uint32_t (*wv)[4], int& q4) -> bool {
+        while (mask == 0 && u < ue) {
+            k0 = u * 64;
+            qv = (int)((const int8_t*)Qs)[k0 + lane];
+            mask = __ballot(qv != 0);
+            u += 4;
+        }
+        if (mask == 0) return false;
+        int kk[4];
+        uint32_t q = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (mask) {
+                const int idx = __builtin_amdgcn_readfirstlane(__builtin_ctzll(mask));
+                mask &= mask - 1;
+                kk[i] = idx;
+                q |= ((uint32_t)__builtin_amdgcn_readlane(qv, idx) & 0xFFu) << (8 * i);
+            } else {
+                kk[i] = kk[0];                    /* a valid row; its activation byte stays 0 */
+            }
+        }
+        q4 = (int)q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t BL_G* row = wbase + (int64_t)(k0 + kk[i]) * ncols;
+#pragma unroll
+            for (int j = 0; j < CB; ++j) wv[j][i] = __builtin_nontemporal_load(row + col[j]);
+        }
+        return true;
+    };
+    auto compute = [&](const uint32_t (*wv)[4], const int q4) {
+#pragma unroll
+        for (int j = 0; j < CB; ++j)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                /* byte b of the four rows side by side: byte i of R = codes of (k_i, n = 16c + 4b + 0..3) */
+                const uint32_t sel = 0x0C0C0400u + 0x0101u * (uint32_t)b;         /* [s1.b, s0.b, 0, 0] */
+                const uint32_t lo = __builtin_amdgcn_perm(wv[j][1], wv[j][0], sel);
+                const uint32_t hi = __builtin_amdgcn_perm(wv[j][3], wv[j][2], sel);
+                const uint32_t R = lo | (hi << 16);
+                A[j][b][0] = __builtin_amdgcn_sdot4((int)(R & 0x03030303u), q4, A[j][b][0], false);
+                A[j][b][1] = __builtin_amdgcn_sdot4((int)(R & 0x0C0C0C0Cu), q4, A[j][b][1], false);
+                A[j][b][2] = __builtin_amdgcn_sdot4((int)(R & 0x30303030u), q4, A[j][b][2], false);
+                A[j][b][3] = __builtin_amdgcn_sdot4((int)((R >> 2) & 0x30303030u), q4, A[j][b][3], false);
+            }
+    };
+    uint32_t wa[CB][4], wb[CB][4];
+    int qa = 0, qb = 0;
+    bool have = fetch(wa, qa);
+    while (have) {
+        const bool have2 = fetch(wb, qb);
+        compute(wa, qa);
+        if (!have2) break;
+        have = fetch(wa, qa);
+        compute(wb, qb);
+    }
+    /* partial sums of the four waves meet in LDS, then go to the product's int32 array */
+#pragma unroll
+    for (int j = 0; j < CB; ++j)
+        if (ok[j]) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int n0 = 16 * (64 * j + lane) + 4 * b;
+                const int v0 = A[j][b][0], v1 = A[j][b][1] >> 2, v2 = A[j][b][2] >> 4, v3 = A[j][b][3] >> 4;
+                if (v0) atomicAdd(red + n0, v0);
+                if (v1) atomicAdd(red + n0 + 1, v1);
+                if (v2) atomicAdd(red + n0 + 2, v2);
+                if (v3) atomicAdd(red + n0 + 3, v3);
+            }
+        }
+    __syncthreads();
+    for (int n = tid; n < N; n += 256) {
+        const int v = red[n];
+        if (v) atomicAdd((int32_t*)P.acc_ws + n, v);
+    }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void bl_stream_m1_km(const bl_stream_item* __restrict__ items, const int2* __restrict__ wgstart, const int q_ints,
+                     const int red_ints) {
+    extern __shared__ int lds[];
+    int* Qs = lds;
+    int* red = lds + q_ints;
+    int* misc = red + red_ints;
+    const int2 s0 = wgstart[blockIdx.x], s1 = wgstart[blockIdx.x + 1];
+    const int p_first = __builtin_amdgcn_readfirstlane(s0.x), u_first = __builtin_amdgcn_readfirstlane(s0.y);
+    const int p_last = __builtin_amdgcn_readfirstlane(s1.x), u_last = __builtin_amdgcn_readfirstlane(s1.y);
+    bool staged = false;
+    for (int pi = p_first; pi <= p_last; ++pi) {
+        if (pi == p_last && u_last == 0) break;
+        const bl_stream_item P = items[pi];
+        const int ub = pi == p_first ? u_first : 0;
+        const int ue = pi == p_last ? u_last : P.units;
+        if (ub >= ue) continue;
+        switch (P.lp) {
+            case 1: bl_km_slice<1>(P, ub, ue, Qs, misc, red, staged); break;
+            case 2: bl_km_slice<2>(P, ub, ue, Qs, misc, red, staged); break;
+            default: bl_km_slice<3>(P, ub, ue, Qs, misc, red, staged); break;
+        }
+        staged = true;
+    }
+}
+
+/* Finishing kernel of the k-major form: grid (ceil(max N / 256), products). */
+__global__ __launch_bounds__(256) void bl_km_finish(const bl_stream_item* __restrict__ items) {
+    const bl_stream_item& P = items[blockIdx.y];
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= P.N) return;
+    const int val = P.acc_ws[n] - *P.rowsum_fin;
+    P.acc_ws[n] = 0;
+    if (P.acc) P.acc[n] = val;
+    if (P.y) {
+        const float cf = *P.beta * *P.scale_fin;
+        const float t = (float)val * cf;
+        P.y[n] = P.residual ? P.residual[n] + t : t;
+    }
+}
+
 /* ---- host side ---------------------------------------------------------------------------- */
 
 #define BL_STREAM_LMAX 5
 #define BL_STREAM_MAX_BLOCKS 4096
-#define BL_STREAM_LDS_BYTES ((max_chunks + 1) * (layout == BL_LAYOUT_TRIT5 ? BL_T5_QSTRIDE : BL_QSTRIDE) * 4 + 64)
+#define BL_STREAM_LDS_BYTES                                                                          \
+    (layout == BL_LAYOUT_KMAJOR ? max_units * 64 + max_cols * 64 + 64                                \
+                                : (max_chunks + 1) * (layout == BL_LAYOUT_TRIT5 ? BL_T5_QSTRIDE : BL_QSTRIDE) * 4 + 64)
+#define BL_KM_MAX_N 3072      /* k-major form: at most three dword columns of 64 lanes per weight row (48 sums per lane) */
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-/* Device buffer layout: [items][slice table][preparation items][rowsum_ws][scale_ws][q_ws]. */
+/* Device buffer layout: [items][slice table][preparation items][rowsum_ws][scale_ws][q_ws][acc_ws]. */
 struct bl_stream_layout {
-    size_t wg_off, prep_off, rowsum_off, scale_off, q_off, total;
+    size_t wg_off, prep_off, rowsum_off, scale_off, q_off, acc_off, total;
 };
-static bl_stream_layout stream_layout(int count, size_t q_bytes) {
+static bl_stream_layout stream_layout(int count, size_t q_bytes, size_t acc_bytes = 0) {
     bl_stream_layout L;
     L.wg_off = align_up((size_t)count * sizeof(bl_stream_item), 256);
     L.prep_off = L.wg_off + align_up((size_t)(BL_STREAM_MAX_BLOCKS + 1) * sizeof(int2), 256);
     L.rowsum_off = L.prep_off + align_up((size_t)count * sizeof(bl_stream_prep_item), 256);
     L.scale_off = L.rowsum_off + align_up((size_t)count * 4, 256);
     L.q_off = L.scale_off + align_up((size_t)count * 4, 256);
-    L.total = L.q_off + align_up(q_bytes, 256);
+    L.acc_off = L.q_off + align_up(q_bytes, 256);
+    L.total = L.acc_off + align_up(acc_bytes, 256);
     return L;
 }
 
@@ -593,7 +807,8 @@ static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
     if (!fused && d.y && !d.scale) return BL_ERR_NULL;
     if (!bl_shape_ok(d.N, d.K) || d.K > 64 * 64 * BL_STREAM_LMAX || d.N > (1 << 28)) return BL_ERR_SHAPE;
     if (fused && d.K % 64 != 0) return BL_ERR_SHAPE;     /* bf16 / producer rows are read 16 elements at a time */
-    if (layout != BL_LAYOUT_ROWMAJOR && layout != BL_LAYOUT_K16 && layout != BL_LAYOUT_TRIT5) return BL_ERR_LAYOUT;
+    if (layout == BL_LAYOUT_KMAJOR && d.N > BL_KM_MAX_N) return BL_ERR_SHAPE;
+    if (layout < BL_LAYOUT_ROWMAJOR || layout > BL_LAYOUT_KMAJOR) return BL_ERR_LAYOUT;
     if (!bl_aligned(d.packed, 16) || !bl_aligned(d.X, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.q_out, 16) ||
         !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) || !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) ||
         !bl_aligned(d.rowsum, 4) || !bl_aligned(d.scale_out, 4) || !bl_aligned(d.residual, 4))
@@ -603,12 +818,13 @@ static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
 
 extern "C" size_t bl_stack_table_bytes(const bl_decode_desc* descs, int count) {
     if (!descs || count < 1 || count > BL_STACK_MAX_COUNT) return 0;
-    size_t q_bytes = 0;
+    size_t q_bytes = 0, acc_bytes = 0;
     for (int i = 0; i < count; ++i) {
-        if (descs[i].K < 1 || descs[i].K > 64 * 64 * BL_STREAM_LMAX) return 0;
+        if (descs[i].K < 1 || descs[i].K > 64 * 64 * BL_STREAM_LMAX || descs[i].N < 1 || descs[i].N > (1 << 28)) return 0;
         if (desc_is_fused(descs[i])) q_bytes += align_up((size_t)descs[i].K, 256);
+        acc_bytes += align_up((size_t)descs[i].N * 4, 256);     /* partial sums of the k-major form */
     }
-    return stream_layout(count, q_bytes).total;
+    return stream_layout(count, q_bytes, acc_bytes).total;
 }
 
 extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int layout, int64_t M, void* table,
@@ -616,17 +832,19 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     if (!descs || !table || !plan) return BL_ERR_NULL;
     if (count < 1 || count > BL_STACK_MAX_COUNT || M != 1) return BL_ERR_SHAPE;
     if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
-    size_t q_bytes = 0;
+    size_t q_bytes = 0, acc_bytes = 0;
     for (int i = 0; i < count; ++i) {
         const bl_status st = check_stack_desc(descs[i], layout);
         if (st != BL_OK) return st;
         if (desc_is_fused(descs[i])) q_bytes += align_up((size_t)descs[i].K, 256);
+        acc_bytes += align_up((size_t)descs[i].N * 4, 256);
     }
-    const bl_stream_layout L = stream_layout(count, q_bytes);
+    const bl_stream_layout L = stream_layout(count, q_bytes, acc_bytes);
     uint8_t* const dev_base = (uint8_t*)table;
     std::vector<bl_stream_item> items((size_t)count);
     std::vector<bl_stream_prep_item> preps;
-    int inline_count = 0, max_chunks = 0;
+    int inline_count = 0, max_chunks = 0, max_units = 0, max_cols = 0;
+    size_t acc_used = 0;
     std::vector<int64_t> unit_bytes((size_t)count);
     bool any_norm = false;
     int64_t total = 0, packed_bytes = 0, total_units = 0;
@@ -644,23 +862,43 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
         it.y = d.y;
         it.N = (int)d.N;
         /* 16-byte loads per weight row: 64 weights each, or 80 in the five-per-byte form */
-        const int64_t row_bytes = layout == BL_LAYOUT_TRIT5 ? bl_kpad5(d.K) / 5 : Kp / 4;
+        const int64_t row_bytes = layout == BL_LAYOUT_TRIT5    ? bl_kpad5(d.K) / 5
+                                  : layout == BL_LAYOUT_KMAJOR ? (d.N + 63) / 64 * 16
+                                                               : Kp / 4;
         it.nchunks = (int)(row_bytes / 16);
         it.qgroups = (int)(Kp / 16);
         if (it.nchunks > max_chunks) max_chunks = it.nchunks;
         it.layout = layout;
         int lgG = 3;
         while (((it.nchunks + (1 << lgG) - 1) >> lgG) > BL_STREAM_LMAX) ++lgG;   /* K bound checked: lgG <= 6 */
-        const int R = 64 >> lgG;
+        int R = 64 >> lgG;
         it.lgG = lgG;
         it.lp = (it.nchunks + (1 << lgG) - 1) >> lgG;
         it.units = (it.N + R - 1) / R;
+        if (layout == BL_LAYOUT_KMAJOR) {
+            /* one row per k: dword columns of 16 output features; a unit is 64 consecutive k */
+            const int ncols = (int)((d.N + 63) / 64 * 4);
+            it.nchunks = ncols;
+            it.lp = (ncols + 63) / 64;
+            it.units = (int)(Kp / 64);
+            it.acc_ws = (int32_t*)(dev_base + L.acc_off + acc_used);
+            acc_used += align_up((size_t)d.N * 4, 256);
+            if (it.units > max_units) max_units = it.units;
+            if (ncols > max_cols) max_cols = ncols;
+            R = 64;                                          /* weight rows of a unit */
+        }
         if (fused && d.prod.in0 == nullptr) {
             /* a plain bf16 row: quantised inside the stream launch by each workgroup that meets it */
             it.xbf16 = d.X;
             it.q_out = d.q_out;
             it.scale_out = d.scale_out;
             it.fixed_scale = d.fixed_scale;
+            it.rowsum_pub = (int32_t*)(dev_base + L.rowsum_off) + i;
+            it.scale_pub = (float*)(dev_base + L.scale_off) + i;
+            if (layout == BL_LAYOUT_KMAJOR) {                /* read back by the finishing kernel */
+                it.rowsum = it.rowsum_pub;
+                it.scale = it.scale_pub;
+            }
             ++inline_count;
         } else if (fused || !d.rowsum) {
             bl_stream_prep_item pp;
@@ -691,10 +929,12 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
             it.scale = d.scale;
             it.rowsum = d.rowsum;
         }
+        it.rowsum_fin = it.rowsum;
+        it.scale_fin = it.scale ? it.scale : it.beta;        /* unused without y; a valid address */
         unit_bytes[(size_t)i] = (int64_t)R * row_bytes;
         total += (int64_t)it.units * unit_bytes[(size_t)i];
         total_units += it.units;
-        packed_bytes += d.N * row_bytes;
+        packed_bytes += (layout == BL_LAYOUT_KMAJOR ? d.K : d.N) * row_bytes;
         items[(size_t)i] = it;
     }
     /* persistent grid: the workgroups that are resident at once, but no more than one per four
@@ -703,7 +943,11 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &per_cu, layout == BL_LAYOUT_TRIT5 ? (const void*)bl_stream_m1_t5 : (const void*)bl_stream_m1, 256,
+            &per_cu,
+            layout == BL_LAYOUT_TRIT5    ? (const void*)bl_stream_m1_t5
+            : layout == BL_LAYOUT_KMAJOR ? (const void*)bl_stream_m1_km
+                                         : (const void*)bl_stream_m1,
+            256,
             (size_t)BL_STREAM_LDS_BYTES) != hipSuccess ||
         cus < 1 || per_cu < 1)
         return BL_ERR_HIP;
@@ -774,6 +1018,9 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     memcpy(blob.data() + L.wg_off, wg.data(), wg.size() * sizeof(int2));
     if (!preps.empty()) memcpy(blob.data() + L.prep_off, preps.data(), preps.size() * sizeof(bl_stream_prep_item));
     hipStream_t st = (hipStream_t)s;
+    /* the k-major form's partial sums start at zero; every run leaves them at zero again */
+    if (layout == BL_LAYOUT_KMAJOR && hipMemsetAsync(dev_base + L.acc_off, 0, acc_bytes, st) != hipSuccess)
+        return BL_ERR_HIP;
     if (hipMemcpyAsync(table, blob.data(), blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return BL_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return BL_ERR_HIP;   /* the host copy of the table dies here */
 
@@ -785,6 +1032,7 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     plan->norm = any_norm ? 1 : 0;
     plan->lds_bytes = BL_STREAM_LDS_BYTES;
     plan->layout = layout;
+    plan->red_ints = layout == BL_LAYOUT_KMAJOR ? max_cols * 16 : 0;
     plan->wg_offset = (int64_t)L.wg_off;
     plan->prep_offset = (int64_t)L.prep_off;
     plan->packed_bytes = packed_bytes;
@@ -797,8 +1045,9 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
     if (plan->count < 1 || plan->count > BL_STACK_MAX_COUNT || plan->blocks < 1 ||
         plan->blocks > BL_STREAM_MAX_BLOCKS || plan->prep_count < 0 || plan->inline_count < 0 ||
         plan->prep_count + plan->inline_count > plan->count || plan->lds_bytes < 64 ||
-        plan->lds_bytes > 64 + (64 * BL_STREAM_LMAX + 1) * BL_T5_QSTRIDE * 4 || plan->lds_bytes % 16 ||
-        plan->layout < 0 || plan->layout > BL_LAYOUT_TRIT5)
+        plan->lds_bytes > 48 * 1024 || plan->lds_bytes % 16 ||
+        plan->layout < 0 || plan->layout > BL_LAYOUT_KMAJOR || plan->red_ints < 0 || plan->red_ints > BL_KM_MAX_N ||
+        (plan->layout == BL_LAYOUT_KMAJOR && (plan->red_ints < 64 || plan->lds_bytes < 64 + 64 + plan->red_ints * 4)))
         return BL_ERR_VALUE;
     const bl_stream_layout L = stream_layout(plan->count, 0);
     if (plan->wg_offset != (int64_t)L.wg_off || plan->prep_offset != (int64_t)L.prep_off) return BL_ERR_VALUE;
@@ -811,7 +1060,14 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
         else bl_stream_prep<false><<<plan->prep_count, 256, 0, st>>>(pp);
         if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
     }
-    if (plan->layout == BL_LAYOUT_TRIT5)
+    if (plan->layout == BL_LAYOUT_KMAJOR) {
+        bl_stream_m1_km<<<plan->blocks, 256, (size_t)plan->lds_bytes, st>>>(
+            (const bl_stream_item*)base, (const int2*)(base + L.wg_off), (plan->lds_bytes - 64) / 4 - plan->red_ints,
+            plan->red_ints);
+        if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
+        bl_km_finish<<<dim3((unsigned)((plan->red_ints + 255) / 256), (unsigned)plan->count), 256, 0, st>>>(
+            (const bl_stream_item*)base);
+    } else if (plan->layout == BL_LAYOUT_TRIT5)
         bl_stream_m1_t5<<<plan->blocks, 256, (size_t)plan->lds_bytes, st>>>(
             (const bl_stream_item*)base, (const int2*)(base + L.wg_off), (plan->lds_bytes - 64) / 4);
     else

@@ -22,6 +22,8 @@ class Case:
             self.y = oracle.rescale(self.acc, self.beta, self.scale)
 
     def packed(self, layout):
+        if layout == 3:
+            return oracle.pack_kmajor(self.Wt)
         return oracle.pack_trit5(self.Wt) if layout == 2 else oracle.pack_padded(self.Wt, layout)
 
 

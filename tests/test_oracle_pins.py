@@ -588,3 +588,19 @@ def test_trit5_positions_padding_and_round_trip():
     p[3] = 129                                                # 129 -> digits of v = 122 -> re-encodes to 129: valid
     p[5] = 1                                                  # 1 is not ceil(v*256/243) of any v (v=0 -> 0, v=1 -> 2)
     assert oracle.unpack_trit5(p, 4, 80)[1] == 1
+
+
+def test_kmajor_form_is_the_packed_transpose():
+    """Layout 3 by hand: weight (n, k) sits in byte k*(Nq/4) + n/4 at bits 2*(n%4); padding decodes to 0."""
+    rng = np.random.default_rng(17)
+    N, K = 70, 9
+    Wt = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+    p = oracle.pack_kmajor(Wt)
+    Nq = 128
+    assert p.size == K * Nq // 4
+    for k in range(K):
+        for n in range(Nq):
+            code = (int(p[k * (Nq // 4) + n // 4]) >> (2 * (n % 4))) & 3
+            assert code == (int(Wt[n, k]) + 1 if n < N else 1)
+    back, bad = oracle.unpack_kmajor(p, N, K)
+    assert bad == 0 and np.array_equal(back, Wt)
