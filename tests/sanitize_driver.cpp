@@ -97,7 +97,7 @@ int main() {
     /* host-only entry points of the library */
     CHECK(bl_packed_bytes(2560, 2560, 1) == 2560 * 2560 / 4);
     CHECK(bl_packed_bytes(6, 64, 0) == 8 * 64 / 4 && bl_packed_bytes(0, 64, 0) == 0);
-    CHECK(bl_packed_bytes(2560, 6912, 2) == 2560 * 6960 / 5 && bl_padded_k(65) == 128 && bl_packed_bytes(4, 64, 3) == 0);
+    CHECK(bl_packed_bytes(2560, 6912, 2) == 2560 * 6960 / 5 && bl_padded_k(65) == 128 && bl_packed_bytes(4, 64, 7) == 0 && bl_packed_bytes(2560, 6912, 3) == 6912 * 2560 / 4);
     CHECK(bl_workspace_bytes(BL_OP_GEMM, 2048, 64, 64) >= 2048 * 4);
     CHECK(bl_status_str(BL_ERR_SHAPE) != nullptr && bl_version() >= 100);
     CHECK(bl_debug_force_path(9) == BL_ERR_VALUE && bl_debug_force_path(0) == BL_OK);
