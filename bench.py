@@ -457,6 +457,27 @@ def main():
             torch.cuda.synchronize()
             dt = e0.elapsed_time(e1) * 1e-3 / nl
             per_shape[name] = {"us": round(dt * 1e6, 2), "tops": round(2.0 * Mp * b.N * b.K / dt / 1e12, 1)}
+        # the clock the tile kernel actually runs at: workgroup 0 of every launch counts shader
+        # clocks and ticks of the constant-rate wall clock (the chip lowers its clock under the
+        # power this kernel draws, so the datasheet peak at 2.4 GHz is not what it is offered)
+        wall_khz = lib.bl_probe_wall_clock_khz()
+        stamps = torch.zeros(2, dtype=torch.int64, device=dev)
+        if wall_khz > 0:
+            assert lib.bl_debug_clock_stamps(stamps.data_ptr()) == 0
+            for name in SHAPE_ORDER:
+                b = pre[name]
+                mhz = []
+                for i in range(nl):
+                    rc = lib.bl_gemm_w158a8(layers[i].packed[name].data_ptr(), layers[i].beta[name].data_ptr(), layout,
+                                            b.q.data_ptr(), b.scale.data_ptr(), b.rowsum.data_ptr(), Mp, b.N, b.K,
+                                            None, b.y.data_ptr(), None, torch.cuda.current_stream().cuda_stream)
+                    assert rc == 0, rc
+                    if i >= nl // 2:
+                        c, w = stamps.tolist()
+                        if w > 0:
+                            mhz.append(c / (w / (wall_khz * 1e3)) / 1e6)
+                per_shape[name]["clock_mhz"] = round(float(np.median(mhz)), 0) if mhz else None
+            assert lib.bl_debug_clock_stamps(None) == 0
         # achievable roof of the matrix cores: a register-resident loop of the same MFMA instruction
         import ctypes
         mops = ctypes.c_double(0)
@@ -469,8 +490,25 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         mfma_roof = mops.value / (e0.elapsed_time(e1) * 1e-3 / 3) / 1e12
-        log("[bench] prefill M=%d: %.1f us/layer, %.1f TOPS (MFMA-only loop: %.0f); %s"
-            % (Mp, t_pre * 1e6, tops, mfma_roof, per_shape))
+        # the same loop on random int8 operands (the activations of this workload for one operand
+        # and ternary codes for the other would sit between the two), with the clock it ran at
+        rnd = torch.randint(-127, 128, (65536,), dtype=torch.int8, device=dev)
+        lib.bl_probe_mfma_i8_ex(20000, rnd.data_ptr(), stamps.data_ptr(), sink.data_ptr(), None,
+                                torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            lib.bl_probe_mfma_i8_ex(20000, rnd.data_ptr(), stamps.data_ptr(), sink.data_ptr(), None,
+                                    torch.cuda.current_stream().cuda_stream)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_roof_rnd = mops.value / (e0.elapsed_time(e1) * 1e-3 / 3) / 1e12
+        c, w = stamps.tolist()
+        mfma_rnd_mhz = round(c / (w / (wall_khz * 1e3)) / 1e6, 0) if wall_khz > 0 and w > 0 else None
+        clocks = [v.get("clock_mhz") for v in per_shape.values() if v.get("clock_mhz")]
+        kernel_mhz = float(np.mean(clocks)) if clocks else None
+        log("[bench] prefill M=%d: %.1f us/layer, %.1f TOPS (MFMA-only loop: %.0f, on random operands %.0f at %s MHz; tile kernel at %s MHz); %s"
+            % (Mp, t_pre * 1e6, tops, mfma_roof, mfma_roof_rnd, mfma_rnd_mhz, kernel_mhz, per_shape))
         out["prefill"] = {"workload": "config 3: M=%d, four layer shapes, int8 q + per-row scales -> fp32 y" % Mp,
                           "tops": round(tops, 2), "unit": "TOP/s", "us_per_layer": round(t_pre * 1e6, 2),
                           "per_shape": per_shape,
@@ -478,7 +516,13 @@ def main():
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
                                        "traffic": profiled_traffic("bl_gemm_tile256:layer_m2048") if Mp == 2048 else None,
                                        "kernel": "bl_gemm_tile256", "achievable": round(mfma_roof, 1),
-                                       "frac_of_achievable": round(tops / mfma_roof, 4)}}
+                                       "frac_of_achievable": round(tops / mfma_roof, 4),
+                                       "achievable_random_operands": round(mfma_roof_rnd, 1),
+                                       "achievable_random_operands_clock_mhz": mfma_rnd_mhz,
+                                       "frac_of_achievable_random_operands": round(tops / mfma_roof_rnd, 4),
+                                       "kernel_clock_mhz": round(kernel_mhz, 0) if kernel_mhz else None,
+                                       "peak_at_kernel_clock": round(INT8_PEAK_TOPS * kernel_mhz / 2400.0, 1) if kernel_mhz else None,
+                                       "frac_at_kernel_clock": round(tops / (INT8_PEAK_TOPS * kernel_mhz / 2400.0), 4) if kernel_mhz else None}}
 
     # ------------------------------------------- config 2: batched decode, M in {8, 32, 64}
     if not args.no_batched:

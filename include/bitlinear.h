@@ -362,10 +362,28 @@ bl_status bl_debug_force_path(int path);
  *   bl_probe_mfma_i8      one launch of `iters` x 4 back-to-back v_mfma_i32_32x32x32_i8 per
  *                         wave, operands in registers; *ops (HOST, optional) receives the
  *                         integer operations of the launch (2 per multiply-accumulate).
+ *   bl_probe_mfma_i8_ex   the same loop with its operands read once from `operands` (device,
+ *                         64 KiB of int8, or NULL for the constants of bl_probe_mfma_i8): with
+ *                         random operands the loop draws more power and the chip runs it at a
+ *                         lower clock, which is the rate a real contraction can hope for.
+ *                         stamps (device, 2 x int64, or NULL) receives what workgroup 0 counted
+ *                         between its first and last instruction: [0] shader clocks, [1] ticks of
+ *                         the constant-rate wall clock (bl_probe_wall_clock_khz), so
+ *                         stamps[0] / stamps[1] x that rate is the clock the kernel ran at.
+ *   bl_probe_wall_clock_khz  rate of that wall clock in kHz (0 on error).  Host-only query.
+ *   bl_debug_clock_stamps  measurement hook for the prefill tile kernel: while a device buffer
+ *                         of 2 x int64 is registered, every launch of that kernel (bl_gemm_w158a8
+ *                         and its variants on the direct-to-LDS path) leaves the same two counts
+ *                         of its workgroup 0 there; NULL (the default) switches it off.
+ *                         Process-wide and atomic; results never depend on it.
  * sink: device, 64 int32, never written in practice (it keeps the work observable). */
 bl_status bl_probe_stream_read(const void* buf, size_t bytes, int workgroups_per_cu, int32_t* sink,
                                bl_stream s);
 bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s);
+bl_status bl_probe_mfma_i8_ex(int iters, const void* operands, int64_t* stamps, int32_t* sink, double* ops /* HOST */,
+                              bl_stream s);
+int       bl_probe_wall_clock_khz(void);
+bl_status bl_debug_clock_stamps(int64_t* stamps);
 
 #ifdef __cplusplus
 }

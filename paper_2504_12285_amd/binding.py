@@ -40,6 +40,9 @@ SIGNATURES = {
     "bl_debug_force_path": (_ci, [_ci]),
     "bl_probe_stream_read": (_ci, [_vp, _sz, _ci, _vp, _vp]),
     "bl_probe_mfma_i8": (_ci, [_ci, _vp, _vp, _vp]),
+    "bl_probe_mfma_i8_ex": (_ci, [_ci, _vp, _vp, _vp, _vp, _vp]),
+    "bl_probe_wall_clock_khz": (_ci, []),
+    "bl_debug_clock_stamps": (_ci, [_vp]),
     "bl_gemm_w158a8_noalloc": (_ci, [_vp, _vp, _ci, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
 }
 

@@ -47,3 +47,12 @@ extern "C" bl_status bl_debug_force_path(int path) {
     g_forced_decode_path.store(path, std::memory_order_relaxed);
     return BL_OK;
 }
+
+/* Measurement hook: where the prefill tile kernel leaves the clock counts of its workgroup 0. */
+static std::atomic<int64_t*> g_clock_stamps{nullptr};
+int64_t* bl_clock_stamps(void) { return g_clock_stamps.load(std::memory_order_relaxed); }
+extern "C" bl_status bl_debug_clock_stamps(int64_t* stamps) {
+    if (!bl_aligned(stamps, 8)) return BL_ERR_ALIGN;
+    g_clock_stamps.store(stamps, std::memory_order_relaxed);
+    return BL_OK;
+}

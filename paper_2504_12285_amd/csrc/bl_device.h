@@ -82,6 +82,10 @@ typedef __attribute__((address_space(3))) void* bl_lptr;
 /* s_waitcnt vmcnt(n) only, n < 64: expcnt = 7, lgkmcnt = 15 left open (gfx9 encoding:
  * vmcnt bits 3:0 in imm[3:0], bits 5:4 in imm[15:14]) */
 #define BL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+/* s_waitcnt lgkmcnt(0) only (vmcnt = 63 and expcnt = 7 left open): a wave's own LDS writes have
+ * been performed.  A raw s_barrier does not imply it, so a wave that hands data to other waves
+ * through LDS waits with this in front of the barrier. */
+#define BL_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
 /* Waits until at most r stages of LOADS direct loads each are still in flight (r <= J). */
 template <int J, int LOADS>

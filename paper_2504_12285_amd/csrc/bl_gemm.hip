@@ -241,7 +241,8 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                                                                 int K, int tiles_m, int tiles_n, int gm,
                                                                 int vgrid, const float* __restrict__ residual,
                                                                 int32_t* __restrict__ acc, float* __restrict__ y,
-                                                                uint16_t* __restrict__ xb, int* __restrict__ absmax) {
+                                                                uint16_t* __restrict__ xb, int* __restrict__ absmax,
+                                                                long long* __restrict__ stamps) {
     static_assert(EPI != 2 || (BN == 128 && WN == 2 && BN / WN / 32 == 2), "the gate epilogue pairs ni = 0 with ni = 1");
     constexpr int NW = WM * WN, THREADS = NW * 64;
     constexpr int G3_BM = BM, G3_A_BYTES = BM * G3_BK;
@@ -338,6 +339,14 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
     int tm, tn;
     int vb = next_tile((int)blockIdx.x, tm, tn);
     if (vb < 0) return;
+    /* measurement hook: workgroup 0 counts shader clocks and wall-clock ticks over its lifetime
+     * (a wave-uniform test, so the counts stay in scalar registers) */
+    const bool stamp = stamps != nullptr && blockIdx.x == 0;
+    long long c_start = 0, w_start = 0;
+    if (stamp) {
+        c_start = clock64();
+        w_start = wall_clock64();
+    }
     setup(tm, tn);
     /* STAGES - 1 k steps are in flight ahead of the matrix cores: a k step of one workgroup
      * takes far less time than a load, so the depth, not the tile, hides the latency */
@@ -396,6 +405,9 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
             rs_s[tid] = row_rs;
             cf_s[tid] = row_cf;
         }
+        /* these LDS writes must have been performed before any wave passes the barrier (a raw
+         * s_barrier does not wait for them) */
+        BL_WAIT_LGKM0();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -529,7 +541,13 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                     }
                 }
         }
-        if (vb2 < 0) break;
+        if (vb2 < 0) {
+            if (stamp && tid == 0) {
+                stamps[0] = clock64() - c_start;
+                stamps[1] = wall_clock64() - w_start;
+            }
+            break;
+        }
         vb = vb2;
         tm = tm2;
         tn = tn2;
@@ -582,7 +600,7 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     }
     if (blocks > vgrid) blocks = vgrid;
     kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, vgrid,
-                                            residual, acc, y, ep.xb, ep.absmax);
+                                            residual, acc, y, ep.xb, ep.absmax, (long long*)bl_clock_stamps());
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 

@@ -23,3 +23,6 @@ static inline bool bl_aligned(const void* p, uintptr_t a) { return ((uintptr_t)p
  * 0 = the measured default, 1 = dot4 kernel where it applies, 2 = row-resident matrix-core
  * kernel, 3 = streaming panel kernel where it applies.  Process-wide, atomic. */
 int bl_forced_decode_path(void);
+/* Measurement hook (bl_debug_clock_stamps): device buffer for the clock counts of the prefill
+ * tile kernel, or NULL (the default).  Process-wide, atomic. */
+int64_t* bl_clock_stamps(void);

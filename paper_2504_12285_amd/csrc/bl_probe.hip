@@ -63,11 +63,27 @@ extern "C" int bl_probe_rows(const void* buf, size_t bytes, int per_cu, int mode
 }
 #endif
 
-/* Four independent accumulator chains per wave, operands in registers. */
-__global__ __launch_bounds__(256) void bl_probe_mfma_kernel(int iters, int32_t* __restrict__ sink) {
+/* Four independent accumulator chains per wave, operands in registers: constants made from the
+ * lane number, or (operands != NULL) 32 bytes per lane read once from memory, e.g. random int8
+ * values: the rate of this loop depends on the switching activity of its operands, because the
+ * chip lowers its clock under the power such a loop draws.  stamps (or NULL) receives what
+ * workgroup 0 counted: shader clocks and ticks of the constant-rate wall clock. */
+__global__ __launch_bounds__(256) void bl_probe_mfma_kernel(int iters, const bl_v4i* __restrict__ operands,
+                                                             long long* __restrict__ stamps,
+                                                             int32_t* __restrict__ sink) {
     const int lane = threadIdx.x & 63;
     bl_v4i a = {lane * 0x01010101, (lane + 3) * 0x01010101, (lane ^ 21) * 0x01010101, (lane + 9) * 0x01010101};
     bl_v4i b = {0x01020001, 0x00010201, 0x02000102, 0x01010200};
+    if (operands) {
+        a = operands[(blockIdx.x & 7) * 512 + threadIdx.x * 2];
+        b = operands[(blockIdx.x & 7) * 512 + threadIdx.x * 2 + 1];
+    }
+    const bool stamp = stamps != nullptr && blockIdx.x == 0;          /* uniform: the counters stay scalar */
+    long long c_start = 0, w_start = 0;
+    if (stamp) {
+        c_start = clock64();
+        w_start = wall_clock64();
+    }
     bl_v16i c0 = {}, c1 = {}, c2 = {}, c3 = {};
     for (int i = 0; i < iters; ++i) {
         c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
@@ -80,6 +96,10 @@ __global__ __launch_bounds__(256) void bl_probe_mfma_kernel(int iters, int32_t* 
 #pragma unroll
     for (int j = 0; j < 16; ++j) r ^= c0[j] ^ c1[j] ^ c2[j] ^ c3[j];
     if (r == 0x5EEDF00D) sink[lane] = r;
+    if (stamp && threadIdx.x == 0) {
+        stamps[0] = clock64() - c_start;
+        stamps[1] = wall_clock64() - w_start;
+    }
 }
 
 static int probe_grid(int per_cu) {
@@ -102,13 +122,26 @@ extern "C" bl_status bl_probe_stream_read(const void* buf, size_t bytes, int wor
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 
-extern "C" bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s) {
+extern "C" bl_status bl_probe_mfma_i8_ex(int iters, const void* operands, int64_t* stamps, int32_t* sink, double* ops,
+                                         bl_stream s) {
     if (!sink) return BL_ERR_NULL;
     if (iters < 1 || iters > (1 << 24)) return BL_ERR_SHAPE;
-    if (!bl_aligned(sink, 4)) return BL_ERR_ALIGN;
+    if (!bl_aligned(sink, 4) || !bl_aligned(operands, 16) || !bl_aligned(stamps, 8)) return BL_ERR_ALIGN;
     const int blocks = probe_grid(2);
     if (blocks < 1) return BL_ERR_HIP;
-    bl_probe_mfma_kernel<<<blocks, 256, 0, (hipStream_t)s>>>(iters, sink);
+    bl_probe_mfma_kernel<<<blocks, 256, 0, (hipStream_t)s>>>(iters, (const bl_v4i*)operands, (long long*)stamps, sink);
     if (ops) *ops = (double)blocks * 4.0 * iters * 4.0 * 2.0 * 32.0 * 32.0 * 32.0;
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+extern "C" bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s) {
+    return bl_probe_mfma_i8_ex(iters, nullptr, nullptr, sink, ops, s);
+}
+
+extern "C" int bl_probe_wall_clock_khz(void) {
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess)
+        return 0;
+    return khz;
 }
