@@ -574,11 +574,31 @@ def main():
                     t_b /= 5 * nl
                     res[vname] = {"us_per_layer": round(t_b * 1e6, 2), "GBps_packed": round(layer_bytes / t_b / 1e9, 1),
                                   "tops": round(ops2 / t_b / 1e12, 2)}
+            # one streamed launch over all layers (bl_stack_* in its batched form: the token rows of a
+            # product in LDS, the weights streamed once through the matrix cores)
+            if layout == 1:
+                items_b = [dict(packed=layers[l].packed[name], beta=layers[l].beta[name], q=bb[name].q,
+                                scale=bb[name].scale, rowsum=bb[name].rowsum, N=bb[name].N, K=bb[name].K, y=bb[name].y)
+                           for l in range(nl) for name in SHAPE_ORDER]
+                stb = bl.Stack(items_b, layout, Mb, dev)
+                with torch.cuda.stream(side):
+                    stb.run()
+                    torch.cuda.synchronize()
+                    g = capture(torch, stb.run)
+                    g.replay()
+                    t_s, _ = time_graph_steps(torch, [(g, 1, 30)], 30)
+                    t_s /= 30 * nl
+                res["streamed"] = {"us_per_layer": round(t_s * 1e6, 2), "GBps_packed": round(layer_bytes / t_s / 1e9, 1),
+                                   "frac_of_hbm_peak": round(layer_bytes / t_s / 1e9 / HBM_PEAK_GBS, 4),
+                                   "tops": round(ops2 / t_s / 1e12, 2), "launches_per_%d_layers" % nl: 1 if stb.plan.prep_count == 0 else 2,
+                                   "table_entries": int(stb.plan.entries)}
+                del stb, items_b
             cfg2["M=%d" % Mb] = res
             del bb
         out["config2_batched_decode"] = cfg2
         log("[bench] config 2 (calls: 4 bl_gemv_w158a8 launches per layer, int8 inputs; grouped: one "
-            "bl_bitlinear_decode_group launch, int8 inputs; grouped_fused: one launch, bf16 inputs): %s" % cfg2)
+            "bl_bitlinear_decode_group launch, int8 inputs; grouped_fused: one launch, bf16 inputs; streamed: one "
+            "bl_stack_run launch over all layers, int8 inputs): %s" % cfg2)
 
     # ------------------------------------------- config 4: the chained 30-layer stack
     if not args.no_chain:

@@ -315,19 +315,31 @@ bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int6
  *                         over the grid, copies the table to `table` (device, 256-byte
  *                         aligned, caller-owned) and fills *plan (HOST, caller-owned).  It
  *                         waits for that copy on `s` (the only call here that synchronises).
- *                         Limits: M = 1, 1 <= count <= 1024, K <= 20480 per product.
+ *                         Limits: 1 <= count <= 1024; M = 1: K <= 20480 per product (M > 1:
+ *                         the batched form below).
  *   bl_stack_run          at most two kernel launches on `s` (preparation, stream); no
  *                         allocation, no synchronisation; may be captured in a HIP graph and
  *                         replayed.  The table and every tensor it names must stay alive and
- *                         in place; runs on one table must not overlap (they share the scratch). */
-enum { BL_STACK_MAX_COUNT = 1024 };
+ *                         in place; runs on one table must not overlap (they share the scratch).
+ * BATCHED FORM, 2 <= M <= BL_STACK_MAX_TOKENS tokens per product (batched decode: the weights
+ * of the table are still read once per run): bl_stack_build with M > 1 takes int8 entries only
+ * (q [M][Kp], scale [M] when y is wanted, rowsum [M]; outputs [M][N]; BL_ERR_VALUE for X / prod,
+ * BL_ERR_NULL without rowsum), layout BL_LAYOUT_K16 (BL_ERR_LAYOUT otherwise), any N and K whose
+ * padded token row fits LDS; `table` needs bl_stack_table_bytes_batched bytes.  The kernel keeps
+ * the token rows of a product in LDS (at most 32 tokens, one matrix-core tile, and at most
+ * 160 KiB): a product whose M rows do not fit is entered as several table entries of fewer
+ * tokens each, whose weights are then read once per entry.  Same arithmetic, bit for bit, as
+ * bl_gemv_w158a8 on each product. */
+enum { BL_STACK_MAX_COUNT = 1024, BL_STACK_MAX_TOKENS = 64 };
 typedef struct {
     int32_t count, blocks, prep_count, inline_count, norm, lds_bytes, layout, red_ints;
     int64_t wg_offset, prep_offset;   /* byte offsets inside `table`                            */
     int64_t packed_bytes;             /* packed weight bytes of the products: what one run streams */
     int64_t table_bytes;
+    int32_t tokens, entries;          /* M; table entries (> count when products were split)    */
 } bl_stack_plan;
 size_t    bl_stack_table_bytes(const bl_decode_desc* descs, int count);
+size_t    bl_stack_table_bytes_batched(const bl_decode_desc* descs, int count, int64_t M);
 bl_status bl_stack_build(const bl_decode_desc* descs, int count, int layout, int64_t M,
                          void* table, bl_stack_plan* plan, bl_stream s);
 bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_stream s);

@@ -35,6 +35,7 @@ SIGNATURES = {
     "bl_gemm_w158a8_fused": (_ci, [_vp, _vp, _ci, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "bl_quant_from_absmax": (_ci, [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "bl_stack_table_bytes": (_sz, [_vp, _ci]),
+    "bl_stack_table_bytes_batched": (_sz, [_vp, _ci, _i64]),
     "bl_stack_build": (_ci, [_vp, _ci, _ci, _i64, _vp, _vp, _vp]),
     "bl_stack_run": (_ci, [_vp, _vp, _vp]),
     "bl_debug_force_path": (_ci, [_ci]),
@@ -86,7 +87,8 @@ class StackPlan(ctypes.Structure):
                 ("inline_count", ctypes.c_int32), ("norm", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
                 ("layout", ctypes.c_int32), ("red_ints", ctypes.c_int32),
                 ("wg_offset", _i64), ("prep_offset", _i64),
-                ("packed_bytes", _i64), ("table_bytes", _i64)]
+                ("packed_bytes", _i64), ("table_bytes", _i64),
+                ("tokens", ctypes.c_int32), ("entries", ctypes.c_int32)]
 
 
 class BitLinearError(RuntimeError):
@@ -318,7 +320,8 @@ class Stack:
         import torch
         self.items = items                      # keeps every tensor of the table alive
         self.descs = make_decode_descs(items)
-        nbytes = load().bl_stack_table_bytes(self.descs, len(items))
+        nbytes = load().bl_stack_table_bytes(self.descs, len(items)) if M == 1 else \
+            load().bl_stack_table_bytes_batched(self.descs, len(items), M)
         if nbytes == 0:
             raise BitLinearError(2, "bl_stack_table_bytes")
         self.table = torch.empty(nbytes, dtype=torch.uint8, device=device)

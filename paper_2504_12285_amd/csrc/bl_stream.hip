@@ -15,6 +15,9 @@
  */
 #include <string.h>
 
+#include <atomic>
+#include <type_traits>
+
 #include <vector>
 
 #include "bl_device.h"
@@ -46,6 +49,9 @@ struct bl_stream_item {
     float fixed_scale;        /* xbf16 only: > 0 replaces absmax/127 in the rescale */
     int N, nchunks, lgG, lp, layout, units;
     int qgroups;              /* 16-byte groups of the quantised row (its padded length / 16) */
+    int m;                    /* tokens of the entry (batched form; 1 otherwise) */
+    int row_chunks, c0;       /* batched form: 16-byte chunks of a whole packed row; first chunk of the entry's k part */
+    int ldq;                  /* batched form: bytes of a token row of q */
     /* k-major form only: partial sums of all workgroups, and what the finishing kernel reads */
     int32_t* acc_ws;          /* [N] int32, zero between runs */
     const int32_t* rowsum_fin;
@@ -770,6 +776,244 @@ __global__ __launch_bounds__(256) void bl_km_finish(const bl_stream_item* __rest
     }
 }
 
+
+/* ---- batched form: 2..32 tokens per table entry on the matrix cores --------------------------
+ * The same persistent walk for a few tokens per product (batched decode: the packed weights are
+ * still read once, Section 5.1).  Workgroups of eight waves.  The int8 activations of all m
+ * tokens of the product live in LDS for the workgroup (m rows of Kp + 16 bytes: the 16 spread
+ * the rows over the banks), staged once per product and workgroup, so between two products no
+ * wave waits for another: a wave takes row groups of 32 weight rows round-robin and streams
+ * their packed bytes global -> registers in batches of 32 rows x 512 k (4 KiB: four wave-wide
+ * loads in which eight consecutive lanes fetch 128 consecutive bytes of one row, the access
+ * pattern of the one-token kernel), two batches in flight while a third is multiplied.
+ * The matrix core wants another lane order (lane r + 32h supplies sixteen consecutive k of row
+ * r), so a landed batch takes one trip through a 4 KiB tile of LDS that belongs to the wave
+ * alone (ds_write_b128 as loaded, ds_read_b128 as needed; 16-byte items XOR-swizzled against
+ * the row so that both directions are free of bank conflicts; a wave's LDS operations execute
+ * in order, so no barrier is involved).  Each 16-byte item is four packed words; a word is
+ * opened into sixteen int8 codes by shift and mask and is the B operand of one
+ * v_mfma_i32_32x32x32_i8 whose A operand is the same sixteen k of token r read from the image
+ * (any k order serves as long as both operands agree).  Lanes whose chunk lies behind the row's
+ * end re-read its last chunk and meet sixteen zero bytes kept behind the image; tokens behind
+ * m re-read token m-1 and are never stored.  Offset codes: sum_k q of the token is subtracted
+ * once per output. */
+#define BL_MB_THREADS 512
+#define BL_MB_WAVES 8
+#define BL_MB_MISC 320        /* bytes behind the image: 64 zero bytes, 32 row sums, 32 factors */
+#define BL_MB_TILE 4096       /* bytes of a wave's private tile */
+
+template <bool RES>
+__device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, const int ub, const int ue,
+                                                   uint8_t* __restrict__ img, uint8_t* __restrict__ tiles,
+                                                   const bool restage) {
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5, r8 = lane >> 3, c8 = lane & 7;
+    const int N = P.N, nchunks = P.nchunks, m = P.m, rowc = P.row_chunks, c0 = P.c0;
+    const int stride = nchunks * 64 + 16;                               /* image row: the entry's k part + 16 */
+    const int nb = (nchunks + 7) / 8;                                   /* batches of 512 k per row */
+    int32_t BL_G* const ws_g = (int32_t BL_G*)P.acc_ws;                 /* k parts of a split product meet here */
+    const bl_gv4i* const wbase = (const bl_gv4i*)P.packed;
+    int32_t BL_G* const acc_g = (int32_t BL_G*)P.acc;
+    float BL_G* const y_g = (float BL_G*)P.y;
+    const float BL_G* const res_g = (const float BL_G*)P.residual;
+    uint8_t* const zero = img + m * stride;                             /* 64 zero bytes */
+    int* const rs_s = (int*)(zero + 64);
+    float* const cf_s = (float*)(rs_s + 32);
+    bl_v4i* const tile = (bl_v4i*)(tiles + w * BL_MB_TILE);
+
+    /* batch b of row group rg: load i covers rows 8i .. 8i+7, lane (r8, c8) chunk 8b + c8 of row 8i + r8 */
+    auto issue = [&](bl_v4i* p, int rg, int b) {
+        const int chunk = b * 8 + c8;
+        const int cc = chunk < nchunks ? chunk : nchunks - 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int n = rg * 32 + i * 8 + r8;
+            n = n < N ? n : N - 1;
+            p[i] = __builtin_nontemporal_load(wbase + (int64_t)n * rowc + c0 + cc);
+        }
+    };
+    const int arow = (l32 < m ? l32 : m - 1) * stride;
+    const int zoff = m * stride;
+    auto process = [&](const bl_v4i* p, int b, bl_v16i& C) {
+#ifdef BL_MB_NOCOMPUTE
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { C[0] ^= p[i][0]; C[1] ^= p[i][1]; C[2] ^= p[i][2]; C[3] ^= p[i][3]; }
+        return;
+#endif
+        /* registers -> tile: row 8i + r8, item c8 ^ ((row / 2) % 8) */
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[(i * 8 + r8) * 8 + (c8 ^ (((i * 8 + r8) >> 1) & 7))] = p[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bl_v4i w4 = tile[l32 * 8 + ((2 * j + h) ^ ((l32 >> 1) & 7))];
+            const int chunk = b * 8 + 2 * j + h;
+            const bool valid = chunk < nchunks;
+            int ao = valid ? arow + chunk * 64 : zoff;
+            const int step = valid ? 16 : 0;
+            asm volatile("" : "+v"(ao));                                /* read at the point of use, not hoisted */
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bl_v4i a = *(const bl_v4i*)(img + ao + t * step);
+                const uint32_t wd = (uint32_t)w4[t];
+                const uint32_t l0 = wd & 0x03030303u, l1 = (wd >> 2) & 0x03030303u, l2 = (wd >> 4) & 0x03030303u,
+                               l3 = (wd >> 6) & 0x03030303u;
+                const bl_v4i bop = {(int)l0, (int)l1, (int)l2, (int)l3};
+                C = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bop, C, 0, 0, 0);
+            }
+        }
+    };
+    /* lane (n = l32, h) holds, in element v, token (v/4)*8 + 4h + v%4 of output feature n */
+    auto epilogue = [&](bl_v16i& C, int rg) {
+        bl_mfma_fence();
+        /* (the row length and the lane half are hidden from the compiler here: it would otherwise
+         * keep the sixteen 64-bit row offsets of a lane's tokens in registers across the k loop) */
+        int Nl = N, hl = h;
+        asm volatile("" : "+s"(Nl));
+        asm volatile("" : "+v"(hl));
+        const int n = rg * 32 + l32;
+        const bool nok = n < N;
+        float rv[16];
+        if (RES) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = (v >> 2) * 8 + hl * 4 + (v & 3);
+                rv[v] = (nok && t < m) ? res_g[(int64_t)t * Nl + n] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int t = (v >> 2) * 8 + hl * 4 + (v & 3);
+            if (nok && t < m) {
+                if (ws_g) {                                             /* one k part: integer atomics, exact and order-free */
+                    atomicAdd((int*)(ws_g + (int64_t)t * Nl + n), C[v]);
+                    continue;
+                }
+                const int val = C[v] - rs_s[t];
+                if (acc_g) acc_g[(int64_t)t * Nl + n] = val;
+                if (y_g) {
+                    const float o = (float)val * cf_s[t];
+                    y_g[(int64_t)t * Nl + n] = RES ? rv[v] + o : o;
+                }
+            }
+        }
+    };
+
+    bl_v4i pa[4], pb[4], pc[4];
+    const int rg0 = ub + w;
+    const bool work = rg0 < ue;
+    /* issue cursor (two batches ahead of the process cursor); behind the wave's last row group it
+     * stays on that row group: valid addresses, data never used */
+    int irg = rg0, ib = 0;
+    auto advance = [&]() {
+        if (++ib == nb) {
+            ib = 0;
+            if (irg + BL_MB_WAVES < ue) irg += BL_MB_WAVES;
+        }
+    };
+    if (work) {                                                          /* in flight during the staging */
+        issue(pa, irg, ib);
+        advance();
+        issue(pb, irg, ib);
+        advance();
+    }
+    if (restage) __syncthreads();                                       /* every wave is done with the previous image */
+    {
+        /* stage the m token rows (16 bytes per thread and step), the zero bytes and the token terms */
+        const int upr = nchunks * 4, ldu = P.ldq / 16;
+        const bl_gv4i* qg = (const bl_gv4i*)P.q + c0 * 4;
+        for (int u = tid; u < m * upr; u += BL_MB_THREADS) {
+            const int row = u / upr, c = u - row * upr;
+            *(bl_v4i*)(img + row * stride + c * 16) = qg[row * ldu + c];
+        }
+        if (tid < 16) ((int*)zero)[tid] = 0;
+        if (tid < 32) {
+            const int t = tid < m ? tid : m - 1;
+            rs_s[tid] = ((const int32_t BL_G*)P.rowsum)[t];
+            cf_s[tid] = P.y ? *(const float BL_G*)P.beta * ((const float BL_G*)P.scale)[t] : 0.0f;
+        }
+    }
+    __syncthreads();
+    if (!work) return;
+
+    int prg = rg0, pbt = 0;                                             /* process cursor */
+    bl_v16i C;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) C[v] = 0;
+    /* one batch out of `buf`; true when the wave's last row group is finished */
+    auto step = [&](const bl_v4i* buf) {
+        process(buf, pbt, C);
+        if (++pbt < nb) return false;
+        epilogue(C, prg);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) C[v] = 0;
+        pbt = 0;
+        prg += BL_MB_WAVES;
+        return prg >= ue;
+    };
+    while (true) {
+        issue(pc, irg, ib);
+        advance();
+        if (step(pa)) break;
+        issue(pa, irg, ib);
+        advance();
+        if (step(pb)) break;
+        issue(pb, irg, ib);
+        advance();
+        if (step(pc)) break;
+    }
+}
+
+__global__ __launch_bounds__(BL_MB_THREADS)
+void bl_stream_mb(const bl_stream_item* __restrict__ items, const int2* __restrict__ wgstart) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t img[];   /* tiles of the eight waves, then the image */
+    uint8_t* const tiles = img;
+    uint8_t* const image = img + BL_MB_WAVES * BL_MB_TILE;
+    const int2 s0 = wgstart[blockIdx.x], s1 = wgstart[blockIdx.x + 1];
+    const int p_first = __builtin_amdgcn_readfirstlane(s0.x), u_first = __builtin_amdgcn_readfirstlane(s0.y);
+    const int p_last = __builtin_amdgcn_readfirstlane(s1.x), u_last = __builtin_amdgcn_readfirstlane(s1.y);
+    bool staged = false;
+    for (int pi = p_first; pi <= p_last; ++pi) {
+        if (pi == p_last && u_last == 0) break;
+        const bl_stream_item P = items[pi];
+        const int ub = pi == p_first ? u_first : 0;
+        const int ue = pi == p_last ? u_last : P.units;
+        if (ub >= ue) continue;
+        if (P.residual) bl_stream_slice_mb<true>(P, ub, ue, image, tiles, staged);
+        else bl_stream_slice_mb<false>(P, ub, ue, image, tiles, staged);
+        staged = true;
+    }
+}
+
+/* Finishing kernel of the batched form for products that were split along k: subtracts the
+ * row sum, rescales, adds the residual, stores, and clears the partial sums for the next run.
+ * grid (ceil(max M*N / 1024), products). */
+struct bl_mb_fin_item {
+    int32_t* ws;              /* [M][N] partial sums (NULL: the product was not split) */
+    const int32_t* rowsum;
+    const float* scale;
+    const float* beta;
+    const float* residual;
+    int32_t* acc;
+    float* y;
+    int M, N;
+};
+__global__ __launch_bounds__(256) void bl_mb_finish(const bl_mb_fin_item* __restrict__ items) {
+    const bl_mb_fin_item F = items[blockIdx.y];
+    if (!F.ws) return;
+    const int64_t total = (int64_t)F.M * F.N;
+    const float bt = F.y ? *F.beta : 0.0f;
+    for (int64_t e = (int64_t)blockIdx.x * 1024 + threadIdx.x; e < total && e < (int64_t)(blockIdx.x + 1) * 1024; e += 256) {
+        const int t = (int)(e / F.N);
+        const int val = F.ws[e] - F.rowsum[t];
+        F.ws[e] = 0;
+        if (F.acc) F.acc[e] = val;
+        if (F.y) {
+            const float o = (float)val * (bt * F.scale[t]);
+            F.y[e] = F.residual ? F.residual[e] + o : o;
+        }
+    }
+}
+
 /* ---- host side ---------------------------------------------------------------------------- */
 
 #define BL_STREAM_LMAX 5
@@ -797,6 +1041,60 @@ static bl_stream_layout stream_layout(int count, size_t q_bytes, size_t acc_byte
     return L;
 }
 
+/* Cuts a table of products (units[i] row groups of unit_cost[i] each, enter_cost[i] for every
+ * workgroup that enters product i) into `blocks` contiguous slices of about equal cost: walk the
+ * row groups once, cutting whenever a workgroup's cost reaches the target; the last workgroup
+ * takes what is left.  Returns blocks + 1 positions (product, row group). */
+static std::vector<int2> cut_slices(const std::vector<int>& units, const std::vector<int64_t>& unit_cost,
+                                    const std::vector<int64_t>& enter_cost, int blocks) {
+    const int count = (int)units.size();
+    std::vector<int2> wg((size_t)blocks + 1);
+    int64_t all = 0;
+    for (int i = 0; i < count; ++i) all += (int64_t)units[(size_t)i] * unit_cost[(size_t)i] + enter_cost[(size_t)i];
+    /* every cut inside a product adds one more entry, so the target is refined until the
+     * last workgroup (which takes what is left) is no longer than the others */
+    int64_t target = all / blocks + 1;
+    for (int iter = 0; iter < 12; ++iter) {
+        int pi = 0, unit = 0;
+        for (int b = 0; b < blocks; ++b) {
+            wg[(size_t)b] = make_int2(pi, unit);
+            int64_t c = 0;
+            bool entered = false;
+            while (pi < count && b < blocks - 1) {
+                if (!entered) { c += enter_cost[(size_t)pi]; entered = true; }
+                const int64_t uc = unit_cost[(size_t)pi];
+                const int64_t room = target - c;
+                const int64_t take = room > 0 ? (room + uc - 1) / uc : 0;
+                const int left = units[(size_t)pi] - unit;
+                if (take >= left) {
+                    c += (int64_t)left * uc;
+                    ++pi;
+                    unit = 0;
+                    entered = false;
+                    if (c >= target) break;
+                } else {
+                    unit += (int)take;
+                    break;
+                }
+            }
+        }
+        /* cost of what is left for the last workgroup */
+        int64_t last = 0;
+        {
+            int pi = wg[(size_t)blocks - 1].x, unit = wg[(size_t)blocks - 1].y;
+            for (; pi < count; ++pi, unit = 0)
+                if (units[(size_t)pi] > unit)
+                    last += enter_cost[(size_t)pi] + (int64_t)(units[(size_t)pi] - unit) * unit_cost[(size_t)pi];
+        }
+        if (last <= target + target / 64) break;
+        target += (last - target) / blocks + 1;
+    }
+    /* normalise an end position (count, 0) to (count - 1, units): the kernel never reads entry `count` */
+    for (int b = 0; b <= blocks; ++b)
+        if (b == blocks || wg[(size_t)b].x >= count) wg[(size_t)b] = make_int2(count - 1, units[(size_t)count - 1]);
+    return wg;
+}
+
 static bool desc_is_fused(const bl_decode_desc& d) { return d.X || d.prod.in0; }
 
 static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
@@ -816,6 +1114,194 @@ static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
     return BL_OK;
 }
 
+/* ---- batched form (2 .. BL_STACK_MAX_TOKENS tokens per product) ------------------------------ */
+
+#define BL_MB_LDS_MAX (160 * 1024)
+
+/* How one product is entered in the table: token groups of at most 32 (one matrix-core tile),
+ * the M tokens split evenly over the fewest groups, and k parts of whole 512-k batches so that a
+ * group's rows of one part fit LDS beside each other.  A product with more than one k part
+ * collects its partial sums in `ws` and is finished by bl_mb_finish. */
+struct mb_split {
+    int groups, per_group;    /* token groups, tokens per group (the last may hold fewer) */
+    int parts, part_chunks;   /* k parts, 16-byte chunks per part (the last may hold fewer) */
+};
+static bool mb_split_product(int64_t M, int64_t Kp, mb_split* sp) {
+    const int64_t budget = BL_MB_LDS_MAX - BL_MB_MISC - BL_MB_WAVES * BL_MB_TILE;
+    const int64_t nchunks = Kp / 64;
+    sp->groups = (int)((M + 31) / 32);
+    sp->per_group = (int)((M + sp->groups - 1) / sp->groups);
+    int64_t parts = ((int64_t)sp->per_group * (Kp + 16) + budget - 1) / budget;
+    int64_t pc = (nchunks + parts - 1) / parts;
+    pc = (pc + 7) / 8 * 8;
+    while (pc > 8 && (int64_t)sp->per_group * (pc * 64 + 16) > budget) pc -= 8;
+    if ((int64_t)sp->per_group * (pc * 64 + 16) > budget) return false;
+    sp->part_chunks = (int)pc;
+    sp->parts = (int)((nchunks + pc - 1) / pc);
+    return true;
+}
+
+/* Device buffer of the batched form: [entries][slice table][finishing items][partial sums]. */
+struct mb_layout_t {
+    size_t wg_off, fin_off, ws_off, total;
+};
+static mb_layout_t mb_layout(int64_t entries, int count, size_t ws_bytes) {
+    mb_layout_t L;
+    L.wg_off = align_up((size_t)entries * sizeof(bl_stream_item), 256);
+    L.fin_off = L.wg_off + align_up((size_t)(BL_STREAM_MAX_BLOCKS + 1) * sizeof(int2), 256);
+    L.ws_off = L.fin_off + align_up((size_t)count * sizeof(bl_mb_fin_item), 256);
+    L.total = L.ws_off + align_up(ws_bytes, 256);
+    return L;
+}
+
+static bl_status check_batched_desc(const bl_decode_desc& d, int layout) {
+    if (!d.packed || !d.beta || !d.q || !d.rowsum) return BL_ERR_NULL;
+    if (d.X || d.prod.in0) return BL_ERR_VALUE;            /* int8 inputs only: quantise with bl_quant_act_int8 */
+    if (!d.acc && !d.y) return BL_ERR_NULL;
+    if (d.y && !d.scale) return BL_ERR_NULL;
+    if (!bl_shape_ok(d.N, d.K) || d.N > (1 << 24)) return BL_ERR_SHAPE;
+    if (layout != BL_LAYOUT_K16) return BL_ERR_LAYOUT;
+    if (!bl_aligned(d.packed, 16) || !bl_aligned(d.q, 16) || !bl_aligned(d.acc, 4) || !bl_aligned(d.y, 4) ||
+        !bl_aligned(d.scale, 4) || !bl_aligned(d.beta, 4) || !bl_aligned(d.rowsum, 4) || !bl_aligned(d.residual, 4))
+        return BL_ERR_ALIGN;
+    return BL_OK;
+}
+
+static bool mb_sizes(const bl_decode_desc* descs, int count, int64_t M, int64_t* entries, size_t* ws_bytes) {
+    *entries = 0;
+    *ws_bytes = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!bl_shape_ok(descs[i].N, descs[i].K) || descs[i].N > (1 << 24)) return false;
+        mb_split sp;
+        if (!mb_split_product(M, bl_kpad(descs[i].K), &sp)) return false;
+        *entries += (int64_t)sp.groups * sp.parts;
+        if (sp.parts > 1) *ws_bytes += align_up((size_t)(M * descs[i].N * 4), 256);
+    }
+    return *entries <= 64 * BL_STACK_MAX_COUNT;
+}
+
+extern "C" size_t bl_stack_table_bytes_batched(const bl_decode_desc* descs, int count, int64_t M) {
+    if (!descs || count < 1 || count > BL_STACK_MAX_COUNT || M < 2 || M > BL_STACK_MAX_TOKENS) return 0;
+    int64_t entries = 0;
+    size_t ws_bytes = 0;
+    if (!mb_sizes(descs, count, M, &entries, &ws_bytes)) return 0;
+    return mb_layout(entries, count, ws_bytes).total;
+}
+
+static std::atomic<bool> g_mb_attr_set;
+
+static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int layout, int M, void* table,
+                                     bl_stack_plan* plan, hipStream_t st) {
+    for (int i = 0; i < count; ++i) {
+        const bl_status rc = check_batched_desc(descs[i], layout);
+        if (rc != BL_OK) return rc;
+    }
+    int64_t entries64 = 0;
+    size_t ws_bytes = 0;
+    if (!mb_sizes(descs, count, M, &entries64, &ws_bytes)) return BL_ERR_SHAPE;
+    const int entries = (int)entries64;
+    const mb_layout_t L = mb_layout(entries, count, ws_bytes);
+    uint8_t* const dev_base = (uint8_t*)table;
+    std::vector<bl_stream_item> items;
+    std::vector<bl_mb_fin_item> fins((size_t)count);
+    std::vector<int> units_v;
+    std::vector<int64_t> ucost_v, ecost_v;
+    int64_t packed_bytes = 0, total_units = 0, max_elems = 0;
+    int lds = 0, split_products = 0;
+    size_t ws_used = 0;
+    for (int i = 0; i < count; ++i) {
+        const bl_decode_desc& d = descs[i];
+        const int64_t Kp = bl_kpad(d.K);
+        mb_split sp;
+        mb_split_product(M, Kp, &sp);
+        packed_bytes += d.N * (Kp / 4);
+        int32_t* ws = nullptr;
+        if (sp.parts > 1) {
+            ws = (int32_t*)(dev_base + L.ws_off + ws_used);
+            ws_used += align_up((size_t)((int64_t)M * d.N * 4), 256);
+            ++split_products;
+            if ((int64_t)M * d.N > max_elems) max_elems = (int64_t)M * d.N;
+        }
+        fins[(size_t)i] = bl_mb_fin_item{ws, d.rowsum, d.scale, d.beta, d.residual, d.acc, d.y, M, (int)d.N};
+        for (int g = 0; g < sp.groups; ++g) {
+            const int m0 = g * sp.per_group, m = M - m0 < sp.per_group ? M - m0 : sp.per_group;
+            for (int pt = 0; pt < sp.parts; ++pt) {
+                const int c0 = pt * sp.part_chunks;
+                const int nch = (int)(Kp / 64) - c0 < sp.part_chunks ? (int)(Kp / 64) - c0 : sp.part_chunks;
+                bl_stream_item it;
+                memset(&it, 0, sizeof(it));
+                it.packed = (const bl_v4i*)d.packed;
+                it.beta = d.beta;
+                it.q = d.q + (int64_t)m0 * Kp;
+                it.scale = d.scale ? d.scale + m0 : nullptr;
+                it.rowsum = d.rowsum + m0;
+                it.residual = d.residual ? d.residual + (int64_t)m0 * d.N : nullptr;
+                it.acc = d.acc ? d.acc + (int64_t)m0 * d.N : nullptr;
+                it.y = d.y ? d.y + (int64_t)m0 * d.N : nullptr;
+                it.acc_ws = ws ? ws + (int64_t)m0 * d.N : nullptr;
+                it.N = (int)d.N;
+                it.nchunks = nch;
+                it.row_chunks = (int)(Kp / 64);
+                it.c0 = c0;
+                it.ldq = (int)Kp;
+                it.qgroups = (int)(Kp / 16);
+                it.layout = layout;
+                it.m = m;
+                it.units = (int)((d.N + 31) / 32);
+                const int need = (int)(m * (nch * 64 + 16) + BL_MB_MISC + BL_MB_WAVES * BL_MB_TILE);
+                if (need > lds) lds = need;
+                items.push_back(it);
+                units_v.push_back(it.units);
+                ucost_v.push_back((int64_t)32 * nch * 16);
+                ecost_v.push_back((int64_t)2 * m * nch * 64);   /* staging the token rows */
+                total_units += it.units;
+            }
+        }
+    }
+    lds = (lds + 255) / 256 * 256;
+    if (!g_mb_attr_set.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute((const void*)bl_stream_mb, hipFuncAttributeMaxDynamicSharedMemorySize, BL_MB_LDS_MAX) !=
+            hipSuccess)
+            return BL_ERR_HIP;
+        g_mb_attr_set.store(true, std::memory_order_release);
+    }
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)bl_stream_mb, BL_MB_THREADS, (size_t)lds) !=
+            hipSuccess ||
+        cus < 1 || per_cu < 1)
+        return BL_ERR_HIP;
+    int64_t blocks64 = (int64_t)cus * per_cu;
+    if (blocks64 > (total_units + BL_MB_WAVES - 1) / BL_MB_WAVES) blocks64 = (total_units + BL_MB_WAVES - 1) / BL_MB_WAVES;
+    if (blocks64 > BL_STREAM_MAX_BLOCKS) blocks64 = BL_STREAM_MAX_BLOCKS;
+    if (blocks64 < 1) blocks64 = 1;
+    const int blocks = (int)blocks64;
+    const std::vector<int2> wg = cut_slices(units_v, ucost_v, ecost_v, blocks);
+    std::vector<uint8_t> blob(L.ws_off, 0);
+    memcpy(blob.data(), items.data(), items.size() * sizeof(bl_stream_item));
+    memcpy(blob.data() + L.wg_off, wg.data(), wg.size() * sizeof(int2));
+    memcpy(blob.data() + L.fin_off, fins.data(), fins.size() * sizeof(bl_mb_fin_item));
+    /* the partial sums start at zero; every run leaves them at zero again */
+    if (ws_bytes && hipMemsetAsync(dev_base + L.ws_off, 0, ws_bytes, st) != hipSuccess) return BL_ERR_HIP;
+    if (hipMemcpyAsync(table, blob.data(), blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return BL_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return BL_ERR_HIP;   /* the host copy of the table dies here */
+    memset(plan, 0, sizeof(*plan));
+    plan->count = count;
+    plan->blocks = blocks;
+    plan->lds_bytes = lds;
+    plan->layout = layout;
+    plan->wg_offset = (int64_t)L.wg_off;
+    plan->prep_offset = (int64_t)L.fin_off;
+    plan->packed_bytes = packed_bytes;
+    plan->table_bytes = (int64_t)L.total;
+    plan->tokens = M;
+    plan->entries = entries;
+    plan->prep_count = split_products;                  /* > 0: the finishing kernel runs */
+    plan->red_ints = (int32_t)((max_elems + 1023) / 1024);   /* its grid in x */
+    return BL_OK;
+}
+
 extern "C" size_t bl_stack_table_bytes(const bl_decode_desc* descs, int count) {
     if (!descs || count < 1 || count > BL_STACK_MAX_COUNT) return 0;
     size_t q_bytes = 0, acc_bytes = 0;
@@ -830,8 +1316,9 @@ extern "C" size_t bl_stack_table_bytes(const bl_decode_desc* descs, int count) {
 extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int layout, int64_t M, void* table,
                                     bl_stack_plan* plan, bl_stream s) {
     if (!descs || !table || !plan) return BL_ERR_NULL;
-    if (count < 1 || count > BL_STACK_MAX_COUNT || M != 1) return BL_ERR_SHAPE;
+    if (count < 1 || count > BL_STACK_MAX_COUNT || M < 1 || M > BL_STACK_MAX_TOKENS) return BL_ERR_SHAPE;
     if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
+    if (M > 1) return stack_build_batched(descs, count, layout, (int)M, table, plan, (hipStream_t)s);
     size_t q_bytes = 0, acc_bytes = 0;
     for (int i = 0; i < count; ++i) {
         const bl_status st = check_stack_desc(descs[i], layout);
@@ -957,62 +1444,18 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     if (blocks64 < 1) blocks64 = 1;
     const int blocks = (int)blocks64;
 
-    /* Slice boundaries.  A workgroup's time is its bytes, weighted by the measured rate of the
+    /* Slice boundaries: a workgroup's time is its bytes, weighted by the measured rate of the
      * product's register shape, plus a fixed cost each time it enters a product (activation
      * row, pipeline refill; larger when it quantises the row itself), expressed in bytes at a
-     * workgroup's share of the stream rate.  Walk the row groups once, cutting whenever a
-     * workgroup's cost reaches the target; the last workgroup takes what is left. */
-    std::vector<int2> wg((size_t)blocks + 1);
-    {
-        auto enter_cost = [&](int pi) { return items[(size_t)pi].xbf16 ? (int64_t)36 << 10 : (int64_t)12 << 10; };
-        auto unit_cost = [&](int pi) {
-            return items[(size_t)pi].lp == 5 ? unit_bytes[(size_t)pi] : unit_bytes[(size_t)pi] * 26 / 25;
-        };
-        int64_t all = 0;
-        for (int i = 0; i < count; ++i) all += (int64_t)items[(size_t)i].units * unit_cost(i) + enter_cost(i);
-        /* every cut inside a product adds one more entry, so the target is refined until the
-         * last workgroup (which takes what is left) is no longer than the others */
-        int64_t target = all / blocks + 1;
-        for (int iter = 0; iter < 12; ++iter) {
-            int pi = 0, unit = 0;
-            for (int b = 0; b < blocks; ++b) {
-                wg[(size_t)b] = make_int2(pi, unit);
-                int64_t c = 0;
-                bool entered = false;
-                while (pi < count && b < blocks - 1) {
-                    if (!entered) { c += enter_cost(pi); entered = true; }
-                    const int64_t uc = unit_cost(pi);
-                    const int64_t room = target - c;
-                    const int64_t take = room > 0 ? (room + uc - 1) / uc : 0;
-                    const int left = items[(size_t)pi].units - unit;
-                    if (take >= left) {
-                        c += (int64_t)left * uc;
-                        ++pi;
-                        unit = 0;
-                        entered = false;
-                        if (c >= target) break;
-                    } else {
-                        unit += (int)take;
-                        break;
-                    }
-                }
-            }
-            /* cost of what is left for the last workgroup */
-            int64_t last = 0;
-            {
-                int pi = wg[(size_t)blocks - 1].x, unit = wg[(size_t)blocks - 1].y;
-                for (; pi < count; ++pi, unit = 0)
-                    if (items[(size_t)pi].units > unit)
-                        last += enter_cost(pi) + (int64_t)(items[(size_t)pi].units - unit) * unit_cost(pi);
-            }
-            if (last <= target + target / 64) break;
-            target += (last - target) / blocks + 1;
-        }
-        /* normalise an end position (count, 0) to (count - 1, units): the kernel never reads entry `count` */
-        for (int b = 0; b <= blocks; ++b)
-            if (b == blocks || wg[(size_t)b].x >= count)
-                wg[(size_t)b] = make_int2(count - 1, items[(size_t)count - 1].units);
+     * workgroup's share of the stream rate. */
+    std::vector<int> units_v((size_t)count);
+    std::vector<int64_t> ucost_v((size_t)count), ecost_v((size_t)count);
+    for (int i = 0; i < count; ++i) {
+        units_v[(size_t)i] = items[(size_t)i].units;
+        ucost_v[(size_t)i] = items[(size_t)i].lp == 5 ? unit_bytes[(size_t)i] : unit_bytes[(size_t)i] * 26 / 25;
+        ecost_v[(size_t)i] = items[(size_t)i].xbf16 ? (int64_t)36 << 10 : (int64_t)12 << 10;
     }
+    const std::vector<int2> wg = cut_slices(units_v, ucost_v, ecost_v, blocks);
     std::vector<uint8_t> blob(L.rowsum_off, 0);
     memcpy(blob.data(), items.data(), items.size() * sizeof(bl_stream_item));
     memcpy(blob.data() + L.wg_off, wg.data(), wg.size() * sizeof(int2));
@@ -1037,11 +1480,34 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
     plan->prep_offset = (int64_t)L.prep_off;
     plan->packed_bytes = packed_bytes;
     plan->table_bytes = (int64_t)L.total;
+    plan->tokens = 1;
+    plan->entries = count;
     return BL_OK;
 }
 
 extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_stream s) {
     if (!table || !plan) return BL_ERR_NULL;
+    if (plan->tokens > 1) {
+        if (plan->tokens > BL_STACK_MAX_TOKENS || plan->count < 1 || plan->count > BL_STACK_MAX_COUNT ||
+            plan->entries < plan->count || plan->entries > 64 * BL_STACK_MAX_COUNT || plan->blocks < 1 ||
+            plan->blocks > BL_STREAM_MAX_BLOCKS || plan->lds_bytes < BL_MB_MISC + BL_MB_WAVES * BL_MB_TILE || plan->lds_bytes > BL_MB_LDS_MAX ||
+            plan->lds_bytes % 256 || plan->layout != BL_LAYOUT_K16)
+            return BL_ERR_VALUE;
+        const mb_layout_t Lb = mb_layout(plan->entries, plan->count, 0);
+        if (plan->wg_offset != (int64_t)Lb.wg_off || plan->prep_offset != (int64_t)Lb.fin_off || plan->prep_count < 0 ||
+            plan->prep_count > plan->count || plan->red_ints < 0 || (plan->prep_count > 0 && plan->red_ints < 1))
+            return BL_ERR_VALUE;
+        if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
+        if (!g_mb_attr_set.load(std::memory_order_acquire)) return BL_ERR_VALUE;   /* no table was built in this process */
+        const uint8_t* tb = (const uint8_t*)table;
+        bl_stream_mb<<<plan->blocks, BL_MB_THREADS, (size_t)plan->lds_bytes, (hipStream_t)s>>>(
+            (const bl_stream_item*)tb, (const int2*)(tb + Lb.wg_off));
+        if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
+        if (plan->prep_count > 0)
+            bl_mb_finish<<<dim3((unsigned)plan->red_ints, (unsigned)plan->count), 256, 0, (hipStream_t)s>>>(
+                (const bl_mb_fin_item*)(tb + Lb.fin_off));
+        return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+    }
     if (plan->count < 1 || plan->count > BL_STACK_MAX_COUNT || plan->blocks < 1 ||
         plan->blocks > BL_STREAM_MAX_BLOCKS || plan->prep_count < 0 || plan->inline_count < 0 ||
         plan->prep_count + plan->inline_count > plan->count || plan->lds_bytes < 64 ||

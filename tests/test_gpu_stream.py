@@ -197,7 +197,7 @@ def test_stream_rejects_bad_tables(bl):
     c = Case(1, 1, 8, 64)
     it = _item(c, 1, "q")
     with pytest.raises(bl.BitLinearError) as e:
-        bl.Stack([it], 1, 2, DEV)          # M != 1
+        bl.Stack([it], 1, 65, DEV)         # M beyond the batched form (tests/test_gpu_stream_batched.py)
     assert e.value.status == 2
     big = dict(it)
     big["K"] = 20480 + 64
