@@ -324,12 +324,16 @@ bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int6
  * BATCHED FORM, 2 <= M <= BL_STACK_MAX_TOKENS tokens per product (batched decode: the weights
  * of the table are still read once per run): bl_stack_build with M > 1 takes int8 entries only
  * (q [M][Kp], scale [M] when y is wanted, rowsum [M]; outputs [M][N]; BL_ERR_VALUE for X / prod,
- * BL_ERR_NULL without rowsum), layout BL_LAYOUT_K16 (BL_ERR_LAYOUT otherwise), any N and K whose
- * padded token row fits LDS; `table` needs bl_stack_table_bytes_batched bytes.  The kernel keeps
- * the token rows of a product in LDS (at most 32 tokens, one matrix-core tile, and at most
- * 160 KiB): a product whose M rows do not fit is entered as several table entries of fewer
- * tokens each, whose weights are then read once per entry.  Same arithmetic, bit for bit, as
- * bl_gemv_w158a8 on each product. */
+ * BL_ERR_NULL without rowsum), layout BL_LAYOUT_K16 (BL_ERR_LAYOUT otherwise), any N and K;
+ * `table` needs bl_stack_table_bytes_batched bytes (0: bad count, M, N or K).  The kernel keeps
+ * the token rows of a table entry in LDS and multiplies on the matrix cores, 32 tokens to a tile.
+ * How a product becomes table entries is the library's business and never changes a result:
+ * up to 64 tokens in one entry where their rows fit LDS whole, else groups of at most 32 tokens
+ * (the weights are then read once per group); rows too long for LDS are cut into k parts whose
+ * partial sums meet in scratch inside `table` through integer atomics (exact, order-free) and
+ * are finished (row sum, rescale, residual) by a second small launch of the same run, which
+ * also clears the scratch.  plan->entries tells how many entries the table holds.
+ * Same arithmetic, bit for bit, as bl_gemv_w158a8 on each product. */
 enum { BL_STACK_MAX_COUNT = 1024, BL_STACK_MAX_TOKENS = 64 };
 typedef struct {
     int32_t count, blocks, prep_count, inline_count, norm, lds_bytes, layout, red_ints;

@@ -777,7 +777,7 @@ __global__ __launch_bounds__(256) void bl_km_finish(const bl_stream_item* __rest
 }
 
 
-/* ---- batched form: 2..32 tokens per table entry on the matrix cores --------------------------
+/* ---- batched form: 2..64 tokens per table entry on the matrix cores --------------------------
  * The same persistent walk for a few tokens per product (batched decode: the packed weights are
  * still read once, Section 5.1).  Workgroups of eight waves.  The int8 activations of all m
  * tokens of the product live in LDS for the workgroup (m rows of Kp + 16 bytes: the 16 spread
@@ -792,17 +792,18 @@ __global__ __launch_bounds__(256) void bl_km_finish(const bl_stream_item* __rest
  * the row so that both directions are free of bank conflicts; a wave's LDS operations execute
  * in order, so no barrier is involved).  Each 16-byte item is four packed words; a word is
  * opened into sixteen int8 codes by shift and mask and is the B operand of one
- * v_mfma_i32_32x32x32_i8 whose A operand is the same sixteen k of token r read from the image
+ * v_mfma_i32_32x32x32_i8 (two for more than 32 tokens) whose A operand is the same sixteen k of
+ * token r (and 32 + r) read from the image
  * (any k order serves as long as both operands agree).  Lanes whose chunk lies behind the row's
  * end re-read its last chunk and meet sixteen zero bytes kept behind the image; tokens behind
  * m re-read token m-1 and are never stored.  Offset codes: sum_k q of the token is subtracted
  * once per output. */
 #define BL_MB_THREADS 512
 #define BL_MB_WAVES 8
-#define BL_MB_MISC 320        /* bytes behind the image: 64 zero bytes, 32 row sums, 32 factors */
+#define BL_MB_MISC 576        /* bytes behind the image: 64 zero bytes, 64 row sums, 64 factors */
 #define BL_MB_TILE 4096       /* bytes of a wave's private tile */
 
-template <bool RES>
+template <int TB, bool RES>
 __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, const int ub, const int ue,
                                                    uint8_t* __restrict__ img, uint8_t* __restrict__ tiles,
                                                    const bool restage) {
@@ -818,7 +819,7 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
     const float BL_G* const res_g = (const float BL_G*)P.residual;
     uint8_t* const zero = img + m * stride;                             /* 64 zero bytes */
     int* const rs_s = (int*)(zero + 64);
-    float* const cf_s = (float*)(rs_s + 32);
+    float* const cf_s = (float*)(rs_s + 64);
     bl_v4i* const tile = (bl_v4i*)(tiles + w * BL_MB_TILE);
 
     /* batch b of row group rg: load i covers rows 8i .. 8i+7, lane (r8, c8) chunk 8b + c8 of row 8i + r8 */
@@ -832,14 +833,11 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
             p[i] = __builtin_nontemporal_load(wbase + (int64_t)n * rowc + c0 + cc);
         }
     };
-    const int arow = (l32 < m ? l32 : m - 1) * stride;
-    const int zoff = m * stride;
-    auto process = [&](const bl_v4i* p, int b, bl_v16i& C) {
-#ifdef BL_MB_NOCOMPUTE
+    int arow[TB];                                                        /* token l32 of tile tt (clamped) */
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { C[0] ^= p[i][0]; C[1] ^= p[i][1]; C[2] ^= p[i][2]; C[3] ^= p[i][3]; }
-        return;
-#endif
+    for (int tt = 0; tt < TB; ++tt) arow[tt] = (tt * 32 + l32 < m ? tt * 32 + l32 : m - 1) * stride;
+    const int zoff = m * stride;
+    auto process = [&](const bl_v4i* p, int b, bl_v16i* C) {
         /* registers -> tile: row 8i + r8, item c8 ^ ((row / 2) % 8) */
 #pragma unroll
         for (int i = 0; i < 4; ++i) tile[(i * 8 + r8) * 8 + (c8 ^ (((i * 8 + r8) >> 1) & 7))] = p[i];
@@ -848,22 +846,29 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
             const bl_v4i w4 = tile[l32 * 8 + ((2 * j + h) ^ ((l32 >> 1) & 7))];
             const int chunk = b * 8 + 2 * j + h;
             const bool valid = chunk < nchunks;
-            int ao = valid ? arow + chunk * 64 : zoff;
+            int ao[TB];
+#pragma unroll
+            for (int tt = 0; tt < TB; ++tt) {
+                ao[tt] = valid ? arow[tt] + chunk * 64 : zoff;
+                asm volatile("" : "+v"(ao[tt]));                        /* read at the point of use, not hoisted */
+            }
             const int step = valid ? 16 : 0;
-            asm volatile("" : "+v"(ao));                                /* read at the point of use, not hoisted */
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const bl_v4i a = *(const bl_v4i*)(img + ao + t * step);
                 const uint32_t wd = (uint32_t)w4[t];
                 const uint32_t l0 = wd & 0x03030303u, l1 = (wd >> 2) & 0x03030303u, l2 = (wd >> 4) & 0x03030303u,
                                l3 = (wd >> 6) & 0x03030303u;
                 const bl_v4i bop = {(int)l0, (int)l1, (int)l2, (int)l3};
-                C = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bop, C, 0, 0, 0);
+#pragma unroll
+                for (int tt = 0; tt < TB; ++tt) {
+                    const bl_v4i a = *(const bl_v4i*)(img + ao[tt] + t * step);
+                    C[tt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bop, C[tt], 0, 0, 0);
+                }
             }
         }
     };
-    /* lane (n = l32, h) holds, in element v, token (v/4)*8 + 4h + v%4 of output feature n */
-    auto epilogue = [&](bl_v16i& C, int rg) {
+    /* lane (n = l32, h) holds, in element v of tile tt, token 32tt + (v/4)*8 + 4h + v%4 of output feature n */
+    auto epilogue = [&](bl_v16i& C, int rg, int tt) {
         bl_mfma_fence();
         /* (the row length and the lane half are hidden from the compiler here: it would otherwise
          * keep the sixteen 64-bit row offsets of a lane's tokens in registers across the k loop) */
@@ -876,13 +881,13 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
         if (RES) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int t = (v >> 2) * 8 + hl * 4 + (v & 3);
+                const int t = tt * 32 + (v >> 2) * 8 + hl * 4 + (v & 3);
                 rv[v] = (nok && t < m) ? res_g[(int64_t)t * Nl + n] : 0.0f;
             }
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int t = (v >> 2) * 8 + hl * 4 + (v & 3);
+            const int t = tt * 32 + (v >> 2) * 8 + hl * 4 + (v & 3);
             if (nok && t < m) {
                 if (ws_g) {                                             /* one k part: integer atomics, exact and order-free */
                     atomicAdd((int*)(ws_g + (int64_t)t * Nl + n), C[v]);
@@ -926,7 +931,7 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
             *(bl_v4i*)(img + row * stride + c * 16) = qg[row * ldu + c];
         }
         if (tid < 16) ((int*)zero)[tid] = 0;
-        if (tid < 32) {
+        if (tid < 64) {
             const int t = tid < m ? tid : m - 1;
             rs_s[tid] = ((const int32_t BL_G*)P.rowsum)[t];
             cf_s[tid] = P.y ? *(const float BL_G*)P.beta * ((const float BL_G*)P.scale)[t] : 0.0f;
@@ -936,16 +941,21 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
     if (!work) return;
 
     int prg = rg0, pbt = 0;                                             /* process cursor */
-    bl_v16i C;
+    bl_v16i C[TB];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) C[v] = 0;
+    for (int tt = 0; tt < TB; ++tt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) C[tt][v] = 0;
     /* one batch out of `buf`; true when the wave's last row group is finished */
     auto step = [&](const bl_v4i* buf) {
         process(buf, pbt, C);
         if (++pbt < nb) return false;
-        epilogue(C, prg);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) C[v] = 0;
+        for (int tt = 0; tt < TB; ++tt) {
+            epilogue(C[tt], prg, tt);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) C[tt][v] = 0;
+        }
         pbt = 0;
         prg += BL_MB_WAVES;
         return prg >= ue;
@@ -963,6 +973,9 @@ __device__ __forceinline__ void bl_stream_slice_mb(const bl_stream_item& P, cons
     }
 }
 
+/* TB = token tiles of 32 an entry may hold: 1 for tables of at most 32 tokens (fewer registers:
+ * two workgroups per compute unit when the images are small), 2 beyond. */
+template <int TB>
 __global__ __launch_bounds__(BL_MB_THREADS)
 void bl_stream_mb(const bl_stream_item* __restrict__ items, const int2* __restrict__ wgstart) {
     extern __shared__ __attribute__((aligned(16))) uint8_t img[];   /* tiles of the eight waves, then the image */
@@ -978,8 +991,13 @@ void bl_stream_mb(const bl_stream_item* __restrict__ items, const int2* __restri
         const int ub = pi == p_first ? u_first : 0;
         const int ue = pi == p_last ? u_last : P.units;
         if (ub >= ue) continue;
-        if (P.residual) bl_stream_slice_mb<true>(P, ub, ue, image, tiles, staged);
-        else bl_stream_slice_mb<false>(P, ub, ue, image, tiles, staged);
+        if (TB == 2 && P.m > 32) {
+            if (P.residual) bl_stream_slice_mb<TB, true>(P, ub, ue, image, tiles, staged);
+            else bl_stream_slice_mb<TB, false>(P, ub, ue, image, tiles, staged);
+        } else {
+            if (P.residual) bl_stream_slice_mb<1, true>(P, ub, ue, image, tiles, staged);
+            else bl_stream_slice_mb<1, false>(P, ub, ue, image, tiles, staged);
+        }
         staged = true;
     }
 }
@@ -1118,7 +1136,7 @@ static bl_status check_stack_desc(const bl_decode_desc& d, int layout) {
 
 #define BL_MB_LDS_MAX (160 * 1024)
 
-/* How one product is entered in the table: token groups of at most 32 (one matrix-core tile),
+/* How one product is entered in the table: token groups of at most 64 (two matrix-core tiles),
  * the M tokens split evenly over the fewest groups, and k parts of whole 512-k batches so that a
  * group's rows of one part fit LDS beside each other.  A product with more than one k part
  * collects its partial sums in `ws` and is finished by bl_mb_finish. */
@@ -1129,8 +1147,15 @@ struct mb_split {
 static bool mb_split_product(int64_t M, int64_t Kp, mb_split* sp) {
     const int64_t budget = BL_MB_LDS_MAX - BL_MB_MISC - BL_MB_WAVES * BL_MB_TILE;
     const int64_t nchunks = Kp / 64;
-    sp->groups = (int)((M + 31) / 32);
+    /* two matrix-core tiles of tokens per entry where their rows fit LDS whole (the weights are
+     * then read once and nothing meets through atomics: measured at M = 64, 2560 <= K: two groups
+     * of 32 tokens 267 us per 30 layers, one group of 64 in k parts 375 us); else one tile */
+    sp->groups = (int)((M + 63) / 64);
     sp->per_group = (int)((M + sp->groups - 1) / sp->groups);
+    if (sp->per_group > 32 && (int64_t)sp->per_group * (Kp + 16) > budget) {
+        sp->groups = (int)((M + 31) / 32);
+        sp->per_group = (int)((M + sp->groups - 1) / sp->groups);
+    }
     int64_t parts = ((int64_t)sp->per_group * (Kp + 16) + budget - 1) / budget;
     int64_t pc = (nchunks + parts - 1) / parts;
     pc = (pc + 7) / 8 * 8;
@@ -1259,16 +1284,25 @@ static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int
         }
     }
     lds = (lds + 255) / 256 * 256;
+    bool two_tiles = false;
+    for (int i = 0; i < count; ++i) {
+        mb_split sp;
+        mb_split_product(M, bl_kpad(descs[i].K), &sp);
+        two_tiles = two_tiles || sp.per_group > 32;
+    }
+    const void* kern = two_tiles ? (const void*)bl_stream_mb<2> : (const void*)bl_stream_mb<1>;
     if (!g_mb_attr_set.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute((const void*)bl_stream_mb, hipFuncAttributeMaxDynamicSharedMemorySize, BL_MB_LDS_MAX) !=
-            hipSuccess)
+        if (hipFuncSetAttribute((const void*)bl_stream_mb<1>, hipFuncAttributeMaxDynamicSharedMemorySize, BL_MB_LDS_MAX) !=
+                hipSuccess ||
+            hipFuncSetAttribute((const void*)bl_stream_mb<2>, hipFuncAttributeMaxDynamicSharedMemorySize, BL_MB_LDS_MAX) !=
+                hipSuccess)
             return BL_ERR_HIP;
         g_mb_attr_set.store(true, std::memory_order_release);
     }
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)bl_stream_mb, BL_MB_THREADS, (size_t)lds) !=
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, BL_MB_THREADS, (size_t)lds) !=
             hipSuccess ||
         cus < 1 || per_cu < 1)
         return BL_ERR_HIP;
@@ -1299,6 +1333,7 @@ static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int
     plan->entries = entries;
     plan->prep_count = split_products;                  /* > 0: the finishing kernel runs */
     plan->red_ints = (int32_t)((max_elems + 1023) / 1024);   /* its grid in x */
+    plan->norm = two_tiles ? 2 : 1;                       /* token tiles of the kernel variant */
     return BL_OK;
 }
 
@@ -1495,13 +1530,18 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
             return BL_ERR_VALUE;
         const mb_layout_t Lb = mb_layout(plan->entries, plan->count, 0);
         if (plan->wg_offset != (int64_t)Lb.wg_off || plan->prep_offset != (int64_t)Lb.fin_off || plan->prep_count < 0 ||
-            plan->prep_count > plan->count || plan->red_ints < 0 || (plan->prep_count > 0 && plan->red_ints < 1))
+            plan->prep_count > plan->count || plan->red_ints < 0 || (plan->prep_count > 0 && plan->red_ints < 1) ||
+            plan->norm < 1 || plan->norm > 2)
             return BL_ERR_VALUE;
         if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
         if (!g_mb_attr_set.load(std::memory_order_acquire)) return BL_ERR_VALUE;   /* no table was built in this process */
         const uint8_t* tb = (const uint8_t*)table;
-        bl_stream_mb<<<plan->blocks, BL_MB_THREADS, (size_t)plan->lds_bytes, (hipStream_t)s>>>(
-            (const bl_stream_item*)tb, (const int2*)(tb + Lb.wg_off));
+        if (plan->norm == 2)
+            bl_stream_mb<2><<<plan->blocks, BL_MB_THREADS, (size_t)plan->lds_bytes, (hipStream_t)s>>>(
+                (const bl_stream_item*)tb, (const int2*)(tb + Lb.wg_off));
+        else
+            bl_stream_mb<1><<<plan->blocks, BL_MB_THREADS, (size_t)plan->lds_bytes, (hipStream_t)s>>>(
+                (const bl_stream_item*)tb, (const int2*)(tb + Lb.wg_off));
         if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
         if (plan->prep_count > 0)
             bl_mb_finish<<<dim3((unsigned)plan->red_ints, (unsigned)plan->count), 256, 0, (hipStream_t)s>>>(
