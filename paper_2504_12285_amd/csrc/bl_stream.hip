@@ -1004,9 +1004,9 @@ void bl_stream_mb(const bl_stream_item* __restrict__ items, const int2* __restri
 
 /* Finishing kernel of the batched form for products that were split along k: subtracts the
  * row sum, rescales, adds the residual, stores, and clears the partial sums for the next run.
- * grid (ceil(max M*N / 1024), products). */
+ * grid (ceil(max M*N / 1024), split products). */
 struct bl_mb_fin_item {
-    int32_t* ws;              /* [M][N] partial sums (NULL: the product was not split) */
+    int32_t* ws;              /* [M][N] partial sums */
     const int32_t* rowsum;
     const float* scale;
     const float* beta;
@@ -1017,17 +1017,34 @@ struct bl_mb_fin_item {
 };
 __global__ __launch_bounds__(256) void bl_mb_finish(const bl_mb_fin_item* __restrict__ items) {
     const bl_mb_fin_item F = items[blockIdx.y];
-    if (!F.ws) return;
     const int64_t total = (int64_t)F.M * F.N;
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    if (base >= total) return;
     const float bt = F.y ? *F.beta : 0.0f;
-    for (int64_t e = (int64_t)blockIdx.x * 1024 + threadIdx.x; e < total && e < (int64_t)(blockIdx.x + 1) * 1024; e += 256) {
-        const int t = (int)(e / F.N);
-        const int val = F.ws[e] - F.rowsum[t];
-        F.ws[e] = 0;
-        if (F.acc) F.acc[e] = val;
-        if (F.y) {
-            const float o = (float)val * (bt * F.scale[t]);
-            F.y[e] = F.residual ? F.residual[e] + o : o;
+    /* four elements per thread, every load of a step issued before the first use */
+    int part[4], rs[4];
+    float cf[4], res[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t e = base + j * 256;
+        const bool ok = e < total;
+        const int t = ok ? (int)(e / F.N) : 0;
+        part[j] = ok ? F.ws[e] : 0;
+        rs[j] = F.rowsum[t];
+        cf[j] = F.y ? F.scale[t] : 0.0f;
+        res[j] = (ok && F.residual) ? F.residual[e] : 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t e = base + j * 256;
+        if (e < total) {
+            const int val = part[j] - rs[j];
+            F.ws[e] = 0;
+            if (F.acc) F.acc[e] = val;
+            if (F.y) {
+                const float o = (float)val * (bt * cf[j]);
+                F.y[e] = F.residual ? res[j] + o : o;
+            }
         }
     }
 }
@@ -1228,7 +1245,7 @@ static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int
     const mb_layout_t L = mb_layout(entries, count, ws_bytes);
     uint8_t* const dev_base = (uint8_t*)table;
     std::vector<bl_stream_item> items;
-    std::vector<bl_mb_fin_item> fins((size_t)count);
+    std::vector<bl_mb_fin_item> fins;                    /* one per product that is split along k */
     std::vector<int> units_v;
     std::vector<int64_t> ucost_v, ecost_v;
     int64_t packed_bytes = 0, total_units = 0, max_elems = 0;
@@ -1247,7 +1264,7 @@ static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int
             ++split_products;
             if ((int64_t)M * d.N > max_elems) max_elems = (int64_t)M * d.N;
         }
-        fins[(size_t)i] = bl_mb_fin_item{ws, d.rowsum, d.scale, d.beta, d.residual, d.acc, d.y, M, (int)d.N};
+        if (ws) fins.push_back(bl_mb_fin_item{ws, d.rowsum, d.scale, d.beta, d.residual, d.acc, d.y, M, (int)d.N});
         for (int g = 0; g < sp.groups; ++g) {
             const int m0 = g * sp.per_group, m = M - m0 < sp.per_group ? M - m0 : sp.per_group;
             for (int pt = 0; pt < sp.parts; ++pt) {
@@ -1315,7 +1332,7 @@ static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int
     std::vector<uint8_t> blob(L.ws_off, 0);
     memcpy(blob.data(), items.data(), items.size() * sizeof(bl_stream_item));
     memcpy(blob.data() + L.wg_off, wg.data(), wg.size() * sizeof(int2));
-    memcpy(blob.data() + L.fin_off, fins.data(), fins.size() * sizeof(bl_mb_fin_item));
+    if (!fins.empty()) memcpy(blob.data() + L.fin_off, fins.data(), fins.size() * sizeof(bl_mb_fin_item));
     /* the partial sums start at zero; every run leaves them at zero again */
     if (ws_bytes && hipMemsetAsync(dev_base + L.ws_off, 0, ws_bytes, st) != hipSuccess) return BL_ERR_HIP;
     if (hipMemcpyAsync(table, blob.data(), blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return BL_ERR_HIP;
@@ -1544,7 +1561,7 @@ extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_str
                 (const bl_stream_item*)tb, (const int2*)(tb + Lb.wg_off));
         if (hipGetLastError() != hipSuccess) return BL_ERR_HIP;
         if (plan->prep_count > 0)
-            bl_mb_finish<<<dim3((unsigned)plan->red_ints, (unsigned)plan->count), 256, 0, (hipStream_t)s>>>(
+            bl_mb_finish<<<dim3((unsigned)plan->red_ints, (unsigned)plan->prep_count), 256, 0, (hipStream_t)s>>>(
                 (const bl_mb_fin_item*)(tb + Lb.fin_off));
         return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
     }
