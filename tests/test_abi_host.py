@@ -146,3 +146,42 @@ def test_debug_hook_and_gemv_workspace_status(lib):
     buf = (ctypes.c_char * 4096)()
     p = (ctypes.addressof(buf) + 255) & ~255
     assert lib.bl_gemv_w158a8(p, p, 1, p, p, None, 1, 64, 8256, p, p, None, None) == 7
+
+
+def test_stack_tables_are_sized_and_checked_on_the_host(lib):
+    """bl_stack_* (one-token and batched form): table sizes, descriptor errors and malformed plans are
+    host work; nothing here reaches a GPU call."""
+    buf = (ctypes.c_char * 8192)()
+    p = (ctypes.addressof(buf) + 255) & ~255
+    d = (bl.DecodeDesc * 2)()
+    for e in d:
+        e.packed = e.beta = e.q = e.scale = e.rowsum = e.y = p
+        e.N, e.K = 2560, 2560
+    d[1].K = 6912
+    one = lib.bl_stack_table_bytes(d, 2)
+    assert one > 0 and one % 256 == 0
+    assert lib.bl_stack_table_bytes(d, 0) == 0 and lib.bl_stack_table_bytes(d, 1025) == 0
+    # batched form: more table entries than products once rows are split, scratch for the k parts
+    sizes = {M: lib.bl_stack_table_bytes_batched(d, 2, M) for M in (2, 8, 32, 64)}
+    assert all(v > 0 and v % 256 == 0 for v in sizes.values())
+    assert sizes[32] >= sizes[8] + 32 * 2560 * 4          # the long-k product collects partial sums at M = 32
+    assert lib.bl_stack_table_bytes_batched(d, 2, 1) == 0 and lib.bl_stack_table_bytes_batched(d, 2, 65) == 0
+    assert lib.bl_stack_table_bytes_batched(d, 0, 8) == 0 and lib.bl_stack_table_bytes_batched(None, 2, 8) == 0
+    plan = bl.StackPlan()
+    assert lib.bl_stack_build(d, 2, 1, 65, p, ctypes.byref(plan), None) == 2
+    assert lib.bl_stack_build(d, 2, 0, 8, p, ctypes.byref(plan), None) == 3        # batched: layout 1 only
+    assert lib.bl_stack_build(d, 2, 1, 8, p + 8, ctypes.byref(plan), None) == 4
+    d[0].rowsum = None
+    assert lib.bl_stack_build(d, 2, 1, 8, p, ctypes.byref(plan), None) == 1        # batched: row sums required
+    d[0].rowsum = p
+    d[0].X = p
+    assert lib.bl_stack_build(d, 2, 1, 8, p, ctypes.byref(plan), None) == 5        # batched: int8 inputs only
+    d[0].X = None
+    d[1].y = None
+    assert lib.bl_stack_build(d, 2, 1, 8, p, ctypes.byref(plan), None) == 1        # no output at all
+    # a plan that no build call produced
+    bad = bl.StackPlan()
+    assert lib.bl_stack_run(p, ctypes.byref(bad), None) == 5
+    bad.tokens, bad.count, bad.entries, bad.blocks, bad.lds_bytes, bad.layout = 8, 2, 2, 16, 100, 1
+    assert lib.bl_stack_run(p, ctypes.byref(bad), None) == 5
+    assert lib.bl_stack_run(None, ctypes.byref(bad), None) == 1
