@@ -125,6 +125,56 @@ def test_stream_many_products_cross_slice_boundaries(bl):
             _check(it, c)
 
 
+@pytest.mark.timeout(900)
+def test_stream_whole_tables_as_benchmarked(bl):
+    """The benchmark's streamed launches at their full size: the 120 BitLinears of 30 layers of
+    the 2B shapes (521 MB of packed weights, packed on the GPU from the seeded latent weights) in
+    ONE bl_stack_run each: M = 1 with bf16 inputs quantised inside the launch (config 1, the
+    headline), M = 8 and M = 64 with int8 inputs (config 2).  Every int32 accumulator and every
+    fp32 output of every product against the oracle."""
+    names = list(synth.LAYER_SHAPES)
+    Ms = (1, 8, 64)
+    X = {(n, M): synth.activations_bf16(0, M, synth.LAYER_SHAPES[n][1], layer=0, matrix=n, relu2=(n == "down"))
+         for n in names for M in Ms}
+    quant = {k: oracle.quant_act(x) for k, x in X.items()}
+    Xd = {n: to_dev(X[(n, 1)]) for n in names}
+    qd = {k: tuple(to_dev(a) for a in v) for k, v in quant.items() if k[1] > 1}
+    items = {M: [] for M in Ms}
+    want = {M: [] for M in Ms}
+    for l in range(synth.N_LAYERS):
+        for n in names:
+            N, K = synth.LAYER_SHAPES[n]
+            W = synth.latent_weights(0, N, K, layer=l, matrix=n)
+            beta, mean64 = oracle.absmean_beta(W, return_mean64=True)
+            assert oracle.beta_guard_ok(mean64)
+            Wt = oracle.ternarize(W, beta)
+            packed, b = bl.bl_pack_ternary(to_dev(W), 1)
+            assert b.item() == float(beta)
+            del W
+            for M in Ms:
+                q, scale, _ = quant[(n, M)]
+                acc = oracle.matmul_i32(q, Wt)
+                want[M].append((acc, oracle.rescale(acc, beta, scale)))
+                it = dict(packed=packed, beta=b, N=N, K=K,
+                          y=torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV),
+                          acc=torch.full((M, N), -99, dtype=torch.int32, device=DEV))
+                if M == 1:
+                    it["X"] = Xd[n]
+                else:
+                    it.update(q=qd[(n, M)][0], scale=qd[(n, M)][1], rowsum=qd[(n, M)][2])
+                items[M].append(it)
+            del Wt
+    for M in Ms:
+        st = bl.Stack(items[M], 1, M, DEV)
+        assert st.plan.count == 120 and (M > 1 or st.plan.prep_count == 0)
+        assert st.plan.packed_bytes == 30 * sum(N * K // 4 for N, K in synth.LAYER_SHAPES.values())
+        st.run()
+        torch.cuda.synchronize()
+        for it, (acc, y) in zip(items[M], want[M]):
+            assert np.array_equal(it["acc"].cpu().numpy(), acc)
+            assert_y_close(it["y"].cpu().numpy(), y)
+
+
 def test_stream_replay_with_changed_inputs(bl):
     """The same table run again after its bf16 inputs changed in place: the quantisation inside
     the launch must be redone and waited for (a stale ready flag would give the old result)."""
