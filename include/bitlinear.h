@@ -333,6 +333,11 @@ bl_status bl_quant_from_absmax(const uint16_t* X, float* absmax, int64_t M, int6
  * partial sums meet in scratch inside `table` through integer atomics (exact, order-free) and
  * are finished (row sum, rescale, residual) by a second small launch of the same run, which
  * also clears the scratch.  plan->entries tells how many entries the table holds.
+ * With more than 48 tokens, and every row length a multiple of 128 after padding, the table is
+ * walked by the prefill tile kernel instead (Section 5.1: packed tiles expanded to int8 on chip
+ * for the int8 matrix cores): 64 x 128 output tiles, both operands streamed through LDS, the
+ * tiles of all products balanced over the resident workgroups by their k steps, one launch,
+ * weights read once; plan->red_ints then holds the tile count.
  * Same arithmetic, bit for bit, as bl_gemv_w158a8 on each product. */
 enum { BL_STACK_MAX_COUNT = 1024, BL_STACK_MAX_TOKENS = 64 };
 typedef struct {

@@ -232,7 +232,11 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * rows are 2 x 32 gate rows and the 2 x 32 matching up rows (n and N/2 + n), t = (relu(g)*relu(g))*u
  * for N/2 output columns, written as bf16 with its row maximum (Section 2: ReLU^2 in the FFN,
  * per-token absmax quantisation of the next BitLinear's input). */
-template <int BM, int BN, int STAGES, int WM, int WN, int EPI>
+/* TABLE: the persistent grid walks the tiles of a whole TABLE of products (device array `items`,
+ * tile0[i] = first virtual tile of product i; at most BM token rows, so a tile is one block of
+ * BN weight rows of one product) instead of the tiles of the one product in the arguments: the
+ * batched decode of a stack of BitLinears in one launch whose weights are read once. */
+template <int BM, int BN, int STAGES, int WM, int WN, int EPI, bool TABLE = false>
 __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
                                                                 const int32_t* __restrict__ rowsum,
@@ -242,7 +246,12 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                                                                 int vgrid, const float* __restrict__ residual,
                                                                 int32_t* __restrict__ acc, float* __restrict__ y,
                                                                 uint16_t* __restrict__ xb, int* __restrict__ absmax,
-                                                                long long* __restrict__ stamps) {
+                                                                long long* __restrict__ stamps,
+                                                                const bl_tile_item* __restrict__ items,
+                                                                const int* __restrict__ tile0, int nitems,
+                                                                const int* __restrict__ wg_start,
+                                                                const int* __restrict__ tile_list) {
+    static_assert(!TABLE || EPI == 0, "the table walk has the plain epilogue only");
     static_assert(EPI != 2 || (BN == 128 && WN == 2 && BN / WN / 32 == 2), "the gate epilogue pairs ni = 0 with ni = 1");
     constexpr int NW = WM * WN, THREADS = NW * 64;
     constexpr int G3_BM = BM, G3_A_BYTES = BM * G3_BK;
@@ -260,10 +269,42 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
-    const int kb = K / 4;
-    const int steps = K / G3_BK;
-    const bool want_cf = EPI != 0 || y != nullptr;      /* the fused epilogues always rescale */
-    const float bt = want_cf ? *beta : 0.0f;
+    /* fixed for the launch, or (TABLE) those of the product whose tile is set up next */
+    int kb = K / 4;
+    int steps = K / G3_BK;
+    bool want_cf = EPI != 0 || y != nullptr;            /* the fused epilogues always rescale */
+    float bt = (!TABLE && want_cf) ? *beta : 0.0f;
+    /* what the epilogue of the tile in flight stores to (TABLE: set when that tile was set up) */
+    int eN = N;
+    const float* eres = residual;
+    int32_t* eacc = acc;
+    float* ey = y;
+    int nN = N, nsteps = steps;
+    const float* nres = residual;
+    int32_t* nacc = acc;
+    float* ny = y;
+    auto load_item = [&](int vb, int& tn) {
+        int lo = 0, hi = nitems - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (tile0[mid] <= vb) lo = mid; else hi = mid - 1;
+        }
+        const bl_tile_item it = items[lo];
+        tn = vb - tile0[lo];
+        packed = it.packed;
+        q = it.q;
+        rowsum = it.rowsum;
+        scale = it.scale;
+        N = nN = it.N;
+        K = it.K;
+        kb = K / 4;
+        nsteps = K / G3_BK;
+        nres = it.residual;
+        nacc = it.acc;
+        ny = it.y;
+        want_cf = it.y != nullptr;
+        bt = want_cf ? *it.beta : 0.0f;
+    };
 
     /* XCD-aware tile order: workgroup L runs on XCD L%8.  The tile grid is cut
      * into gm x gn = 8 rectangular regions, one per XCD, narrow enough in M that
@@ -279,8 +320,16 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         tn = (xcd % gn) * rn + idx / rm;
         return tm < tiles_m && tn < tiles_n;
     };
+    int vend = vgrid;
+    if constexpr (TABLE) vend = wg_start[blockIdx.x + 1];
     /* the next virtual block of this workgroup that maps to a real tile, or -1 */
     auto next_tile = [&](int vb, int& tm, int& tn) {
+        if constexpr (TABLE) {                      /* vb: position in this workgroup's tile list */
+            if (vb >= vend) return -1;
+            tm = 0;
+            load_item(tile_list[vb], tn);
+            return vb;
+        }
         for (; vb < vgrid; vb += (int)gridDim.x)
             if (tile_of(vb, tm, tn)) return vb;
         return -1;
@@ -337,7 +386,7 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
     const int w_off = G3_A_BYTES + ((wn0 + l32) * 2 + (h ^ ((l32 >> 3) & 1))) * 16;
 
     int tm, tn;
-    int vb = next_tile((int)blockIdx.x, tm, tn);
+    int vb = next_tile(TABLE ? wg_start[blockIdx.x] : (int)blockIdx.x, tm, tn);
     if (vb < 0) return;
     /* measurement hook: workgroup 0 counts shader clocks and wall-clock ticks over its lifetime
      * (a wave-uniform test, so the counts stay in scalar registers) */
@@ -348,6 +397,9 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         w_start = wall_clock64();
     }
     setup(tm, tn);
+    if constexpr (TABLE) {
+        steps = nsteps; eN = nN; eres = nres; eacc = nacc; ey = ny;
+    }
     /* STAGES - 1 k steps are in flight ahead of the matrix cores: a k step of one workgroup
      * takes far less time than a load, so the depth, not the tile, hides the latency */
     for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
@@ -412,10 +464,10 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         int tm2 = 0, tn2 = 0;
-        const int vb2 = next_tile(vb + (int)gridDim.x, tm2, tn2);
+        const int vb2 = next_tile(vb + (TABLE ? 1 : (int)gridDim.x), tm2, tn2);
         if (vb2 >= 0) {
             setup(tm2, tn2);
-            for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
+            for (int s0 = 0; s0 < STAGES - 1 && s0 < (TABLE ? nsteps : steps); ++s0) issue(s0, s0);
         }
         if constexpr (EPI == 0) {
 #pragma unroll
@@ -425,14 +477,14 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                 /* the residual values of four rows first, then their stores back to back: a load
                  * between two stores would make each store wait for the one before it */
                 float rres[4][NI];
-                if (residual && y) {
+                if (eres && ey) {
 #pragma unroll
                     for (int v4 = 0; v4 < 4; ++v4) {
                         const int m = m0 + wm0 + mi * 32 + vq * 8 + h * 4 + v4;
 #pragma unroll
                         for (int ni = 0; ni < NI; ++ni) {
                             const int n = n0 + wn0 + ni * 32 + l32;
-                            rres[v4][ni] = (m < M && n < N) ? residual[(int64_t)m * N + n] : 0.0f;
+                            rres[v4][ni] = (m < M && n < eN) ? eres[(int64_t)m * eN + n] : 0.0f;
                         }
                     }
                 }
@@ -447,13 +499,13 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
 #pragma unroll
                         for (int ni = 0; ni < NI; ++ni) {
                             const int n = n0 + wn0 + ni * 32 + l32;
-                            if (n < N) {
+                            if (n < eN) {
                                 const int val = C[mi][ni][v] - rs;
-                                if (acc) acc[(int64_t)m * N + n] = val;
-                                if (y) {
+                                if (eacc) eacc[(int64_t)m * eN + n] = val;
+                                if (ey) {
                                     const float t = (float)val * c;
-                                    const float out = residual ? rres[v4][ni] + t : t;
-                                    __builtin_nontemporal_store(out, y + (int64_t)m * N + n);
+                                    const float out = eres ? rres[v4][ni] + t : t;
+                                    __builtin_nontemporal_store(out, ey + (int64_t)m * eN + n);
                                 }
                             }
                         }
@@ -551,6 +603,9 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         vb = vb2;
         tm = tm2;
         tn = tn2;
+        if constexpr (TABLE) {
+            steps = nsteps; eN = nN; eres = nres; eacc = nacc; ey = ny;
+        }
         /* the next tile's epilogue rewrites rs_s / cf_s only after its own k loop, whose barriers
          * every wave passes after it has finished the reads above */
     }
@@ -600,7 +655,42 @@ static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, cons
     }
     if (blocks > vgrid) blocks = vgrid;
     kern<<<blocks, WM * WN * 64, lds, st>>>(packed, q, rowsum, beta, scale, M, N, K, tiles_m, tiles_n, gm, vgrid,
-                                            residual, acc, y, ep.xb, ep.absmax, (long long*)bl_clock_stamps());
+                                            residual, acc, y, ep.xb, ep.absmax, (long long*)bl_clock_stamps(), nullptr, nullptr, 0, nullptr, nullptr);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+/* Table walk (batched decode of a stack, more than 48 tokens): 64 x 128 tiles, one launch over
+ * every tile of every product.  items / tile0: device arrays of `nitems` entries (tile0 ascending,
+ * tile0[0] = 0); total_tiles = tiles of the whole table; M <= 64 tokens, the same for every
+ * product.  Workgroup b takes the tiles tile_list[wg_start[b] .. wg_start[b+1]) (device arrays
+ * of blocks + 1 and total_tiles entries: the host balances the k steps over the workgroups).
+ * bl_gemm_table_blocks: the persistent grid (resident workgroups), 0 on error. */
+static constexpr int TABLE_LDS = 2 * (64 * G3_BK + 128 * G3_BK / 4) + 64 * 8;
+static std::atomic<int> g_table_blocks{0};
+
+int bl_gemm_table_blocks(void) {
+    int blocks = g_table_blocks.load(std::memory_order_acquire);
+    if (blocks > 0) return blocks;
+    auto kern = bl_gemm_tile256<64, 128, 2, 1, 4, 0, true>;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TABLE_LDS) != hipSuccess ||
+        hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, 256, TABLE_LDS) != hipSuccess ||
+        cus < 1 || per_cu < 1)
+        return 0;
+    blocks = cus * per_cu;
+    g_table_blocks.store(blocks, std::memory_order_release);
+    return blocks;
+}
+
+bl_status bl_gemm_table_launch(const bl_tile_item* items, const int* tile0, int nitems, int total_tiles, int M,
+                               int blocks, const int* wg_start, const int* tile_list, bl_stream s) {
+    hipStream_t st = (hipStream_t)s;
+    if (g_table_blocks.load(std::memory_order_acquire) == 0) return BL_ERR_VALUE;   /* no table was built in this process */
+    bl_gemm_tile256<64, 128, 2, 1, 4, 0, true><<<blocks, 256, TABLE_LDS, st>>>(
+        nullptr, nullptr, nullptr, nullptr, nullptr, M, 0, G3_BK, 1, 0, 1, total_tiles, nullptr, nullptr, nullptr, nullptr,
+        nullptr, nullptr, items, tile0, nitems, wg_start, tile_list);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 

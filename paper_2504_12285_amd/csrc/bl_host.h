@@ -26,3 +26,21 @@ int bl_forced_decode_path(void);
 /* Measurement hook (bl_debug_clock_stamps): device buffer for the clock counts of the prefill
  * tile kernel, or NULL (the default).  Process-wide, atomic. */
 int64_t* bl_clock_stamps(void);
+
+/* One product of a table walked by the TABLE form of bl_gemm_tile256 (device memory). */
+struct bl_tile_item {
+    const uint8_t* packed;
+    const int8_t* q;
+    const int32_t* rowsum;
+    const float* beta;
+    const float* scale;       /* NULL: y is not wanted */
+    const float* residual;
+    int32_t* acc;
+    float* y;
+    int N, K;                 /* K: the padded row length, a multiple of 128 */
+};
+
+/* Launch of that table walk (bl_gemm.hip) for the batched streamed decode (bl_stream.hip). */
+int bl_gemm_table_blocks(void);
+bl_status bl_gemm_table_launch(const bl_tile_item* items, const int* tile0, int nitems, int total_tiles, int M,
+                               int blocks, const int* wg_start, const int* tile_list, bl_stream s);

@@ -18,6 +18,8 @@
 #include <atomic>
 #include <type_traits>
 
+#include <algorithm>
+#include <queue>
 #include <vector>
 
 #include "bl_device.h"
@@ -1222,12 +1224,124 @@ static bool mb_sizes(const bl_decode_desc* descs, int count, int64_t M, int64_t*
     return *entries <= 64 * BL_STACK_MAX_COUNT;
 }
 
+static bool mb_tile_route(const bl_decode_desc* descs, int count, int64_t M);
+static size_t tile_route_total(const bl_decode_desc* descs, int count);
+
 extern "C" size_t bl_stack_table_bytes_batched(const bl_decode_desc* descs, int count, int64_t M) {
     if (!descs || count < 1 || count > BL_STACK_MAX_COUNT || M < 2 || M > BL_STACK_MAX_TOKENS) return 0;
     int64_t entries = 0;
     size_t ws_bytes = 0;
     if (!mb_sizes(descs, count, M, &entries, &ws_bytes)) return 0;
-    return mb_layout(entries, count, ws_bytes).total;
+    size_t total = mb_layout(entries, count, ws_bytes).total;
+    if (mb_tile_route(descs, count, M)) {
+        const size_t tt = tile_route_total(descs, count);
+        if (tt > total) total = tt;
+    }
+    return total;
+}
+
+/* More than 48 tokens per product: the token rows of most products no longer fit LDS whole, the
+ * work is a dense contraction, and the table is walked by the prefill tile kernel instead
+ * (64 x 128 tiles, both operands streamed through LDS per k step, weights read once; measured on
+ * the 30-layer table at M = 64: 6.3 us per layer against 9.3 with two token groups of 32; at
+ * M = 48 the two are equal, below the LDS-resident form wins).  Needs rows padded to 128. */
+#define BL_MB_TILE_ROUTE_MIN 49
+static bool mb_tile_route(const bl_decode_desc* descs, int count, int64_t M) {
+    if (M < BL_MB_TILE_ROUTE_MIN) return false;
+    int64_t tiles = 0;
+    for (int i = 0; i < count; ++i) {
+        if (bl_kpad(descs[i].K) % 128 != 0) return false;
+        tiles += (descs[i].N + 127) / 128;
+    }
+    return tiles < ((int64_t)1 << 30);
+}
+
+/* Device buffer of the tile route: [products][first tile of each product][first list position of
+ * each workgroup][tile list]. */
+struct tile_layout_t {
+    size_t t0_off, wg_off, list_off, total;
+};
+static tile_layout_t tile_layout(int count, int64_t tiles) {
+    tile_layout_t L;
+    L.t0_off = align_up((size_t)count * sizeof(bl_tile_item), 256);
+    L.wg_off = L.t0_off + align_up((size_t)count * sizeof(int), 256);
+    L.list_off = L.wg_off + align_up((size_t)(BL_STREAM_MAX_BLOCKS + 1) * sizeof(int), 256);
+    L.total = L.list_off + align_up((size_t)tiles * sizeof(int), 256);
+    return L;
+}
+static int64_t tile_route_tiles(const bl_decode_desc* descs, int count) {
+    int64_t tiles = 0;
+    for (int i = 0; i < count; ++i) tiles += (descs[i].N + 127) / 128;
+    return tiles;
+}
+
+static size_t tile_route_total(const bl_decode_desc* descs, int count) {
+    return tile_layout(count, tile_route_tiles(descs, count)).total;
+}
+
+static bl_status stack_build_tiles(const bl_decode_desc* descs, int count, int layout, int M, void* table,
+                                   bl_stack_plan* plan, hipStream_t st) {
+    const int resident = bl_gemm_table_blocks();
+    if (resident < 1) return BL_ERR_HIP;
+    const int64_t tiles = tile_route_tiles(descs, count);
+    const tile_layout_t L = tile_layout(count, tiles);
+    int blocks = (int)(tiles < resident ? tiles : resident);
+    if (blocks > BL_STREAM_MAX_BLOCKS) blocks = BL_STREAM_MAX_BLOCKS;
+    std::vector<uint8_t> blob(L.total, 0);
+    bl_tile_item* items = (bl_tile_item*)blob.data();
+    int* tile0 = (int*)(blob.data() + L.t0_off);
+    int* wg_start = (int*)(blob.data() + L.wg_off);
+    int* tile_list = (int*)(blob.data() + L.list_off);
+    int64_t packed_bytes = 0, t = 0;
+    /* (cost, first tile, tiles) of each product; cost of a tile = its k steps + a fixed part for
+     * set-up and stores */
+    std::vector<std::pair<int, int>> by_cost;             /* (-cost, product) */
+    for (int i = 0; i < count; ++i) {
+        const bl_decode_desc& d = descs[i];
+        const int64_t Kp = bl_kpad(d.K);
+        items[i] = bl_tile_item{d.packed, d.q, d.rowsum, d.beta, d.y ? d.scale : nullptr, d.residual, d.acc, d.y,
+                                (int)d.N, (int)Kp};
+        tile0[i] = (int)t;
+        t += (d.N + 127) / 128;
+        packed_bytes += d.N * (Kp / 4);
+        by_cost.push_back({-(int)(Kp / 128 + 4), i});
+    }
+    /* longest tiles first, each to the workgroup with the least work so far */
+    std::sort(by_cost.begin(), by_cost.end());
+    std::vector<std::vector<int>> lists((size_t)blocks);
+    std::priority_queue<std::pair<int64_t, int>, std::vector<std::pair<int64_t, int>>, std::greater<std::pair<int64_t, int>>> load;
+    for (int b = 0; b < blocks; ++b) load.push({0, b});
+    for (const auto& pc : by_cost) {
+        const int i = pc.second, n_tiles = (int)((descs[i].N + 127) / 128);
+        for (int j = 0; j < n_tiles; ++j) {
+            auto top = load.top();
+            load.pop();
+            lists[(size_t)top.second].push_back(tile0[i] + j);
+            top.first += -pc.first;
+            load.push(top);
+        }
+    }
+    int pos = 0;
+    for (int b = 0; b < blocks; ++b) {
+        wg_start[b] = pos;
+        for (int v : lists[(size_t)b]) tile_list[pos++] = v;
+    }
+    wg_start[blocks] = pos;
+    if (hipMemcpyAsync(table, blob.data(), blob.size(), hipMemcpyHostToDevice, st) != hipSuccess) return BL_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return BL_ERR_HIP;   /* the host copy of the table dies here */
+    memset(plan, 0, sizeof(*plan));
+    plan->count = count;
+    plan->blocks = blocks;
+    plan->layout = layout;
+    plan->wg_offset = (int64_t)L.wg_off;
+    plan->prep_offset = (int64_t)L.list_off;
+    plan->packed_bytes = packed_bytes;
+    plan->table_bytes = (int64_t)bl_stack_table_bytes_batched(descs, count, M);
+    plan->tokens = M;
+    plan->entries = count;
+    plan->red_ints = (int32_t)tiles;                      /* tiles of the whole table */
+    plan->norm = 3;                                       /* the tile route */
+    return BL_OK;
 }
 
 static std::atomic<bool> g_mb_attr_set;
@@ -1241,6 +1355,7 @@ static bl_status stack_build_batched(const bl_decode_desc* descs, int count, int
     int64_t entries64 = 0;
     size_t ws_bytes = 0;
     if (!mb_sizes(descs, count, M, &entries64, &ws_bytes)) return BL_ERR_SHAPE;
+    if (mb_tile_route(descs, count, M)) return stack_build_tiles(descs, count, layout, M, table, plan, st);
     const int entries = (int)entries64;
     const mb_layout_t L = mb_layout(entries, count, ws_bytes);
     uint8_t* const dev_base = (uint8_t*)table;
@@ -1539,6 +1654,20 @@ extern "C" bl_status bl_stack_build(const bl_decode_desc* descs, int count, int 
 
 extern "C" bl_status bl_stack_run(void* table, const bl_stack_plan* plan, bl_stream s) {
     if (!table || !plan) return BL_ERR_NULL;
+    if (plan->tokens > 1 && plan->norm == 3) {               /* the tile route of the batched form */
+        if (plan->tokens < BL_MB_TILE_ROUTE_MIN || plan->tokens > BL_STACK_MAX_TOKENS || plan->count < 1 ||
+            plan->count > BL_STACK_MAX_COUNT || plan->entries != plan->count || plan->red_ints < plan->count ||
+            plan->blocks < 1 || plan->blocks > plan->red_ints || plan->blocks > BL_STREAM_MAX_BLOCKS ||
+            plan->layout != BL_LAYOUT_K16 || plan->prep_count != 0)
+            return BL_ERR_VALUE;
+        const tile_layout_t Lt = tile_layout(plan->count, plan->red_ints);
+        if (plan->wg_offset != (int64_t)Lt.wg_off || plan->prep_offset != (int64_t)Lt.list_off) return BL_ERR_VALUE;
+        if (!bl_aligned(table, 256)) return BL_ERR_ALIGN;
+        const uint8_t* tb = (const uint8_t*)table;
+        return bl_gemm_table_launch((const bl_tile_item*)tb, (const int*)(tb + Lt.t0_off), plan->count, plan->red_ints,
+                                    plan->tokens, plan->blocks, (const int*)(tb + Lt.wg_off),
+                                    (const int*)(tb + Lt.list_off), s);
+    }
     if (plan->tokens > 1) {
         if (plan->tokens > BL_STACK_MAX_TOKENS || plan->count < 1 || plan->count > BL_STACK_MAX_COUNT ||
             plan->entries < plan->count || plan->entries > 64 * BL_STACK_MAX_COUNT || plan->blocks < 1 ||

@@ -185,3 +185,12 @@ def test_stack_tables_are_sized_and_checked_on_the_host(lib):
     bad.tokens, bad.count, bad.entries, bad.blocks, bad.lds_bytes, bad.layout = 8, 2, 2, 16, 100, 1
     assert lib.bl_stack_run(p, ctypes.byref(bad), None) == 5
     assert lib.bl_stack_run(None, ctypes.byref(bad), None) == 1
+    # the tile route of the batched form (more than 48 tokens): more workgroups than tiles, offsets that
+    # no build call laid out, fewer tokens than the route takes
+    tile = bl.StackPlan()
+    tile.tokens, tile.count, tile.entries, tile.norm, tile.layout, tile.red_ints, tile.blocks = 64, 2, 2, 3, 1, 40, 41
+    assert lib.bl_stack_run(p, ctypes.byref(tile), None) == 5
+    tile.blocks = 40
+    assert lib.bl_stack_run(p, ctypes.byref(tile), None) == 5
+    tile.tokens = 8
+    assert lib.bl_stack_run(p, ctypes.byref(tile), None) == 5

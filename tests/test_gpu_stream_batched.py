@@ -95,6 +95,65 @@ def test_batched_stream_token_counts(bl, M):
         _check(it, c, res)
 
 
+@pytest.mark.parametrize("M", [49, 56, 64])
+def test_batched_stream_tile_route(bl, M):
+    """More than 48 tokens with every row padded to a multiple of 128: the table is walked by the
+    matrix-core tile kernel (plan.norm == 3).  Ragged N (a part-filled last tile, a single
+    part-filled tile), K = 128 (one k step) to K = 6912, residuals, y alone, acc alone; two runs."""
+    shapes = [(100, 2560), (259, 6912), (2563, 1000), (129, 128), (33, 4608), (1280, 1152)]
+    cases, items, ress = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        c = Case(40 + M, M, N, K, layer=i, matrix=i % 4)
+        res = None
+        if i % 2 == 1:
+            res = synth.latent_weights(6, M, N, layer=i, matrix=9).astype(np.float32) * 50.0
+        cases.append(c)
+        ress.append(res)
+        items.append(_item(c, want_acc=(i != 2), want_y=(i != 3), residual=res))
+    st = bl.Stack(items, 1, M, DEV)
+    assert st.plan.norm == 3 and st.plan.tokens == M and st.plan.prep_count == 0
+    assert st.plan.red_ints == sum((N + 127) // 128 for N, _ in shapes)
+    for _ in range(2):
+        for it in items:
+            if "y" in it:
+                it["y"].fill_(float("nan"))
+            if "acc" in it:
+                it["acc"].fill_(-99)
+        st.run()
+        torch.cuda.synchronize()
+        for it, c, res in zip(items, cases, ress):
+            _check(it, c, res)
+
+
+def test_batched_stream_tile_route_extreme_values_and_fallback(bl):
+    """|acc| = 127 * K on every output through the tile route; and a table that holds one row
+    length that is not a multiple of 128 stays on the LDS-resident kernel with the same results."""
+    M, N, K = 64, 200, 6912
+    c = Case(0, M, N, K, full=False)
+    c.Wt = np.ones((N, K), dtype=np.int8)
+    c.Wt[1::2] = -1
+    c.q = np.full((M, K), 127, dtype=np.int8)
+    c.q[1::2] = -127
+    c.rowsum = c.q.astype(np.int32).sum(1).astype(np.int32)
+    c.acc = oracle.matmul_i32(c.q, c.Wt)
+    c.y = oracle.rescale(c.acc, c.beta, c.scale)
+    assert abs(int(c.acc[0, 0])) == 127 * K
+    it = _item(c)
+    st = bl.Stack([it], 1, M, DEV)
+    assert st.plan.norm == 3
+    st.run()
+    torch.cuda.synchronize()
+    _check(it, c)
+    c2 = Case(1, M, 96, 192)                      # 192 = 64 * 3: not a multiple of 128
+    it1, it2 = _item(c), _item(c2)
+    st = bl.Stack([it1, it2], 1, M, DEV)
+    assert st.plan.norm != 3
+    st.run()
+    torch.cuda.synchronize()
+    _check(it1, c)
+    _check(it2, c2)
+
+
 def test_batched_stream_extreme_values(bl):
     """|acc| = 127 * K on every output: all weights +1 or -1 against saturated activations."""
     M, N, K = 16, 96, 6912
