@@ -236,8 +236,16 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * tile0[i] = first virtual tile of product i; at most BM token rows, so a tile is one block of
  * BN weight rows of one product) instead of the tiles of the one product in the arguments: the
  * batched decode of a stack of BitLinears in one launch whose weights are read once. */
-template <int BM, int BN, int STAGES, int WM, int WN, int EPI, bool TABLE = false>
-__global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
+/* DEFER: the fp32 outputs of a tile are not stored in a burst behind its k loop (every workgroup of
+ * a launch reaches that point together, the chip then writes at the HBM rate while its matrix cores
+ * idle: measured 19 - 23 thousand clocks of stores per 128 x 128 tile against 28 - 31 thousand of k
+ * loop) but kept in registers and stored a few rows per k step during the NEXT tile of the
+ * workgroup, behind that step's operand loads.  Vector memory operations retire in order, so the
+ * wait in front of the following step leaves exactly those stores in flight.  Interior tiles
+ * with a following tile only; edge tiles and a workgroup's last tile store at once.  fp32 output
+ * alone (no int32 output, no residual). */
+template <int BM, int BN, int STAGES, int WM, int WN, int EPI, bool TABLE = false, bool DEFER = false>
+__global__ __launch_bounds__(WM * WN * 64, (DEFER && BM * BN >= 128 * 128 ? 2 : BM * BN >= 128 * 128 ? 3 : 4)) void bl_gemm_tile256(const uint8_t* __restrict__ packed,
                                                                 const int8_t* __restrict__ q,
                                                                 const int32_t* __restrict__ rowsum,
                                                                 const float* __restrict__ beta,
@@ -252,6 +260,7 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
                                                                 const int* __restrict__ wg_start,
                                                                 const int* __restrict__ tile_list) {
     static_assert(!TABLE || EPI == 0, "the table walk has the plain epilogue only");
+    static_assert(!DEFER || (EPI == 0 && !TABLE && STAGES == 2), "deferred stores: plain epilogue, two stages");
     static_assert(EPI != 2 || (BN == 128 && WN == 2 && BN / WN / 32 == 2), "the gate epilogue pairs ni = 0 with ni = 1");
     constexpr int NW = WM * WN, THREADS = NW * 64;
     constexpr int G3_BM = BM, G3_A_BYTES = BM * G3_BK;
@@ -264,8 +273,10 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
     static_assert(THREADS >= BM, "one thread per tile row fetches the row terms");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     /* behind the stages: the per-row terms of the tile in flight (row sum, beta*scale) */
-    int* const rs_s = (int*)(smem + STAGES * G3_STAGE_BYTES);
-    float* const cf_s = (float*)(rs_s + G3_BM);
+    /* (DEFER: two sets, the second for the tile whose stores are still pending) */
+    int* const rs_base = (int*)(smem + STAGES * G3_STAGE_BYTES);
+    int* rs_s = rs_base;
+    float* cf_s = (float*)(rs_base + G3_BM);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
@@ -404,8 +415,60 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
      * takes far less time than a load, so the depth, not the tile, hides the latency */
     for (int s0 = 0; s0 < STAGES - 1 && s0 < steps; ++s0) issue(s0, s0);
 
+    /* DEFER: the accumulators of the workgroup's previous tile, where that tile lies and which set
+     * of per-row terms is its; cset = the set of the tile in flight */
+    bl_v16i P[MI][NI];
+    bool have_prev = false;
+    int pm0 = 0, pn0 = 0, pset = 0, cset = 0;
+    constexpr int GROUPS = MI * 4;        /* store groups of a tile: rows 8 vq + 4 h + (0..3) of row block mi */
+    constexpr int SPG = 4 * NI;           /* store instructions of a group */
+    /* group g of the accumulators A of the tile at (sm0, sn0) -> y; masked: the tile may cross M or N */
+    auto emit_rows = [&](const bl_v16i (&A)[MI][NI], const int g, const int sm0, const int sn0, const int set,
+                         const bool masked) __attribute__((always_inline)) {
+        const int mi = g / 4, vq = g % 4;
+        const int* rs_p = rs_base + set * 2 * G3_BM;
+        const float* cf_p = (const float*)(rs_p + G3_BM);
+        /* (the row is hidden from the compiler here: it would otherwise keep the 64-bit addresses of
+         * all 16 * MI * NI stores of a lane in registers across the k loop) */
+        int mlb = wm0 + mi * 32 + vq * 8 + h * 4;
+        asm volatile("" : "+v"(mlb));
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int ml = mlb + v4;
+            const int m = sm0 + ml;
+            const int rs = rs_p[ml];
+            const float c = cf_p[ml];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int n = sn0 + wn0 + ni * 32 + l32;
+                if (!masked || (m < M && n < eN))
+                    __builtin_nontemporal_store((float)(A[mi][ni][vq * 4 + v4] - rs) * c, ey + (int64_t)m * eN + n);
+            }
+        }
+    };
+
+    /* group g of the previous tile, whose finished fp32 values wait in P: one address add and one
+     * store per value (32-bit byte offsets from the uniform base: the host sends outputs of 4 GiB
+     * or more to the kernel without deferred stores) */
+    auto emit_prev = [&](const int g) __attribute__((always_inline)) {
+        const int mi = g / 4, vq = g % 4;
+        int mlb = wm0 + mi * 32 + vq * 8 + h * 4;
+        asm volatile("" : "+v"(mlb));
+        const uint32_t bo = ((uint32_t)(pm0 + mlb) * (uint32_t)eN + (uint32_t)(pn0 + wn0 + l32)) * 4u;
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                __builtin_nontemporal_store(__int_as_float(P[mi][ni][vq * 4 + v4]),
+                                            (float*)((char*)ey + (size_t)(bo + ((uint32_t)v4 * (uint32_t)eN + ni * 32u) * 4u)));
+    };
+
     while (true) {
         const int m0 = tm * G3_BM, n0 = tn * BN;
+        if constexpr (DEFER) {
+            rs_s = rs_base + cset * 2 * G3_BM;
+            cf_s = (float*)(rs_s + G3_BM);
+        }
         bl_v16i C[MI][NI];
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
@@ -417,11 +480,25 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
         for (int kk = 0; kk < steps; ++kk) {
             /* stage kk must have landed; the stages issued after it may stay in flight */
             const int later = steps - 1 - kk;
-            bl_wait_stages<STAGES - 2, LOADS>(later < STAGES - 2 ? later : STAGES - 2);
+            if constexpr (DEFER) {
+                /* the SPG stores of the step before were issued behind this stage's loads: they may
+                 * stay in flight (vector memory operations retire in order) */
+                if (have_prev && kk >= 1 && kk <= GROUPS) BL_WAIT_VM(SPG);
+                else BL_WAIT_VM(0);
+            } else {
+                bl_wait_stages<STAGES - 2, LOADS>(later < STAGES - 2 ? later : STAGES - 2);
+            }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             if (kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
+            if constexpr (DEFER) {
+                if (have_prev && kk < GROUPS) {
+#pragma unroll
+                    for (int g = 0; g < GROUPS; ++g)
+                        if (kk == g) emit_prev(g);
+                }
+            }
             const uint8_t* st = smem + (kk % STAGES) * G3_STAGE_BYTES;
             /* operands of sub-step ks+1 are fetched while ks multiplies */
             bl_v4i wq[NI], a[2][MI];
@@ -452,6 +529,14 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
          * store loop would serialise on latency.  Every wave is past its last stage read after
          * the barrier, so the first stages of this workgroup's NEXT tile are requested here and
          * travel while this tile is stored. */
+        if constexpr (DEFER) {
+            if (have_prev) {
+#pragma unroll
+                for (int g = 0; g < GROUPS; ++g)
+                    if (g >= steps) emit_prev(g);
+                have_prev = false;
+            }
+        }
         bl_mfma_fence();
         if (tid < G3_BM) {
             rs_s[tid] = row_rs;
@@ -469,7 +554,28 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN >= 128 * 128 ? 3 : 4)) void 
             setup(tm2, tn2);
             for (int s0 = 0; s0 < STAGES - 1 && s0 < (TABLE ? nsteps : steps); ++s0) issue(s0, s0);
         }
-        if constexpr (EPI == 0) {
+        if constexpr (DEFER) {
+            if (vb2 >= 0 && m0 + G3_BM <= M && n0 + BN <= eN) {
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int ml = wm0 + mi * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+                        const int rs = rs_s[ml];
+                        const float c = cf_s[ml];
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) P[mi][ni][v] = __float_as_int((float)(C[mi][ni][v] - rs) * c);
+                    }
+                pm0 = m0;
+                pn0 = n0;
+                pset = cset;
+                have_prev = true;
+            } else {
+#pragma unroll
+                for (int g = 0; g < GROUPS; ++g) emit_rows(C, g, m0, n0, cset, true);
+            }
+            cset ^= 1;
+        } else if constexpr (EPI == 0) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -617,13 +723,13 @@ struct bl_epi_args {
     int* absmax;
 };
 
-template <int BM, int BN, int STAGES, int WM, int WN, int EPI = 0>
+template <int BM, int BN, int STAGES, int WM, int WN, int EPI = 0, bool DEFER = false>
 static bl_status launch_tile256_t(const uint8_t* packed, const float* beta, const int8_t* q, const float* scale,
                                   const int32_t* rowsum, int M, int N, int K, const float* residual,
                                   int32_t* acc, float* y, hipStream_t st, bl_epi_args ep = bl_epi_args{nullptr, nullptr}) {
     constexpr int G3_BM = BM;
-    constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4) + BM * 8;
-    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN, EPI>;
+    constexpr int lds = STAGES * (BM * G3_BK + BN * G3_BK / 4) + BM * 8 * (DEFER ? 2 : 1);
+    auto kern = bl_gemm_tile256<BM, BN, STAGES, WM, WN, EPI, false, DEFER>;
     static std::atomic<bool> attr_set;
     if (!attr_set.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
@@ -739,6 +845,12 @@ bl_status bl_gemm_dispatch(const uint8_t* packed, const float* beta, int layout,
     if (layout == 1 && k % G3_BK == 0) {
         if ((int64_t)((m + 127) / 128) * ((n + 127) / 128) <= 400)
             return launch_tile256_t<64, 128, 2, 1, 4>(packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
+        /* fp32 output alone: the stores of a tile travel during the workgroup's next tile (measured at
+         * M = 2048 / 8192: the 13824-wide shape 77 - 80 us against 86 - 90, 297 - 308 against 317 - 327;
+         * the 64 x 128 kernel with deferred stores loses: it has under one tile per workgroup on the
+         * shapes it serves) */
+        if (!acc && !residual && (int64_t)m * n < ((int64_t)1 << 30))
+            return launch_tile256_t<128, 128, 2, 2, 2, 0, true>(packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
         return launch_tile256_t<128, 128, 2, 2, 2>(packed, beta, q, scale, rowsum, m, n, k, residual, acc, y, st);
     }
     if (k % 128 == 0)

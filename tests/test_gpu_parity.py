@@ -472,3 +472,32 @@ def test_fused_fixed_scale(bl):
     _sync()
     unit = np.full(2, np.float32(1.0) / np.float32(127.0), dtype=np.float32)
     assert_y_close(it["y"].cpu().numpy(), oracle.rescale(c.acc, c.beta, unit))
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 13824, 2560), (2100, 4200, 640), (1024, 8320, 128), (1100, 8200, 1152)])
+def test_gemm_prefill_fp32_output_alone_defers_its_stores(bl, M, N, K):
+    """With only the fp32 output asked for, the 128x128 prefill kernel keeps a tile's results in
+    registers and stores them during the workgroup's next tile.  More tiles than resident
+    workgroups (so tiles are deferred), edges in M and N (stored at once), fewer k steps than
+    store groups (flushed behind the k loop), one k step: bit-identical to the call that also
+    returns the accumulators, and within 1e-6 of the oracle on sampled rows."""
+    rng = np.random.default_rng(M + N + K)
+    Wt = rng.integers(-1, 2, size=(N, K), dtype=np.int8)
+    q = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    scale = (rng.random(M, dtype=np.float32) + np.float32(0.5)) / np.float32(127.0)
+    beta = np.float32(0.0173)
+    rowsum = q.astype(np.int32).sum(1).astype(np.int32)
+    packed = to_dev(oracle.pack(Wt, 1))
+    b = to_dev(np.array([beta], dtype=np.float32))
+    qd, sd, rd = to_dev(q), to_dev(scale), to_dev(rowsum)
+    acc, y_both = bl.bl_gemm_w158a8(packed, b, 1, qd, sd, rd, N)
+    y_only = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    for _ in range(2):
+        y_only.fill_(float("nan"))
+        bl.bl_gemm_w158a8(packed, b, 1, qd, sd, rd, N, want_acc=False, y=y_only)
+        torch.cuda.synchronize()
+        assert torch.equal(y_only, y_both)
+    rows = np.unique(np.concatenate([np.arange(0, M, 97), [M - 1]]))
+    want_acc = oracle.matmul_i32(q[rows], Wt)
+    assert np.array_equal(acc.cpu().numpy()[rows], want_acc)
+    assert_y_close(y_only.cpu().numpy()[rows], oracle.rescale(want_acc, beta, scale[rows]))
