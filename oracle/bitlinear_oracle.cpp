@@ -22,9 +22,10 @@
  * Pins (tests/test_oracle_*.py): exhaustive 81-tuple pack table, hand-made tie
  * cases, closed-form Gaussian statistics, exact int64 library matmul, fp64
  * brute force of the dequantised product, one-hot / all-ones special cases.
- * Unpinned: the synthetic 30-layer chain glue (orc_chain_* below) is a
- * construction of this repository, not of the report: "parity unpinned"
- * against anything external; it is pinned only through its parts.
+ * The synthetic 30-layer chain glue (orc_chain_* below) is a construction of
+ * this repository, not of the report, so nothing external defines it; its
+ * functions are pinned against a library cast and hand-made probes, and the
+ * composed layer against numpy index arithmetic and an fp64 contraction.
  */
 #include <cmath>
 #include <cstdint>
@@ -205,7 +206,7 @@ void orc_rescale(const int32_t* acc, float beta, const float* scale, int64_t M, 
     }
 }
 
-/* ---- synthetic chain glue (a construction of this repository; unpinned) -----
+/* ---- synthetic chain glue (a construction of this repository) ----------------
  * One token-independent "layer" around the four BitLinear products, made only
  * of order-free, elementwise-exact steps so that integer parity survives a
  * 30-layer chain.  The report's real glue (sub-layer norm, rotary embedding,

@@ -439,6 +439,51 @@ def test_chain_layer_stays_bounded_and_is_token_independent():
     assert np.array_equal(one[0], out[2])
 
 
+def test_chain_layer_wiring_and_products_at_full_geometry():
+    """chain_layer at the 2B geometry, two tokens, checked from outside: the input of every
+    BitLinear it records must be what plain numpy index arithmetic makes of the recorded outputs
+    before it (V of KV head h // 4 for query head h, fp32 sums in the stated operand order, gate
+    and up halves), and every product, teacher-forced on the recorded input, must agree with an
+    fp64 contraction of the operands scaled afterwards, (Wt . q) * beta / 127."""
+    import torch
+
+    def bf16(a):            # round-to-nearest-even narrowing by the library cast (pinned elsewhere against the oracle's own)
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+    wts = {}
+    for name, (N, K) in synth.LAYER_SHAPES.items():
+        W = synth.latent_weights(3, N, K, layer=7, matrix=name)
+        beta = oracle.absmean_beta(W)
+        wts[name] = (oracle.ternarize(W, beta), beta)
+    x = synth.bf16_bits_to_f32(synth.activations_bf16(3, 2, 2560, layer=7))
+    tr = []
+    out = oracle.chain_layer(x, wts, trace=tr)
+    assert [t["name"] for t in tr] == ["qkv", "o", "gate_up", "down"]
+    qkv, o, gu, dn = (t["y"] for t in tr)
+    # wiring
+    assert np.array_equal(tr[0]["x_bf16"], bf16(x))
+    heads = np.arange(20)
+    v = qkv[:, 3200:].reshape(2, 5, 128)[:, heads // 4, :].reshape(2, 2560)      # [Q 20x128 | K 5x128 | V 5x128]
+    assert np.array_equal(tr[1]["x_bf16"], bf16(v))
+    h1 = x + o
+    assert np.array_equal(tr[2]["x_bf16"], bf16(h1))
+    g, u = gu[:, :6912], gu[:, 6912:]
+    r = np.maximum(g, np.float32(0.0))
+    assert np.array_equal(tr[3]["x_bf16"], bf16((r * r) * u))
+    assert np.array_equal(out.view(np.uint32), (h1 + dn).view(np.uint32))
+    # products, teacher-forced, in another formulation: fp64 over dequantised operands
+    for t in tr:
+        Wt, beta = wts[t["name"]]
+        xb = synth.bf16_bits_to_f32(t["x_bf16"]).astype(np.float64)
+        gamma = np.maximum(np.abs(xb).max(axis=1, keepdims=True), 1e-5)
+        q = np.clip(np.rint(xb * (np.float64(np.float32(127.0) / gamma.astype(np.float32)))), -127, 127)
+        assert np.array_equal(q.astype(np.int8), t["q"])
+        want = (q @ Wt.astype(np.float64).T) * (np.float64(beta) / 127.0)     # integer-valued sums are exact in fp64
+        nz = want != 0
+        assert np.all(np.abs(t["y"][nz] - want[nz]) <= 1e-6 * np.abs(want[nz]))
+        assert np.all(t["y"][~nz] == 0)
+
+
 # --------------------------------------------------------------- RMS normalisation
 def _bf16_to_f32(bits):
     return (bits.astype(np.uint32) << 16).view(np.float32)
