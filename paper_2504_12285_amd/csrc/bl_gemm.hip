@@ -420,8 +420,9 @@ __global__ __launch_bounds__(WM * WN * 64, (DEFER && BM * BN >= 128 * 128 ? 2 : 
     bl_v16i P[MI][NI];
     bool have_prev = false;
     int pm0 = 0, pn0 = 0, pset = 0, cset = 0;
-    constexpr int GROUPS = MI * 4;        /* store groups of a tile: rows 8 vq + 4 h + (0..3) of row block mi */
-    constexpr int SPG = 4 * NI;           /* store instructions of a group */
+    constexpr int RPG = 4;                      /* rows of a lane per store group (2: equal; 1: more groups than k steps at K = 2560, slower) */
+    constexpr int GROUPS = MI * 4 * (4 / RPG);  /* store groups of a tile: RPG of the rows 8 vq + 4 h + (0..3) of row block mi */
+    constexpr int SPG = RPG * NI;               /* store instructions of a group */
     /* group g of the accumulators A of the tile at (sm0, sn0) -> y; masked: the tile may cross M or N */
     auto emit_rows = [&](const bl_v16i (&A)[MI][NI], const int g, const int sm0, const int sn0, const int set,
                          const bool masked) __attribute__((always_inline)) {
@@ -451,12 +452,13 @@ __global__ __launch_bounds__(WM * WN * 64, (DEFER && BM * BN >= 128 * 128 ? 2 : 
      * store per value (32-bit byte offsets from the uniform base: the host sends outputs of 4 GiB
      * or more to the kernel without deferred stores) */
     auto emit_prev = [&](const int g) __attribute__((always_inline)) {
-        const int mi = g / 4, vq = g % 4;
+        constexpr int GPQ = 4 / RPG;                     /* groups per block of four rows */
+        const int mi = g / (4 * GPQ), vq = (g / GPQ) % 4, v0 = (g % GPQ) * RPG;
         int mlb = wm0 + mi * 32 + vq * 8 + h * 4;
         asm volatile("" : "+v"(mlb));
         const uint32_t bo = ((uint32_t)(pm0 + mlb) * (uint32_t)eN + (uint32_t)(pn0 + wn0 + l32)) * 4u;
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4)
+        for (int v4 = v0; v4 < v0 + RPG; ++v4)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
                 __builtin_nontemporal_store(__int_as_float(P[mi][ni][vq * 4 + v4]),
@@ -492,13 +494,6 @@ __global__ __launch_bounds__(WM * WN * 64, (DEFER && BM * BN >= 128 * 128 ? 2 : 
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             if (kk + STAGES - 1 < steps) issue(kk + STAGES - 1, (kk + STAGES - 1) % STAGES);
-            if constexpr (DEFER) {
-                if (have_prev && kk < GROUPS) {
-#pragma unroll
-                    for (int g = 0; g < GROUPS; ++g)
-                        if (kk == g) emit_prev(g);
-                }
-            }
             const uint8_t* st = smem + (kk % STAGES) * G3_STAGE_BYTES;
             /* operands of sub-step ks+1 are fetched while ks multiplies */
             bl_v4i wq[NI], a[2][MI];
@@ -521,6 +516,16 @@ __global__ __launch_bounds__(WM * WN * 64, (DEFER && BM * BN >= 128 * 128 ? 2 : 
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi)
                         C[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][mi], bop, C[mi][ni], 0, 0, 0);
+                }
+            }
+            /* the pending stores go out behind the step's last MFMA: the matrix core works on while
+             * the wave issues them */
+            if constexpr (DEFER) {
+                if (have_prev && kk < GROUPS) {
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int g = 0; g < GROUPS; ++g)
+                        if (kk == g) emit_prev(g);
                 }
             }
         }
@@ -572,7 +577,7 @@ __global__ __launch_bounds__(WM * WN * 64, (DEFER && BM * BN >= 128 * 128 ? 2 : 
                 have_prev = true;
             } else {
 #pragma unroll
-                for (int g = 0; g < GROUPS; ++g) emit_rows(C, g, m0, n0, cset, true);
+                for (int g = 0; g < MI * 4; ++g) emit_rows(C, g, m0, n0, cset, true);
             }
             cset ^= 1;
         } else if constexpr (EPI == 0) {
