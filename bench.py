@@ -457,6 +457,38 @@ def main():
             torch.cuda.synchronize()
             dt = e0.elapsed_time(e1) * 1e-3 / nl
             per_shape[name] = {"us": round(dt * 1e6, 2), "tops": round(2.0 * Mp * b.N * b.K / dt / 1e12, 1)}
+        # the same four launches at M = 8192 (not the headline size: what the tile kernel does once a
+        # workgroup has several tiles and its stores travel during the next tile)
+        large_m = None
+        if Mp == 2048:
+            Ml = 8192
+            ql = {K: torch.randint(-127, 128, (Ml, K), dtype=torch.int8, device=dev) for K in (2560, 6912)}
+            sl = torch.rand(Ml, device=dev) * 0.01 + 0.01
+            rl = {K: ql[K].to(torch.int32).sum(1).to(torch.int32) for K in ql}
+            yl = torch.empty((Ml, 13824), dtype=torch.float32, device=dev)
+
+            def large_layer(l):
+                s_ = torch.cuda.current_stream().cuda_stream
+                for name in SHAPE_ORDER:
+                    N, K = synth.LAYER_SHAPES[name]
+                    rc = lib.bl_gemm_w158a8(layers[l].packed[name].data_ptr(), layers[l].beta[name].data_ptr(), layout,
+                                            ql[K].data_ptr(), sl.data_ptr(), rl[K].data_ptr(), Ml, N, K, None,
+                                            yl.data_ptr(), None, s_)
+                    assert rc == 0, rc
+            for i in range(4):
+                large_layer(i % nl)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(16):
+                large_layer(i % nl)
+            e1.record()
+            torch.cuda.synchronize()
+            t_l = e0.elapsed_time(e1) * 1e-3 / 16
+            ops_l = sum(2.0 * Ml * n * k for n, k in synth.LAYER_SHAPES.values())
+            large_m = {"M": Ml, "us_per_layer": round(t_l * 1e6, 1), "tops": round(ops_l / t_l / 1e12, 1),
+                       "frac_of_int8_peak": round(ops_l / t_l / 1e12 / INT8_PEAK_TOPS, 4),
+                       "data": "uniform random int8 activations (timing only)"}
+            del ql, rl, yl
         # the clock the tile kernel actually runs at: workgroup 0 of every launch counts shader
         # clocks and ticks of the constant-rate wall clock (the chip lowers its clock under the
         # power this kernel draws, so the datasheet peak at 2.4 GHz is not what it is offered)
@@ -511,7 +543,7 @@ def main():
             % (Mp, t_pre * 1e6, tops, mfma_roof, mfma_roof_rnd, mfma_rnd_mhz, kernel_mhz, per_shape))
         out["prefill"] = {"workload": "config 3: M=%d, four layer shapes, int8 q + per-row scales -> fp32 y" % Mp,
                           "tops": round(tops, 2), "unit": "TOP/s", "us_per_layer": round(t_pre * 1e6, 2),
-                          "per_shape": per_shape,
+                          "per_shape": per_shape, "same_layer_at_large_m": large_m,
                           "roofline": {"bound": "mfma", "achieved": round(tops, 2), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
                                        "traffic": profiled_traffic("bl_gemm_tile256:layer_m2048") if Mp == 2048 else None,
