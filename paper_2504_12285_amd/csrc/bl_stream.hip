@@ -1253,7 +1253,7 @@ static bool mb_tile_route(const bl_decode_desc* descs, int count, int64_t M) {
         if (bl_kpad(descs[i].K) % 128 != 0) return false;
         tiles += (descs[i].N + 127) / 128;
     }
-    return tiles < ((int64_t)1 << 30);
+    return tiles <= ((int64_t)1 << 22);       /* beyond ~4 M tiles (a 16 MB tile list) the table stays on bl_stream_mb */
 }
 
 /* Device buffer of the tile route: [products][first tile of each product][first list position of
