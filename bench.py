@@ -489,6 +489,20 @@ def main():
                        "frac_of_int8_peak": round(ops_l / t_l / 1e12 / INT8_PEAK_TOPS, 4),
                        "data": "uniform random int8 activations (timing only)"}
             del ql, rl, yl
+        # what the memory system takes when every workgroup stores its tile at once: the epilogue's
+        # store pattern alone, on a matrix of the size of the widest output (3 workgroups per CU)
+        wr = torch.empty((Mp, 13824), dtype=torch.float32, device=dev)
+        for _ in range(2):
+            assert lib.bl_probe_stream_write(wr.data_ptr(), Mp, 13824, 3, torch.cuda.current_stream().cuda_stream) == 0
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            lib.bl_probe_stream_write(wr.data_ptr(), Mp, 13824, 3, torch.cuda.current_stream().cuda_stream)
+        e1.record()
+        torch.cuda.synchronize()
+        write_roof = Mp * 13824 * 4 / (e0.elapsed_time(e1) * 1e-3 / 10) / 1e9
+        out_bytes = sum(Mp * n * 4 for n, _ in synth.LAYER_SHAPES.values())
+        del wr
         # the clock the tile kernel actually runs at: workgroup 0 of every launch counts shader
         # clocks and ticks of the constant-rate wall clock (the chip lowers its clock under the
         # power this kernel draws, so the datasheet peak at 2.4 GHz is not what it is offered)
@@ -544,6 +558,8 @@ def main():
         out["prefill"] = {"workload": "config 3: M=%d, four layer shapes, int8 q + per-row scales -> fp32 y" % Mp,
                           "tops": round(tops, 2), "unit": "TOP/s", "us_per_layer": round(t_pre * 1e6, 2),
                           "per_shape": per_shape, "same_layer_at_large_m": large_m,
+                          "output_stores": {"bytes_per_layer": out_bytes, "store_pattern_alone_GBps": round(write_roof, 1),
+                                            "us_per_layer_at_that_rate": round(out_bytes / write_roof / 1e3, 1)},
                           "roofline": {"bound": "mfma", "achieved": round(tops, 2), "peak": INT8_PEAK_TOPS,
                                        "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
                                        "traffic": profiled_traffic("bl_gemm_tile256:layer_m2048") if Mp == 2048 else None,

@@ -380,6 +380,12 @@ bl_status bl_debug_force_path(int path);
  *                         buffer much larger than the caches to get the streaming-read rate.
  *                         workgroups_per_cu: 256-thread workgroups per compute unit, 1..8
  *                         (0 = 8, the fastest); 2 is the occupancy of the streaming decode.
+ *   bl_probe_stream_write one launch that fills a row-major fp32 matrix [rows][cols] (device, both
+ *                         multiples of 128) with the store pattern of the prefill epilogue (128 x 128
+ *                         tiles, dword stores of 32 consecutive floats per row, non-temporal) and
+ *                         does nothing else: the rate at which the outputs of a prefill launch can be
+ *                         written when every workgroup stores at once.  workgroups_per_cu 1..8
+ *                         (0 = 3, the occupancy of the tile kernel).
  *   bl_probe_mfma_i8      one launch of `iters` x 4 back-to-back v_mfma_i32_32x32x32_i8 per
  *                         wave, operands in registers; *ops (HOST, optional) receives the
  *                         integer operations of the launch (2 per multiply-accumulate).
@@ -400,6 +406,7 @@ bl_status bl_debug_force_path(int path);
  * sink: device, 64 int32, never written in practice (it keeps the work observable). */
 bl_status bl_probe_stream_read(const void* buf, size_t bytes, int workgroups_per_cu, int32_t* sink,
                                bl_stream s);
+bl_status bl_probe_stream_write(float* buf, int64_t rows, int64_t cols, int workgroups_per_cu, bl_stream s);
 bl_status bl_probe_mfma_i8(int iters, int32_t* sink, double* ops, bl_stream s);
 bl_status bl_probe_mfma_i8_ex(int iters, const void* operands, int64_t* stamps, int32_t* sink, double* ops /* HOST */,
                               bl_stream s);

@@ -40,6 +40,7 @@ SIGNATURES = {
     "bl_stack_run": (_ci, [_vp, _vp, _vp]),
     "bl_debug_force_path": (_ci, [_ci]),
     "bl_probe_stream_read": (_ci, [_vp, _sz, _ci, _vp, _vp]),
+    "bl_probe_stream_write": (_ci, [_vp, _i64, _i64, _ci, _vp]),
     "bl_probe_mfma_i8": (_ci, [_ci, _vp, _vp, _vp]),
     "bl_probe_mfma_i8_ex": (_ci, [_ci, _vp, _vp, _vp, _vp, _vp]),
     "bl_probe_wall_clock_khz": (_ci, []),

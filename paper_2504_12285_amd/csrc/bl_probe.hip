@@ -33,6 +33,29 @@ __global__ __launch_bounds__(256) void bl_probe_read_kernel(const bl_v4i* __rest
     if (r == 0x5EEDF00D) sink[threadIdx.x & 63] = r;
 }
 
+/* The write side: every lane stores fp32 values with the prefill epilogue's pattern (a wave-wide
+ * dword store = 32 consecutive floats of each of two rows of a row-major [rows][cols] matrix, 64
+ * such stores per lane and 64 x 64 tile, non-temporal), the matrix cut into one run of tiles per
+ * workgroup, and nothing else: what the memory system takes when every workgroup of a launch
+ * stores its tile at the same time. */
+__global__ __launch_bounds__(256) void bl_probe_write_kernel(float* __restrict__ buf, int rows, int cols) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int tiles_n = cols / 128, tiles = (rows / 128) * tiles_n;
+    for (int t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int m0 = (t / tiles_n) * 128 + (w >> 1) * 64, n0 = (t % tiles_n) * 128 + (w & 1) * 64;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + mi * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    __builtin_nontemporal_store((float)(m + v), buf + (int64_t)m * cols + n0 + ni * 32 + l32);
+            }
+    }
+}
+
 #ifdef BL_PROBE_EXPERIMENTS
 /* experiment: the access pattern of the decode kernel (8 lanes per 640-byte row, 8 rows per load) */
 __global__ __launch_bounds__(256) void bl_probe_read_rows(const bl_v4i* __restrict__ buf, int64_t n16,
@@ -119,6 +142,17 @@ extern "C" bl_status bl_probe_stream_read(const void* buf, size_t bytes, int wor
     const int blocks = probe_grid(workgroups_per_cu ? workgroups_per_cu : 8);
     if (blocks < 1) return BL_ERR_HIP;
     bl_probe_read_kernel<<<blocks, 256, 0, (hipStream_t)s>>>((const bl_v4i*)buf, (int64_t)(bytes / 16), sink);
+    return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+extern "C" bl_status bl_probe_stream_write(float* buf, int64_t rows, int64_t cols, int workgroups_per_cu, bl_stream s) {
+    if (!buf) return BL_ERR_NULL;
+    if (rows < 128 || cols < 128 || rows % 128 || cols % 128 || rows > (1 << 24) || cols > (1 << 24)) return BL_ERR_SHAPE;
+    if (!bl_aligned(buf, 4)) return BL_ERR_ALIGN;
+    if (workgroups_per_cu < 0 || workgroups_per_cu > 8) return BL_ERR_SHAPE;
+    const int blocks = probe_grid(workgroups_per_cu ? workgroups_per_cu : 3);
+    if (blocks < 1) return BL_ERR_HIP;
+    bl_probe_write_kernel<<<blocks, 256, 0, (hipStream_t)s>>>(buf, (int)rows, (int)cols);
     return hipGetLastError() == hipSuccess ? BL_OK : BL_ERR_HIP;
 }
 

@@ -194,3 +194,16 @@ def test_stack_tables_are_sized_and_checked_on_the_host(lib):
     assert lib.bl_stack_run(p, ctypes.byref(tile), None) == 5
     tile.tokens = 8
     assert lib.bl_stack_run(p, ctypes.byref(tile), None) == 5
+
+
+def test_probe_arguments_are_checked_on_the_host(lib):
+    """The measurement aids reject bad arguments before any GPU call."""
+    buf = (ctypes.c_char * 4096)()
+    p = (ctypes.addressof(buf) + 255) & ~255
+    assert lib.bl_probe_stream_write(None, 128, 128, 0, None) == 1
+    assert lib.bl_probe_stream_write(p, 100, 128, 0, None) == 2          # rows not a multiple of 128
+    assert lib.bl_probe_stream_write(p, 128, 64, 0, None) == 2
+    assert lib.bl_probe_stream_write(p, 128, 128, 9, None) == 2
+    assert lib.bl_probe_stream_write(p + 2, 128, 128, 0, None) == 4
+    assert lib.bl_probe_stream_read(None, 1024, 0, p, None) == 1
+    assert lib.bl_probe_stream_read(p, 24, 0, p, None) == 2
