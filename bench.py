@@ -172,6 +172,7 @@ def main():
     ap.add_argument("--no-chain", action="store_true")
     ap.add_argument("--no-batched", action="store_true")
     ap.add_argument("--prefill-m", type=int, default=2048)
+    ap.add_argument("--no-large-m", action="store_true", help="leave out the prefill layer at M = 8192 (profile runs: its launches share grids with M = 2048)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -460,7 +461,7 @@ def main():
         # the same four launches at M = 8192 (not the headline size: what the tile kernel does once a
         # workgroup has several tiles and its stores travel during the next tile)
         large_m = None
-        if Mp == 2048:
+        if Mp == 2048 and not args.no_large_m:
             Ml = 8192
             ql = {K: torch.randint(-127, 128, (Ml, K), dtype=torch.int8, device=dev) for K in (2560, 6912)}
             sl = torch.rand(Ml, device=dev) * 0.01 + 0.01
