@@ -240,8 +240,9 @@ static bl_status launch_gemm(const uint8_t* packed, const float* beta, int layou
  * a launch reaches that point together, the chip then writes at the HBM rate while its matrix cores
  * idle: measured 19 - 23 thousand clocks of stores per 128 x 128 tile against 28 - 31 thousand of k
  * loop) but kept in registers and stored a few rows per k step during the NEXT tile of the
- * workgroup, behind that step's operand loads.  Vector memory operations retire in order, so the
- * wait in front of the following step leaves exactly those stores in flight.  Interior tiles
+ * workgroup, behind that step's operand loads and behind its last MFMA (the matrix core works on
+ * while the wave issues them).  Vector memory operations retire in order, so the wait in front of
+ * the following step leaves exactly those stores in flight.  Interior tiles
  * with a following tile only; edge tiles and a workgroup's last tile store at once.  fp32 output
  * alone (no int32 output, no residual). */
 template <int BM, int BN, int STAGES, int WM, int WN, int EPI, bool TABLE = false, bool DEFER = false>
